@@ -1,0 +1,41 @@
+"""Shared test helpers: build teacher/student policies of a config with the oracle's PTQ."""
+import functools
+
+import numpy as np
+
+import oracle
+import workloads as wl
+
+
+def make_states(net, B, stream, first=0):
+    if net.obs_dtype == "u8":
+        return wl.make_frames_u8(B, *net.obs_shape, stream=stream, first=first)
+    return wl.make_obs_f32(B, net.obs_shape[0], stream=stream, first=first)
+
+
+@functools.lru_cache(maxsize=None)
+def policies(ci, calib=None):
+    """(teacher net, teacher params, student net, student fp32 params, QuantPolicy)."""
+    cfg = wl.CONFIGS[ci]
+    nt, ns = cfg["teacher"], cfg["student"]
+    pt = wl.init_params(nt, wl.STREAM["weights_teacher"])
+    if cfg["student_from"] == "quantize":
+        ps = pt
+    elif cfg["student_from"] == "independent":
+        ps = wl.init_params(ns, wl.STREAM["weights_student"])
+    else:
+        ps, _ = oracle.prune_policy(nt, pt, ns)
+    n = calib or cfg["calib"]
+    qp = oracle.quantize_policy(ns, ps, make_states(ns, n, wl.STREAM["calibration"]))
+    return nt, pt, ns, ps, qp
+
+
+def rel_err_rows(got, ref):
+    """|got-ref| / max(|ref|, row max |ref|, 1e-6), per element; ref rows are states."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    if ref.ndim == 1:
+        den = np.maximum(np.abs(ref).max(), 1e-6)
+    else:
+        den = np.maximum(np.abs(ref).max(axis=1, keepdims=True), 1e-6)
+    return np.abs(got - ref) / den
