@@ -1,0 +1,186 @@
+/*
+ * accerl.h -- C ABI of the MI355X actor-forward library.
+ *
+ * The one operation behind this boundary is the Actor's policy inference of the AcceRL paper
+ * (Section 1: the agent maps each environment state s to an action a, and this step is the
+ * bottleneck of data collection; Section 2.1: the Actors run the *compressed* policy; Section
+ * 2.2, Eq. 1: the network yields an action distribution pi(.|s) and a value v(s)).  The
+ * compressed ("student") policy is the post-training-quantized int8 network of Section 2.2
+ * "Parameter Quantization" with the Conv+ReLU / FC+ReLU fusion described there, optionally of a
+ * pruned or distilled shape (Section 2.2 "Structured Pruning", "Knowledge Distillation"); the
+ * original ("teacher") policy in fp32 or bf16 sits alongside because the Corrector (Section 2.3,
+ * Eq. 2: rho_t = min(rho, pi_original / pi_smaller)) and the Monitor (Section 2.4, Eq. 5) need
+ * both distributions on the same states.  The behaviour logits are an output for the same reason.
+ *
+ * General rules
+ *  - Every function returns an accerl_status (0 = OK, negative = error); nothing throws or
+ *    aborts across this boundary.  accerl_last_error() gives a thread-local message.
+ *  - "HOST" pointers are read during the call and never kept.  "DEVICE" pointers are HIP device
+ *    memory owned by the caller, 16-byte aligned, valid until the work enqueued on `stream`
+ *    has finished.  The library owns only its device copy of the weights and a per-policy
+ *    workspace that it grows (hipMalloc, synchronising) when a call needs more than any
+ *    earlier call did.
+ *  - Forward calls only enqueue work on `stream` (a hipStream_t; NULL = the default stream) and
+ *    return without synchronising; the status reports argument and launch errors only.
+ *    B == 0 is valid and enqueues nothing.  One policy must not be used by two streams at once
+ *    (the workspace is shared).
+ *  - All tensors are dense and row-major in the logical order written below.
+ */
+#ifndef ACCERL_H
+#define ACCERL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct accerl_policy accerl_policy; /* opaque, library-owned */
+
+typedef enum {
+    ACCERL_OK = 0,
+    ACCERL_EINVAL = -1,       /* NULL / mis-shaped / misaligned argument, inconsistent arch */
+    ACCERL_ENOMEM = -2,       /* host or device allocation failed */
+    ACCERL_EHIP = -3,         /* a HIP runtime call or kernel launch failed */
+    ACCERL_EUNSUPPORTED = -4  /* valid request outside what the kernels cover */
+} accerl_status;
+
+typedef enum { ACCERL_OBS_U8 = 0, ACCERL_OBS_F32 = 1 } accerl_obs_dtype;
+
+typedef enum {
+    ACCERL_INT8 = 0, /* student: int8 weights and activations, int32 accumulation        */
+    ACCERL_FP32 = 1, /* teacher: fp32 throughout                                           */
+    ACCERL_BF16 = 2  /* teacher: bf16 operands and stored activations, fp32 accumulation  */
+} accerl_precision;
+
+typedef enum {
+    ACCERL_CONV = 1,     /* cin cout k stride pad relu : square kernel, zero padding        */
+    ACCERL_DENSE = 2,    /* cin cout relu                                                   */
+    ACCERL_MAXPOOL = 3,  /* k stride pad : taps outside the image are ignored               */
+    ACCERL_RESBLOCK = 4, /* cin == cout == channels : x + convB(relu(convA(relu(x)))), 3x3 pad 1 */
+    ACCERL_RELU = 5,
+    ACCERL_FLATTEN = 6,  /* C,H,W order                                                     */
+    ACCERL_LSTM = 7      /* cin = input width, cout = hidden units; gate order i,f,g,o      */
+} accerl_layer_kind;
+
+typedef struct {
+    int32_t kind;   /* accerl_layer_kind */
+    int32_t cin, cout;
+    int32_t k, stride, pad;
+    int32_t relu;   /* conv / dense: ReLU fused after the layer */
+    int32_t reserved;
+} accerl_layer;
+
+#define ACCERL_MAX_LAYERS 48
+
+/* A network: observation, layer list, then two implicit heads on the last layer's flat output:
+ * A = n_actions logits and one value (Section 2.2, Eq. 1: pi and v). */
+typedef struct {
+    int32_t obs_dtype;             /* accerl_obs_dtype */
+    int32_t obs_c, obs_h, obs_w;   /* image observation [C,H,W]; vector observation: obs_c = D, obs_h = obs_w = 1 */
+    int32_t n_actions;             /* 1 .. 64 */
+    int32_t precision;             /* accerl_precision */
+    int32_t n_layers;
+    accerl_layer layers[ACCERL_MAX_LAYERS];
+} accerl_arch;
+
+/*
+ * Sizes of the two host blobs accerl_policy_create expects for `arch` (so a caller can check its
+ * packing).  Return ACCERL_EINVAL for an inconsistent arch.
+ *
+ * Weight blob: the parametrised tensors in layer order -- conv: W[cout,cin,k,k], b[cout];
+ * dense: W[cout,cin], b[cout]; resblock: convA W,b then convB W,b; lstm: W_ih[4H,cin], b[4H],
+ * W_hh[4H,H]; finally the heads W[A+1, F], b[A+1] (row A is the value head).  Each tensor
+ * starts at the next multiple of 16 bytes.  Biases are always fp32.  W is int8 (already
+ * quantized, values in -127..127) for every tensor of an ACCERL_INT8 policy except the LSTM
+ * matrices and the heads of a network that contains an LSTM, which are fp32; W is fp32 for
+ * teacher policies (an ACCERL_BF16 policy rounds it to bf16, ties to even, on upload).
+ *
+ * Scale array (ACCERL_INT8 only; n_scales = 0 for teachers): first the activation scales --
+ * s_0 of the observation (uint8 observations: must be 1/255, the bytes enter as integers
+ * 0..255), then in layer order one scale per quantized activation: conv and dense: their
+ * output; resblock: the output of conv A, then the stream after the add -- followed by the
+ * per-output-channel weight scales s_w of every int8 tensor in blob order.
+ */
+int accerl_blob_sizes(const accerl_arch* arch, int64_t* weights_bytes, int64_t* n_scales);
+
+/*
+ * Build a policy: validates `arch`, copies and re-lays the weights for the kernels, derives the
+ * integer biases and fp32 requantization multipliers, uploads everything and fixes the launch
+ * plan (the library's form of the static computational graph of Section 2.2).
+ *
+ * Derived constants (double arithmetic, then one rounding):
+ *   biasq[n] = (int32) rint(b[n] / (s_in * s_w[n]))
+ *   m[n]     = (float)((s_in * s_w[n]) / s_out)         requantization multiplier
+ *   r        = (float)(s_x / s_out)                     residual-stream ratio
+ *   d[n]     = (float)(s_in * s_w[n])                   head dequantization
+ *   inv_s0   = (float)(1 / s_0)                         fp32 observation quantizer
+ *
+ * weights, quant_scales: HOST, copied.  quant_scales may be NULL iff n_scales == 0.
+ * *out receives the policy; destroy it with accerl_policy_destroy.  Uses the current HIP device.
+ */
+int accerl_policy_create(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
+                         const float* quant_scales, int64_t n_scales, accerl_policy** out);
+
+void accerl_policy_destroy(accerl_policy* p);
+
+/*
+ * Student forward (Section 1 / 2.1: the Actor's inference on the compressed policy; arithmetic:
+ * Section 2.2 "Parameter Quantization").  The policy must be ACCERL_INT8 and contain no LSTM.
+ *
+ *   states     DEVICE [B, C, H, W] uint8 or [B, D] fp32, as the arch says
+ *   uniforms   DEVICE [B] fp32 in [0, 1): one draw per state for the sampler
+ *   out_logits DEVICE [B, A] fp32 behaviour logits
+ *   out_value  DEVICE [B] fp32
+ *   out_action DEVICE [B] int32: with m = max_a logit, e_a = exp(logit_a - m), Z = sum_a e_a
+ *              (index order), the first a with e_0 + .. + e_a > u * Z, else A - 1
+ *
+ * Per layer: acc = sum Wq * xq + biasq (exact int32); y = (float)acc * m[n];
+ * q = clamp(rint(y), relu ? 0 : -127, 127); residual join y = fma((float)acc, m[n], (float)xq * r);
+ * heads logit = (float)acc * d[n].
+ */
+int accerl_actor_forward(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
+                         float* out_logits, float* out_value, int32_t* out_action, void* stream);
+
+/* Teacher forward: same arguments and outputs; the policy must be ACCERL_FP32 or ACCERL_BF16 and
+ * contain no LSTM (Section 3.1: the original network runs in fp32; Section 2.2: fp16-class
+ * storage is the paper's other low-bit option).  uint8 observations enter as obs / 255. */
+int accerl_actor_forward_teacher(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
+                                 float* out_logits, float* out_value, int32_t* out_action, void* stream);
+
+/*
+ * One environment step of a recurrent policy (the arch ends in an ACCERL_LSTM layer), any
+ * precision.  done: DEVICE [B] uint8; rows with done != 0 have h and c zeroed before the cell.
+ * h, c: DEVICE [B, H] fp32, updated in place.  The LSTM and the heads behind it use bf16 GEMM
+ * operands (fp32 for an ACCERL_FP32 policy) with fp32 accumulation and fp32 gate arithmetic:
+ * c' = sig(f) * c + sig(i) * tanh(g), h' = sig(o) * tanh(c').
+ */
+int accerl_actor_forward_recurrent(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
+                                   const uint8_t* done, float* h, float* c,
+                                   float* out_logits, float* out_value, int32_t* out_action, void* stream);
+
+typedef enum {
+    ACCERL_TAP_ACC = 0,   /* int32 accumulator of a conv / dense layer (resblock: of conv B); layer = n_layers: of the heads */
+    ACCERL_TAP_ACT = 1,   /* stored output of the layer: int8 (student), fp32 (teachers, converted) */
+    ACCERL_TAP_ACC_A = 2, /* resblock: accumulator of conv A */
+    ACCERL_TAP_ACT_A = 3  /* resblock: output of conv A */
+} accerl_tap;
+
+/*
+ * Debug forward for parity tests: runs the same kernels as the forward calls up to and
+ * including layer `layer` and copies one intermediate tensor to `out` (DEVICE, `out_bytes`
+ * must equal the tensor's size).  Image tensors are written channels-last, [B, H, W, C];
+ * flat tensors [B, N].  Accumulator taps are student-only and include the integer bias and are
+ * zero-point free (uint8 observations count as 0..255).  Recurrent policies: layers before the
+ * LSTM only.  Synchronises the stream before returning.
+ */
+int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, int32_t layer, int32_t tap,
+                               void* out, int64_t out_bytes, void* stream);
+
+/* Message of the last error on this thread ("" if none). */
+const char* accerl_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACCERL_H */

@@ -1,6 +1,8 @@
 """The actor forward pass as a walk over a layer list, one oracle layer call per step.
 
-forward_float : the teacher (fp32, or bf16 GEMM operands with fp32 everything else).
+forward_float : the teacher: fp32, or bf16 (GEMM operands and every stored layer output --
+                conv, FC, residual sum -- rounded to bfloat16; accumulation, bias, ReLU, pooling
+                and the LSTM gate arithmetic in fp32; h, c and the head outputs stay fp32).
 forward_int8  : the post-training-quantized student (paper Section 2.2, "Parameter
                 Quantization": int8 parameters, Conv/FC+ReLU fused; arithmetic as stated in
                 oracle.c).
@@ -45,10 +47,12 @@ def forward_float(net, params, states, uniforms=None, precision="fp32", h=None, 
         if kd == "conv":
             _, w, b = next(it)
             x = L.conv2d_f(x, w, b, ly["stride"], ly["pad"], ly["relu"], bf)
+            x = L.bf16_round(x) if bf else x
             obs((i, "out"), x)
         elif kd == "dense":
             _, w, b = next(it)
             x = L.dense_f(x, w, b, ly["relu"], bf)
+            x = L.bf16_round(x) if bf else x
             obs((i, "out"), x)
         elif kd == "maxpool":
             x = L.maxpool_f(x, ly["k"], ly["stride"], ly["pad"])
@@ -57,9 +61,11 @@ def forward_float(net, params, states, uniforms=None, precision="fp32", h=None, 
             _, wb, bb = next(it)
             a = np.maximum(x, np.float32(0))
             a = L.conv2d_f(a, wa, ba, 1, 1, True, bf)
+            a = L.bf16_round(a) if bf else a
             obs((i, "mid"), a)
             t = L.conv2d_f(a, wb, bb, 1, 1, False, bf)
-            x = x + t                                              # fp32 add
+            x = x + t                                              # fp32 add of the unrounded branch
+            x = L.bf16_round(x) if bf else x
             obs((i, "out"), x)
         elif kd == "relu":
             x = np.maximum(x, np.float32(0))
