@@ -169,8 +169,8 @@ typedef enum {
 /*
  * Debug forward for parity tests: runs the same kernels as the forward calls up to and
  * including layer `layer` and copies one intermediate tensor to `out` (DEVICE, `out_bytes`
- * must equal the tensor's size).  Image tensors are written channels-last, [B, H, W, C];
- * flat tensors [B, N].  Accumulator taps are student-only and include the integer bias and are
+ * must equal the tensor's size).  Image tensors are written channels-last, [B, H, W, Cs] with
+ * Cs = C rounded up to a multiple of 4 (padding channels are zero); flat tensors [B, N].  Accumulator taps are student-only and include the integer bias and are
  * zero-point free (uint8 observations count as 0..255).  Recurrent policies: layers before the
  * LSTM only.  Synchronises the stream before returning.
  */

@@ -1,0 +1,127 @@
+// Internal declarations shared by the C-ABI translation unit and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "accerl.h"
+
+namespace accerl {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+enum Elem : int { EL_I8 = 0, EL_BF16 = 1, EL_F32 = 2 };
+
+// ---------------------------------------------------------------- fused int8 MLP (wave per 16 rows)
+constexpr int MLP_MAX_LAYERS = 4;   // hidden layers; the heads come on top
+struct MlpParams {
+    const float* obs;        // [B, D] fp32
+    const float* uniforms;   // [B]
+    float* logits;           // [B, A]
+    float* value;            // [B]
+    int32_t* action;         // [B]
+    int64_t B;
+    int D;                   // observation width (<= 64)
+    int A;                   // actions
+    int n_hidden;            // hidden layers, each padded to 64 units
+    float inv_s0;
+    const v4i* wfrag;        // A-operand fragments, layer after layer: [layer][n_tile][64 lanes]
+    const int32_t* bias;     // [layer][64] integer bias (heads last)
+    const float* mult;       // [layer][64] requant multiplier (heads: dequant d)
+    int lo[MLP_MAX_LAYERS];  // lower clamp per hidden layer (0 = fused ReLU, -127 otherwise)
+    // debug taps (NULL = off): accumulator / activation of layer tap_layer, [B, n] row-major
+    int32_t* tap_acc;
+    int8_t* tap_act;
+    int tap_layer;           // -1 = quantized observation (tap_act only)
+    int tap_n;               // logical width of the tapped tensor
+};
+hipError_t launch_mlp_i8(const MlpParams& p, hipStream_t s);
+
+// ---------------------------------------------------------------- observation quantizer (generic path)
+hipError_t launch_quant_obs(const float* obs, int64_t B, int D, int Dpad, float inv_s0, int8_t* out, hipStream_t s);
+
+// ---------------------------------------------------------------- convolution (NHWC tile in LDS, MFMA)
+struct ConvParams {
+    const void* in;          // NHWC elements, or NCHW uint8 observations (src_nchw_u8)
+    void* out;               // NHWC elements [B, Ho, Wo, Cs_out]
+    const void* res;         // residual stream, same shape as out (NULL = none)
+    int32_t* tap_acc;        // int32 [B, Ho, Wo, Cs_out] (NULL = off)
+    const void* wfrag;       // [k_steps][NT][64 lanes][16 B]
+    const void* bias;        // int32 (int8 path, zero-point correction folded in) or fp32, [NT*16]
+    const float* mult;       // [NT*16] (int8 path)
+    const uint16_t* lut;     // 256 bf16 values obs/255 (bf16 path with uint8 source)
+    int64_t B;
+    int H, W;                // input image
+    int Cin_real;            // channels present in the source
+    int Cs_in;               // stored channels per input pixel (multiple of 4)
+    int Ho, Wo, Cs_out;
+    int k, s, pad;
+    int TH;                  // output rows per band
+    int n_bands;
+    int in_rows;             // (TH-1)*s + k
+    int pitch;               // bytes per LDS input row
+    int tile_bytes;          // LDS bytes of the input tile including read slack
+    int cpr;                 // 16-byte chunks per kernel row
+    int k_steps;             // MFMA steps (4 chunks each)
+    int w_bytes;             // bytes of wfrag
+    int relu_in;             // max(x, 0) on load
+    int relu;                // teacher: ReLU after bias; student: lower clamp 0
+    int src_nchw_u8;
+    float r;                 // residual ratio (int8 path)
+    int imgs_per_block;      // images one workgroup walks through
+};
+hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int align, hipStream_t s);
+
+// ---------------------------------------------------------------- max pooling on NHWC
+hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,
+                          int k, int s, int pad, Elem el, hipStream_t stream);
+
+// ---------------------------------------------------------------- dense layers (MFMA GEMM)
+enum GemmEpi : int { EPI_REQUANT = 0, EPI_HEADS_I8 = 1, EPI_BF16 = 2, EPI_HEADS_F32ACC = 3, EPI_LSTM = 4 };
+struct GemmParams {
+    const void* x;           // [B, Kp] elements (Kp = padded K, multiple of 16 bytes)
+    const void* wfrag;       // [n_tiles][k_steps][64 lanes][16 B]
+    const void* bias;        // int32 or fp32, [n_tiles*16]
+    const float* mult;       // [n_tiles*16]
+    void* out;               // EPI_REQUANT: int8 [B, Np]; EPI_BF16: bf16 [B, Np]
+    int32_t* tap_acc;        // int32 [B, N] (NULL = off)
+    float* logits;           // heads
+    float* value;
+    // LSTM epilogue
+    float* h;                // [B, Hd] in/out
+    float* c;
+    int64_t B;
+    int Kp_bytes;            // row pitch of x in bytes
+    int k_steps;
+    int N;                   // logical outputs
+    int Np;                  // stored outputs per row (out pitch in elements)
+    int n_tiles;
+    int relu_in;
+    int relu;
+    int A;                   // heads: actions
+    int Hd;                  // lstm hidden
+};
+hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s);
+
+// fp32 dense layer (teacher MLP): out = relu?(x W^T + b); heads variant writes logits/value
+struct GemmF32Params {
+    const float* x; const float* w; const float* bias; float* out; float* logits; float* value;
+    int64_t B; int K; int N; int ldx; int ldo; int relu; int heads; int A;
+};
+hipError_t launch_gemm_f32(const GemmF32Params& p, hipStream_t s);
+
+// LSTM operand packing: xh[b] = [bf16(x[b]) , bf16(done ? 0 : h[b])], and h,c zeroed where done
+struct LstmPackParams {
+    const void* x; int x_elem; float x_scale; int x_pitch_bytes; int x_relu; int In;
+    const uint8_t* done; float* h; float* c; uint16_t* xh; int Hd; int64_t B;
+};
+hipError_t launch_lstm_pack(const LstmPackParams& p, hipStream_t s);
+
+// ---------------------------------------------------------------- sampler
+hipError_t launch_sample(const float* logits, const float* uniforms, int32_t* action, int64_t B, int A, hipStream_t s);
+
+// ---------------------------------------------------------------- debug conversions
+hipError_t launch_bf16_to_f32(const uint16_t* in, float* out, int64_t n, hipStream_t s);
+
+}  // namespace accerl

@@ -1,0 +1,1008 @@
+// C-ABI entry points, the host-side plan builder (arch -> fixed list of kernel launches) and the
+// weight re-layout into MFMA fragment order.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "accerl_internal.h"
+
+using namespace accerl;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(ACCERL_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+inline int64_t up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+inline int out_hw(int h, int k, int s, int p) { return (h + 2 * p - k) / s + 1; }
+
+uint16_t host_bf16(float x) {
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)(u >> 16);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ------------------------------------------------------------------ blob layout
+enum WType { W_I8, W_F32 };
+struct TensorSpec {
+    int layer;        // arch layer index; n_layers = heads
+    int sub;          // 0: conv/dense/convA/lstm_ih, 1: convB / lstm_hh
+    int64_t rows, cols;   // W is [rows, cols]
+    bool has_bias;
+    WType wt;
+    int64_t w_off, b_off; // byte offsets in the weight blob
+    int64_t sw_off;       // index of its per-channel scales in the scale array (-1: none)
+};
+
+struct Shape { int c, h, w; bool flat; int n; };
+
+struct Parsed {
+    std::vector<TensorSpec> tensors;
+    std::vector<Shape> shapes;   // after each layer
+    int64_t weights_bytes = 0, n_scales = 0, n_act_scales = 0;
+    bool has_lstm = false;
+    int feat = 0;
+};
+
+int parse_arch(const accerl_arch* a, Parsed& P) {
+    if (!a) return fail(ACCERL_EINVAL, "arch is NULL");
+    if (a->n_layers < 0 || a->n_layers > ACCERL_MAX_LAYERS) return fail(ACCERL_EINVAL, "n_layers out of range");
+    if (a->n_actions < 1 || a->n_actions > 63) return fail(ACCERL_EINVAL, "n_actions must be 1..63");
+    if (a->precision < ACCERL_INT8 || a->precision > ACCERL_BF16) return fail(ACCERL_EINVAL, "bad precision");
+    if (a->obs_dtype != ACCERL_OBS_U8 && a->obs_dtype != ACCERL_OBS_F32) return fail(ACCERL_EINVAL, "bad obs_dtype");
+    if (a->obs_c < 1 || a->obs_h < 1 || a->obs_w < 1) return fail(ACCERL_EINVAL, "bad observation shape");
+    const bool q = a->precision == ACCERL_INT8;
+    Shape s;
+    if (a->obs_h == 1 && a->obs_w == 1) s = Shape{0, 0, 0, true, a->obs_c};
+    else s = Shape{a->obs_c, a->obs_h, a->obs_w, false, 0};
+    for (int i = 0; i < a->n_layers; ++i) if (a->layers[i].kind == ACCERL_LSTM) P.has_lstm = true;
+    int64_t off = 0;
+    int64_t n_act = 1, n_sw = 0;
+    auto add = [&](int layer, int sub, int64_t rows, int64_t cols, bool bias, WType wt) {
+        TensorSpec t{layer, sub, rows, cols, bias, wt, 0, -1, -1};
+        off = up(off, 16);
+        t.w_off = off;
+        off += rows * cols * (wt == W_I8 ? 1 : 4);
+        if (bias) { off = up(off, 16); t.b_off = off; off += rows * 4; }
+        if (wt == W_I8) { t.sw_off = n_sw; n_sw += rows; }
+        P.tensors.push_back(t);
+    };
+    for (int i = 0; i < a->n_layers; ++i) {
+        const accerl_layer& L = a->layers[i];
+        switch (L.kind) {
+            case ACCERL_CONV:
+                if (s.flat) return fail(ACCERL_EINVAL, "layer %d: conv on a flat tensor", i);
+                if (L.cin != s.c || L.cout < 1 || L.k < 1 || L.stride < 1 || L.pad < 0 || L.pad >= L.k)
+                    return fail(ACCERL_EINVAL, "layer %d: inconsistent conv", i);
+                if (s.h + 2 * L.pad < L.k || s.w + 2 * L.pad < L.k) return fail(ACCERL_EINVAL, "layer %d: kernel larger than input", i);
+                add(i, 0, L.cout, (int64_t)L.cin * L.k * L.k, true, q ? W_I8 : W_F32);
+                s = Shape{L.cout, out_hw(s.h, L.k, L.stride, L.pad), out_hw(s.w, L.k, L.stride, L.pad), false, 0};
+                n_act += 1;
+                break;
+            case ACCERL_DENSE:
+                if (!s.flat || L.cin != s.n || L.cout < 1) return fail(ACCERL_EINVAL, "layer %d: inconsistent dense", i);
+                add(i, 0, L.cout, L.cin, true, q ? W_I8 : W_F32);
+                s = Shape{0, 0, 0, true, L.cout};
+                n_act += 1;
+                break;
+            case ACCERL_MAXPOOL:
+                if (s.flat || L.k < 1 || L.stride < 1 || L.pad < 0 || 2 * L.pad > L.k || s.h + 2 * L.pad < L.k || s.w + 2 * L.pad < L.k)
+                    return fail(ACCERL_EINVAL, "layer %d: inconsistent maxpool", i);
+                s = Shape{s.c, out_hw(s.h, L.k, L.stride, L.pad), out_hw(s.w, L.k, L.stride, L.pad), false, 0};
+                break;
+            case ACCERL_RESBLOCK:
+                if (s.flat || L.cin != s.c || L.cout != s.c) return fail(ACCERL_EINVAL, "layer %d: inconsistent resblock", i);
+                add(i, 0, s.c, (int64_t)s.c * 9, true, q ? W_I8 : W_F32);
+                add(i, 1, s.c, (int64_t)s.c * 9, true, q ? W_I8 : W_F32);
+                n_act += 2;
+                break;
+            case ACCERL_RELU:
+                break;
+            case ACCERL_FLATTEN:
+                if (!s.flat) s = Shape{0, 0, 0, true, s.c * s.h * s.w};
+                break;
+            case ACCERL_LSTM:
+                if (!s.flat || L.cin != s.n || L.cout < 1) return fail(ACCERL_EINVAL, "layer %d: inconsistent lstm", i);
+                if (i != a->n_layers - 1) return fail(ACCERL_EUNSUPPORTED, "layer %d: the lstm must be the last layer", i);
+                add(i, 0, 4 * (int64_t)L.cout, L.cin, true, W_F32);
+                add(i, 1, 4 * (int64_t)L.cout, L.cout, false, W_F32);
+                s = Shape{0, 0, 0, true, L.cout};
+                break;
+            default:
+                return fail(ACCERL_EINVAL, "layer %d: unknown kind %d", i, L.kind);
+        }
+        P.shapes.push_back(s);
+    }
+    if (!s.flat) return fail(ACCERL_EINVAL, "the heads need a flat feature vector (add a flatten layer)");
+    P.feat = s.n;
+    add(a->n_layers, 0, a->n_actions + 1, s.n, true, (q && !P.has_lstm) ? W_I8 : W_F32);
+    P.weights_bytes = off;
+    P.n_act_scales = q ? n_act : 0;
+    P.n_scales = q ? n_act + n_sw : 0;
+    return ACCERL_OK;
+}
+
+// ------------------------------------------------------------------ plan
+enum StepKind { ST_MLP, ST_QUANT_OBS, ST_CONV, ST_GEMM, ST_GEMM_F32, ST_MAXPOOL, ST_LSTM_PACK, ST_SAMPLE };
+
+struct Step {
+    StepKind kind;
+    int layer = -1, sub = 0;
+    int in_buf = -1, out_buf = -1, res_buf = -1;   // -1 = the caller's states (in) / none
+    ConvParams cp{};
+    Elem el = EL_I8;
+    int NT = 1, align = 16;
+    GemmParams gp{};
+    GemmEpi epi = EPI_REQUANT;
+    GemmF32Params fp{};
+    LstmPackParams lp{};
+    MlpParams mp{};
+    // maxpool
+    int H = 0, W = 0, Cs = 0, Ho = 0, Wo = 0, k = 0, s = 0, pad = 0;
+    float inv_s0 = 0.f;
+    int D = 0, Dpad = 0;
+    // offsets into the device constant block
+    int64_t o_w = -1, o_bias = -1, o_mult = -1, o_lut = -1;
+    // what the step's output is, for taps
+    int64_t out_elems = 0;      // stored elements per state
+    int64_t acc_elems = 0;      // int32 accumulator elements per state (0 = none)
+};
+
+struct Buf { int64_t per_state; int64_t off; };
+
+}  // namespace
+
+struct accerl_policy {
+    accerl_arch arch;
+    Parsed P;
+    int device = 0;
+    std::vector<Step> steps;
+    std::vector<Buf> bufs;
+    int64_t ws_per_state = 0;
+    char* consts = nullptr;
+    char* ws = nullptr;
+    int64_t ws_states = 0;
+    int64_t chunk = 0;
+    int64_t obs_bytes = 0;
+    bool recurrent = false;
+    int lstm_hidden = 0;
+};
+
+namespace {
+
+struct Builder {
+    const accerl_arch* a;
+    const Parsed& P;
+    const char* wblob;
+    const float* scales;
+    accerl_policy* pol;
+    std::vector<char> cst;      // host image of the device constant block
+
+    int64_t put(const void* src, int64_t bytes) {
+        const int64_t o = up((int64_t)cst.size(), 256);
+        cst.resize(o + bytes);
+        if (src) memcpy(cst.data() + o, src, bytes);
+        else memset(cst.data() + o, 0, bytes);
+        return o;
+    }
+    int new_buf(int64_t per_state) {
+        pol->bufs.push_back(Buf{up(per_state, 16), 0});
+        return (int)pol->bufs.size() - 1;
+    }
+    const TensorSpec& tensor(int layer, int sub) const {
+        for (const auto& t : P.tensors) if (t.layer == layer && t.sub == sub) return t;
+        return P.tensors.back();
+    }
+    const int8_t* wq(const TensorSpec& t) const { return (const int8_t*)(wblob + t.w_off); }
+    const float* wf(const TensorSpec& t) const { return (const float*)(wblob + t.w_off); }
+    const float* bias(const TensorSpec& t) const { return (const float*)(wblob + t.b_off); }
+    const float* sw(const TensorSpec& t) const { return scales + P.n_act_scales + t.sw_off; }
+
+    static int32_t biasq(float b, float s_in, float s_w) {
+        return (int32_t)std::rint((double)b / ((double)s_in * (double)s_w));
+    }
+    static float mult(float s_in, float s_w, float s_out) {
+        return (float)(((double)s_in * (double)s_w) / (double)s_out);
+    }
+};
+
+// One convolution (a conv layer or half of a resblock) -> a conv step.
+int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool src_u8,
+              int Cin, int H, int W, int Cout, int k, int s, int pad, bool relu, bool relu_in,
+              int in_buf, int out_buf, int res_buf, float s_in, float s_out, float s_res) {
+    Step st;
+    st.kind = ST_CONV;
+    st.layer = layer;
+    st.sub = sub;
+    st.in_buf = in_buf;
+    st.out_buf = out_buf;
+    st.res_buf = res_buf;
+    st.el = el;
+    const int esz = el == EL_I8 ? 1 : 2;
+    const int Cs_in = (int)up(Cin, 4), Cs_out = (int)up(Cout, 4);
+    if (src_u8 && Cin > 4) return fail(ACCERL_EUNSUPPORTED, "uint8 observations with more than 4 channels");
+    if (src_u8 && (W & 3)) return fail(ACCERL_EUNSUPPORTED, "uint8 observation width must be a multiple of 4");
+    const int NT = (Cout <= 16) ? 1 : (Cout <= 32) ? 2 : (Cout <= 64) ? 4 : 0;
+    if (!NT) return fail(ACCERL_EUNSUPPORTED, "layer %d: more than 64 output channels", layer);
+    const int pix = Cs_in * esz;
+    const int run = k * pix;                        // bytes of one kernel row of one pixel
+    const int cpr = (run + 15) / 16;
+    const int chunks = k * cpr;
+    const int k_steps = (chunks + 3) / 4;
+    const int Ho = out_hw(H, k, s, pad), Wo = out_hw(W, k, s, pad);
+    const int pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16);
+    const int w_bytes = k_steps * NT * 1024;
+    // band height: the largest that keeps weights + patch within the LDS budget
+    const int lds_cap = 160 * 1024 - 1024;
+    int budget = 72 * 1024;
+    if (w_bytes + 40 * 1024 > budget) budget = w_bytes + 40 * 1024;
+    if (budget > lds_cap) budget = lds_cap;
+    int TH = Ho;
+    auto tile_bytes = [&](int th) { return ((th - 1) * s + k) * pitch + 32; };
+    while (TH > 1 && w_bytes + k_steps * 16 + tile_bytes(TH) > budget) --TH;
+    if (w_bytes + k_steps * 16 + tile_bytes(TH) > lds_cap)
+        return fail(ACCERL_EUNSUPPORTED, "layer %d: weights and one input band exceed LDS", layer);
+    const int n_bands = (Ho + TH - 1) / TH;
+    TH = (Ho + n_bands - 1) / n_bands;              // even out the bands
+
+    ConvParams& c = st.cp;
+    c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_out;
+    c.k = k; c.s = s; c.pad = pad; c.TH = TH; c.n_bands = (Ho + TH - 1) / TH;
+    c.in_rows = (TH - 1) * s + k; c.pitch = pitch; c.tile_bytes = tile_bytes(TH);
+    c.cpr = cpr; c.k_steps = k_steps; c.w_bytes = w_bytes;
+    c.relu_in = relu_in; c.relu = relu; c.src_nchw_u8 = src_u8;
+    st.NT = NT;
+    int al = 16;
+    while ((s * pix) % al) al >>= 1;
+    st.align = al < 4 ? 4 : al;
+    st.out_elems = (int64_t)Ho * Wo * Cs_out;
+    st.acc_elems = el == EL_I8 ? st.out_elems : 0;
+
+    // ---- weight fragments: [k_step][n_tile][lane][16 bytes]
+    std::vector<char> frag((size_t)w_bytes, 0);
+    const int epc = 16 / esz;                       // elements per chunk
+    std::vector<int64_t> wsum(NT * 16, 0);
+    for (int stp = 0; stp < k_steps; ++stp)
+        for (int tt = 0; tt < NT; ++tt)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int n = 16 * tt + (lane & 15), g = lane >> 4;
+                const int q = 4 * stp + g;
+                const int ky = q / cpr, cx = q - ky * cpr;
+                char* dst = frag.data() + ((size_t)(stp * NT + tt) * 64 + lane) * 16;
+                for (int e = 0; e < epc; ++e) {
+                    const int idx = cx * epc + e;   // element index inside the kernel row run
+                    const int kx = idx / Cs_in, ci = idx - kx * Cs_in;
+                    if (ky >= k || kx >= k || ci >= Cin || n >= Cout) continue;
+                    const int64_t src = (((int64_t)n * Cin + ci) * k + ky) * k + kx;
+                    if (el == EL_I8) {
+                        const int8_t v = B.wq(t)[src];
+                        dst[e] = (char)v;
+                        wsum[n] += v;
+                    } else {
+                        const uint16_t v = host_bf16(B.wf(t)[src]);
+                        memcpy(dst + 2 * e, &v, 2);
+                    }
+                }
+            }
+    st.o_w = B.put(frag.data(), w_bytes);
+    if (el == EL_I8) {
+        std::vector<int32_t> bq(NT * 16, 0);
+        std::vector<float> ml(NT * 16, 0.f);
+        for (int n = 0; n < Cout; ++n) {
+            int64_t b = Builder::biasq(B.bias(t)[n], s_in, B.sw(t)[n]);
+            if (src_u8) b += 128 * wsum[n];          // observations are staged as obs - 128
+            bq[n] = (int32_t)b;
+            ml[n] = Builder::mult(s_in, B.sw(t)[n], s_out);
+        }
+        st.o_bias = B.put(bq.data(), bq.size() * 4);
+        st.o_mult = B.put(ml.data(), ml.size() * 4);
+        c.r = res_buf >= 0 ? (float)((double)s_res / (double)s_out) : 0.f;
+    } else {
+        std::vector<float> bf(NT * 16, 0.f);
+        for (int n = 0; n < Cout; ++n) bf[n] = B.bias(t)[n];
+        st.o_bias = B.put(bf.data(), bf.size() * 4);
+        if (src_u8) {
+            std::vector<uint16_t> lut(256);
+            for (int v = 0; v < 256; ++v) lut[v] = host_bf16((float)v / 255.0f);
+            st.o_lut = B.put(lut.data(), 512);
+        }
+    }
+    B.pol->steps.push_back(st);
+    return ACCERL_OK;
+}
+
+// Fragments of a dense weight matrix: [n_tile][k_step][lane][16 bytes].  perm maps a stored input
+// position to the logical input index (-1 = padding); rowmap maps a stored output row to the logical
+// row (-1 = padding); get(n, k) returns the logical weight.
+template <typename Get>
+std::vector<char> gemm_frags(Elem el, int n_tiles, int k_steps, const std::vector<int>& perm,
+                             const std::vector<int>& rowmap, Get get) {
+    const int esz = el == EL_I8 ? 1 : 2, epc = 16 / esz;
+    std::vector<char> frag((size_t)n_tiles * k_steps * 1024, 0);
+    for (int nt = 0; nt < n_tiles; ++nt)
+        for (int st = 0; st < k_steps; ++st)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int nrow = 16 * nt + (lane & 15), g = lane >> 4;
+                if (nrow >= (int)rowmap.size() || rowmap[nrow] < 0) continue;
+                char* dst = frag.data() + ((size_t)(nt * k_steps + st) * 64 + lane) * 16;
+                for (int e = 0; e < epc; ++e) {
+                    const int pos = st * 4 * epc + g * epc + e;
+                    if (pos >= (int)perm.size() || perm[pos] < 0) continue;
+                    const double v = get(rowmap[nrow], perm[pos]);
+                    if (el == EL_I8) dst[e] = (char)(int8_t)v;
+                    else { const uint16_t h = host_bf16((float)v); memcpy(dst + 2 * e, &h, 2); }
+                }
+            }
+    return frag;
+}
+
+struct Cursor {            // the tensor the next layer reads
+    Shape shape;
+    int buf = -1;          // -1 = the caller's states
+    Elem el = EL_I8;
+    float scale = 1.f;     // int8 activations
+    bool relu_pending = false;
+    std::vector<int> perm; // flat tensors: stored position -> logical index
+    int stored = 0;        // stored elements per state (flat tensors)
+};
+
+int build_plan(Builder& B) {
+    const accerl_arch* a = B.a;
+    const Parsed& P = B.P;
+    accerl_policy* pol = B.pol;
+    const bool q = a->precision == ACCERL_INT8;
+    const bool image = !(a->obs_h == 1 && a->obs_w == 1);
+    pol->recurrent = P.has_lstm;
+    pol->obs_bytes = (int64_t)a->obs_c * a->obs_h * a->obs_w * (a->obs_dtype == ACCERL_OBS_U8 ? 1 : 4);
+    const float* act = B.scales;
+    int ai = 0;
+    if (q) {
+        for (int64_t i = 0; i < P.n_scales; ++i)
+            if (!(B.scales[i] > 0.f) || !std::isfinite(B.scales[i])) return fail(ACCERL_EINVAL, "quant_scales[%lld] is not a positive finite number", (long long)i);
+        if (a->obs_dtype == ACCERL_OBS_U8 && act[0] != (float)(1.0 / 255.0))
+            return fail(ACCERL_EINVAL, "uint8 observations need s_0 = 1/255");
+    }
+    if (image && a->obs_dtype != ACCERL_OBS_U8) return fail(ACCERL_EUNSUPPORTED, "image observations must be uint8");
+    if (!image && a->obs_dtype != ACCERL_OBS_F32) return fail(ACCERL_EUNSUPPORTED, "vector observations must be fp32");
+    if (image && a->precision == ACCERL_FP32) return fail(ACCERL_EUNSUPPORTED, "image networks run as int8 or bf16");
+    if (!image && a->precision == ACCERL_BF16) return fail(ACCERL_EUNSUPPORTED, "vector-observation teachers run in fp32");
+
+    // ---------------- fused int8 MLP: every layer dense, at most 64 wide
+    if (q && !image && !P.has_lstm) {
+        bool ok = a->n_layers >= 1 && a->n_layers <= MLP_MAX_LAYERS && a->obs_c <= 64;
+        for (int i = 0; i < a->n_layers; ++i) ok = ok && a->layers[i].kind == ACCERL_DENSE && a->layers[i].cout <= 64;
+        if (ok) {
+            Step st;
+            st.kind = ST_MLP;
+            st.layer = 0;
+            MlpParams& m = st.mp;
+            m.D = a->obs_c; m.A = a->n_actions; m.n_hidden = a->n_layers;
+            m.inv_s0 = (float)(1.0 / (double)act[0]);
+            const int nl = a->n_layers + 1;
+            std::vector<char> frag((size_t)nl * 4 * 1024, 0);
+            std::vector<int32_t> bq((size_t)nl * 64, 0);
+            std::vector<float> ml((size_t)nl * 64, 0.f);
+            float s_in = act[0];
+            int Kprev = a->obs_c;
+            for (int l = 0; l < nl; ++l) {
+                const TensorSpec& t = B.tensor(l < a->n_layers ? l : a->n_layers, 0);
+                const int N = (int)t.rows, K = (int)t.cols;
+                const float s_out = l < a->n_layers ? act[1 + l] : 0.f;
+                for (int tt = 0; tt < 4; ++tt)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int n = 16 * tt + (lane & 15), g = lane >> 4;
+                        if (n >= N) continue;
+                        char* dst = frag.data() + ((size_t)(l * 4 + tt) * 64 + lane) * 16;
+                        for (int e = 0; e < 16; ++e) {
+                            // layer 0 reads features in natural order; later layers read the accumulator
+                            // layout of the layer before: slot 4*t' + r of lane group g is unit 16t' + 4g + r
+                            const int k = (l == 0) ? 16 * g + e : 16 * (e >> 2) + 4 * g + (e & 3);
+                            if (k < K) dst[e] = (char)B.wq(t)[(int64_t)n * K + k];
+                        }
+                    }
+                for (int n = 0; n < N; ++n) {
+                    bq[l * 64 + n] = Builder::biasq(B.bias(t)[n], s_in, B.sw(t)[n]);
+                    ml[l * 64 + n] = l < a->n_layers ? Builder::mult(s_in, B.sw(t)[n], s_out)
+                                                      : (float)((double)s_in * (double)B.sw(t)[n]);
+                }
+                if (l < a->n_layers) { m.lo[l] = a->layers[l].relu ? 0 : -127; s_in = s_out; }
+                (void)Kprev; Kprev = N;
+            }
+            st.o_w = B.put(frag.data(), frag.size());
+            st.o_bias = B.put(bq.data(), bq.size() * 4);
+            st.o_mult = B.put(ml.data(), ml.size() * 4);
+            pol->steps.push_back(st);
+            return ACCERL_OK;
+        }
+    }
+
+    // ---------------- fp32 teacher on vector observations: chain of fp32 dense layers
+    if (a->precision == ACCERL_FP32) {
+        int cur = -1, K = a->obs_c;
+        for (int i = 0; i <= a->n_layers; ++i) {
+            const bool heads = i == a->n_layers;
+            if (!heads && a->layers[i].kind != ACCERL_DENSE) return fail(ACCERL_EUNSUPPORTED, "fp32 teachers are dense-only");
+            const TensorSpec& t = B.tensor(i, 0);
+            Step st;
+            st.kind = ST_GEMM_F32;
+            st.layer = i;
+            st.in_buf = cur;
+            GemmF32Params& f = st.fp;
+            f.K = K; f.N = (int)t.rows; f.ldx = K; f.relu = heads ? 0 : a->layers[i].relu; f.heads = heads; f.A = a->n_actions;
+            st.o_w = B.put(B.wf(t), t.rows * t.cols * 4);
+            st.o_bias = B.put(B.bias(t), t.rows * 4);
+            if (!heads) {
+                st.out_buf = B.new_buf(t.rows * 4);
+                f.ldo = (int)t.rows;
+                st.out_elems = t.rows;
+                cur = st.out_buf;
+                K = (int)t.rows;
+            }
+            pol->steps.push_back(st);
+        }
+        Step ss; ss.kind = ST_SAMPLE; ss.layer = a->n_layers;
+        pol->steps.push_back(ss);
+        return ACCERL_OK;
+    }
+
+    // ---------------- general path: int8 student or bf16 teacher, layer by layer
+    const Elem el = q ? EL_I8 : EL_BF16;
+    const int esz = q ? 1 : 2;
+    Cursor cur;
+    cur.shape = image ? Shape{a->obs_c, a->obs_h, a->obs_w, false, 0} : Shape{0, 0, 0, true, a->obs_c};
+    cur.el = el;
+    if (q) cur.scale = act[ai++];
+    for (int i = 0; i < a->n_layers; ++i) {
+        const accerl_layer& L = a->layers[i];
+        switch (L.kind) {
+            case ACCERL_CONV: {
+                const Shape o = P.shapes[i];
+                const int ob = B.new_buf((int64_t)o.h * o.w * up(o.c, 4) * esz);
+                const float s_out = q ? act[ai++] : 0.f;
+                int rc = plan_conv(B, i, 0, B.tensor(i, 0), el, cur.buf < 0, cur.shape.c, cur.shape.h, cur.shape.w,
+                                   L.cout, L.k, L.stride, L.pad, L.relu != 0, cur.relu_pending, cur.buf, ob, -1,
+                                   cur.scale, s_out, 0.f);
+                if (rc) return rc;
+                cur.shape = o; cur.buf = ob; cur.scale = s_out; cur.relu_pending = false;
+                break;
+            }
+            case ACCERL_MAXPOOL: {
+                if (cur.buf < 0) return fail(ACCERL_EUNSUPPORTED, "layer %d: pooling directly on the observation", i);
+                if (cur.relu_pending) return fail(ACCERL_EUNSUPPORTED, "layer %d: relu directly before maxpool", i);
+                const Shape o = P.shapes[i];
+                Step st;
+                st.kind = ST_MAXPOOL; st.layer = i; st.el = el;
+                st.in_buf = cur.buf;
+                st.H = cur.shape.h; st.W = cur.shape.w; st.Cs = (int)up(cur.shape.c, 4); st.Ho = o.h; st.Wo = o.w;
+                st.k = L.k; st.s = L.stride; st.pad = L.pad;
+                st.out_buf = B.new_buf((int64_t)o.h * o.w * st.Cs * esz);
+                st.out_elems = (int64_t)o.h * o.w * st.Cs;
+                pol->steps.push_back(st);
+                cur.shape = o; cur.buf = st.out_buf;
+                break;
+            }
+            case ACCERL_RESBLOCK: {
+                if (cur.buf < 0 || cur.relu_pending) return fail(ACCERL_EUNSUPPORTED, "layer %d: resblock needs a stored, un-rectified stream", i);
+                const Shape sh = cur.shape;
+                const int64_t bytes = (int64_t)sh.h * sh.w * up(sh.c, 4) * esz;
+                const int mid = B.new_buf(bytes), ob = B.new_buf(bytes);
+                const float s1 = q ? act[ai++] : 0.f, s_out = q ? act[ai++] : 0.f;
+                int rc = plan_conv(B, i, 0, B.tensor(i, 0), el, false, sh.c, sh.h, sh.w, sh.c, 3, 1, 1, true, true,
+                                   cur.buf, mid, -1, cur.scale, s1, 0.f);
+                if (rc) return rc;
+                rc = plan_conv(B, i, 1, B.tensor(i, 1), el, false, sh.c, sh.h, sh.w, sh.c, 3, 1, 1, false, false,
+                               mid, ob, cur.buf, s1, s_out, cur.scale);
+                if (rc) return rc;
+                cur.buf = ob; cur.scale = s_out;
+                break;
+            }
+            case ACCERL_RELU:
+                cur.relu_pending = true;
+                break;
+            case ACCERL_FLATTEN: {
+                if (cur.shape.flat) break;
+                if (cur.buf < 0) return fail(ACCERL_EUNSUPPORTED, "flatten directly on the observation");
+                const Shape sh = cur.shape;
+                const int Cs = (int)up(sh.c, 4);
+                cur.stored = sh.h * sh.w * Cs;
+                cur.perm.assign(cur.stored, -1);
+                for (int y = 0; y < sh.h; ++y)
+                    for (int x = 0; x < sh.w; ++x)
+                        for (int c = 0; c < sh.c; ++c) cur.perm[(y * sh.w + x) * Cs + c] = (c * sh.h + y) * sh.w + x;
+                cur.shape = P.shapes[i];
+                break;
+            }
+            case ACCERL_DENSE: {
+                if (cur.buf < 0) {   // vector observation on the general path: quantize to padded int8 rows
+                    if (!q) return fail(ACCERL_EUNSUPPORTED, "bf16 teacher on vector observations");
+                    Step st;
+                    st.kind = ST_QUANT_OBS; st.layer = -1;
+                    st.D = a->obs_c; st.Dpad = (int)up(a->obs_c, 16);
+                    st.inv_s0 = (float)(1.0 / (double)cur.scale);
+                    st.out_buf = B.new_buf(st.Dpad);
+                    st.out_elems = st.Dpad;
+                    pol->steps.push_back(st);
+                    cur.buf = st.out_buf; cur.stored = st.Dpad;
+                    cur.perm.assign(st.Dpad, -1);
+                    for (int k = 0; k < a->obs_c; ++k) cur.perm[k] = k;
+                }
+                const TensorSpec& t = B.tensor(i, 0);
+                const int N = L.cout, Np = (int)up(N, 16 / esz), n_tiles = (N + 15) / 16;
+                const int epm = 64 / esz, k_steps = (cur.stored + epm - 1) / epm;
+                std::vector<int> rowmap(n_tiles * 16, -1);
+                for (int n = 0; n < N; ++n) rowmap[n] = n;
+                const int K = (int)t.cols;
+                Step st;
+                st.kind = ST_GEMM; st.layer = i; st.el = el;
+                st.in_buf = cur.buf;
+                st.out_buf = B.new_buf((int64_t)Np * esz);
+                GemmParams& gp = st.gp;
+                gp.Kp_bytes = cur.stored * esz; gp.k_steps = k_steps; gp.N = N; gp.Np = Np; gp.n_tiles = n_tiles;
+                gp.relu_in = cur.relu_pending; gp.relu = L.relu;
+                st.out_elems = Np;
+                if (q) {
+                    st.epi = EPI_REQUANT;
+                    st.acc_elems = N;
+                    const float s_out = act[ai++];
+                    auto frag = gemm_frags(el, n_tiles, k_steps, cur.perm, rowmap, [&](int n, int k) { return (double)B.wq(t)[(int64_t)n * K + k]; });
+                    st.o_w = B.put(frag.data(), frag.size());
+                    std::vector<int32_t> bq(n_tiles * 16, 0);
+                    std::vector<float> ml(n_tiles * 16, 0.f);
+                    for (int n = 0; n < N; ++n) {
+                        bq[n] = Builder::biasq(B.bias(t)[n], cur.scale, B.sw(t)[n]);
+                        ml[n] = Builder::mult(cur.scale, B.sw(t)[n], s_out);
+                    }
+                    st.o_bias = B.put(bq.data(), bq.size() * 4);
+                    st.o_mult = B.put(ml.data(), ml.size() * 4);
+                    cur.scale = s_out;
+                } else {
+                    st.epi = EPI_BF16;
+                    auto frag = gemm_frags(el, n_tiles, k_steps, cur.perm, rowmap, [&](int n, int k) { return (double)B.wf(t)[(int64_t)n * K + k]; });
+                    st.o_w = B.put(frag.data(), frag.size());
+                    std::vector<float> bf(n_tiles * 16, 0.f);
+                    for (int n = 0; n < N; ++n) bf[n] = B.bias(t)[n];
+                    st.o_bias = B.put(bf.data(), bf.size() * 4);
+                }
+                pol->steps.push_back(st);
+                cur.buf = st.out_buf; cur.shape = P.shapes[i]; cur.relu_pending = false;
+                cur.stored = Np;
+                cur.perm.assign(Np, -1);
+                for (int n = 0; n < N; ++n) cur.perm[n] = n;
+                break;
+            }
+            case ACCERL_LSTM: {
+                if (cur.buf < 0) return fail(ACCERL_EUNSUPPORTED, "lstm directly on the observation");
+                const int In = L.cin, Hd = L.cout;
+                if (Hd % 4) return fail(ACCERL_EUNSUPPORTED, "lstm hidden size must be a multiple of 4");
+                for (int k = 0; k < In; ++k) if (cur.perm[k] != k) return fail(ACCERL_EUNSUPPORTED, "lstm input must be a plain vector");
+                pol->lstm_hidden = Hd;
+                const int Kx = In + Hd;
+                Step pk;
+                pk.kind = ST_LSTM_PACK; pk.layer = i; pk.sub = 0;
+                pk.in_buf = cur.buf;
+                pk.out_buf = B.new_buf((int64_t)Kx * 2);
+                LstmPackParams& lp = pk.lp;
+                lp.x_elem = cur.el; lp.x_scale = cur.scale; lp.x_pitch_bytes = cur.stored * esz; lp.x_relu = cur.relu_pending;
+                lp.In = In; lp.Hd = Hd;
+                pk.out_elems = Kx;
+                pol->steps.push_back(pk);
+                const TensorSpec& tih = B.tensor(i, 0);
+                const TensorSpec& thh = B.tensor(i, 1);
+                const int N = 4 * Hd, n_tiles = N / 16, k_steps = (Kx + 31) / 32;
+                std::vector<int> perm(Kx), rowmap(N);
+                for (int k = 0; k < Kx; ++k) perm[k] = k;
+                for (int u = 0; u < Hd; ++u) for (int gt = 0; gt < 4; ++gt) rowmap[4 * u + gt] = gt * Hd + u;
+                auto frag = gemm_frags(EL_BF16, n_tiles, k_steps, perm, rowmap, [&](int n, int k) {
+                    return (double)(k < In ? B.wf(tih)[(int64_t)n * In + k] : B.wf(thh)[(int64_t)n * Hd + (k - In)]);
+                });
+                Step st;
+                st.kind = ST_GEMM; st.layer = i; st.sub = 1; st.el = EL_BF16; st.epi = EPI_LSTM;
+                st.in_buf = pk.out_buf;
+                st.out_buf = B.new_buf((int64_t)Hd * 2);
+                st.o_w = B.put(frag.data(), frag.size());
+                std::vector<float> bf(N);
+                for (int n = 0; n < N; ++n) bf[n] = B.bias(tih)[rowmap[n]];
+                st.o_bias = B.put(bf.data(), bf.size() * 4);
+                GemmParams& gp = st.gp;
+                gp.Kp_bytes = Kx * 2; gp.k_steps = k_steps; gp.N = N; gp.Np = Hd; gp.n_tiles = n_tiles; gp.Hd = Hd;
+                st.out_elems = Hd;
+                pol->steps.push_back(st);
+                cur.buf = st.out_buf; cur.el = EL_BF16; cur.shape = P.shapes[i]; cur.relu_pending = false;
+                cur.stored = Hd;
+                cur.perm.resize(Hd);
+                for (int k = 0; k < Hd; ++k) cur.perm[k] = k;
+                break;
+            }
+        }
+    }
+    // ---------------- heads + sampler
+    {
+        if (cur.buf < 0) return fail(ACCERL_EUNSUPPORTED, "a network needs at least one layer before the heads");
+        const TensorSpec& t = B.tensor(a->n_layers, 0);
+        const int A = a->n_actions, N = A + 1, n_tiles = (N + 15) / 16, K = (int)t.cols;
+        const Elem hel = cur.el;
+        const int hesz = hel == EL_I8 ? 1 : 2, epm = 64 / hesz, k_steps = (cur.stored + epm - 1) / epm;
+        std::vector<int> rowmap(n_tiles * 16, -1);
+        for (int n = 0; n < N; ++n) rowmap[n] = n;
+        Step st;
+        st.kind = ST_GEMM; st.layer = a->n_layers; st.el = hel;
+        st.in_buf = cur.buf;
+        GemmParams& gp = st.gp;
+        gp.Kp_bytes = cur.stored * hesz; gp.k_steps = k_steps; gp.N = N; gp.Np = N; gp.n_tiles = n_tiles; gp.A = A;
+        gp.relu_in = cur.relu_pending;
+        if (hel == EL_I8) {
+            st.epi = EPI_HEADS_I8;
+            st.acc_elems = N;
+            auto frag = gemm_frags(hel, n_tiles, k_steps, cur.perm, rowmap, [&](int n, int k) { return (double)B.wq(t)[(int64_t)n * K + k]; });
+            st.o_w = B.put(frag.data(), frag.size());
+            std::vector<int32_t> bq(n_tiles * 16, 0);
+            std::vector<float> ml(n_tiles * 16, 0.f);
+            for (int n = 0; n < N; ++n) {
+                bq[n] = Builder::biasq(B.bias(t)[n], cur.scale, B.sw(t)[n]);
+                ml[n] = (float)((double)cur.scale * (double)B.sw(t)[n]);
+            }
+            st.o_bias = B.put(bq.data(), bq.size() * 4);
+            st.o_mult = B.put(ml.data(), ml.size() * 4);
+        } else {
+            st.epi = EPI_HEADS_F32ACC;
+            auto frag = gemm_frags(hel, n_tiles, k_steps, cur.perm, rowmap, [&](int n, int k) { return (double)B.wf(t)[(int64_t)n * K + k]; });
+            st.o_w = B.put(frag.data(), frag.size());
+            std::vector<float> bf(n_tiles * 16, 0.f);
+            for (int n = 0; n < N; ++n) bf[n] = B.bias(t)[n];
+            st.o_bias = B.put(bf.data(), bf.size() * 4);
+        }
+        pol->steps.push_back(st);
+        Step ss; ss.kind = ST_SAMPLE; ss.layer = a->n_layers;
+        pol->steps.push_back(ss);
+    }
+    return ACCERL_OK;
+}
+
+int ensure_workspace(accerl_policy* p, int64_t n, hipStream_t stream) {
+    if (p->bufs.empty() || n <= p->ws_states) return ACCERL_OK;
+    if (p->ws) {
+        HIP_TRY(hipStreamSynchronize(stream));
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipFree(p->ws));
+        p->ws = nullptr;
+        p->ws_states = 0;
+    }
+    int64_t off = 0;
+    for (auto& b : p->bufs) { b.off = off; off += up(b.per_state * n + 256, 256); }
+    hipError_t e = hipMalloc((void**)&p->ws, (size_t)off);
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ACCERL_ENOMEM, "workspace of %lld bytes: %s", (long long)off, hipGetErrorString(e)); }
+    HIP_TRY(hipMemset(p->ws, 0, (size_t)off));
+    p->ws_states = n;
+    return ACCERL_OK;
+}
+
+struct Call {
+    const void* states; int64_t B; const float* uniforms; const uint8_t* done; float* h; float* c;
+    float* logits; float* value; int32_t* action; hipStream_t stream;
+    // debug
+    bool debug = false; int layer = 0, tap = 0; void* out = nullptr; int64_t out_bytes = 0;
+};
+
+int find_tap_step(const accerl_policy* p, int layer, int tap, bool& is_acc) {
+    const bool resblock = layer >= 0 && layer < p->arch.n_layers && p->arch.layers[layer].kind == ACCERL_RESBLOCK;
+    is_acc = (tap == ACCERL_TAP_ACC || tap == ACCERL_TAP_ACC_A);
+    if ((tap == ACCERL_TAP_ACC_A || tap == ACCERL_TAP_ACT_A) && !resblock) return -1;
+    const int want_sub = resblock ? ((tap == ACCERL_TAP_ACC_A || tap == ACCERL_TAP_ACT_A) ? 0 : 1) : -1;
+    int found = -1;
+    for (int i = 0; i < (int)p->steps.size(); ++i) {
+        const Step& s = p->steps[i];
+        if (s.kind == ST_SAMPLE || s.layer != layer) continue;
+        if (want_sub >= 0 && s.sub != want_sub) continue;
+        if (is_acc && s.acc_elems == 0) continue;
+        if (!is_acc && s.out_buf < 0) continue;
+        found = i;
+    }
+    return found;
+}
+
+int run(accerl_policy* p, const Call& c) {
+    if (c.B == 0) return ACCERL_OK;
+    const accerl_arch& a = p->arch;
+    const int A = a.n_actions;
+    int last_step = (int)p->steps.size() - 1;
+    bool tap_acc = false;
+    int64_t tap_elems = 0, tap_esz = 0;
+    const bool fused = p->steps.size() == 1 && p->steps[0].kind == ST_MLP;
+    if (c.debug) {
+        if (fused) {
+            const int nl = a.n_layers;
+            tap_acc = c.tap == ACCERL_TAP_ACC;
+            if (c.tap != ACCERL_TAP_ACC && c.tap != ACCERL_TAP_ACT) return fail(ACCERL_EINVAL, "tap kind not available for this layer");
+            if (c.layer < -1 || c.layer > nl || (c.layer == -1 && tap_acc) || (c.layer == nl && !tap_acc))
+                return fail(ACCERL_EINVAL, "no such tap");
+            tap_elems = c.layer == -1 ? a.obs_c : c.layer == nl ? A + 1 : a.layers[c.layer].cout;
+            tap_esz = tap_acc ? 4 : 1;
+        } else {
+            last_step = find_tap_step(p, c.layer, c.tap, tap_acc);
+            if (last_step < 0) return fail(ACCERL_EINVAL, "layer %d has no such tap", c.layer);
+            const Step& s = p->steps[last_step];
+            tap_elems = tap_acc ? s.acc_elems : s.out_elems;
+            if (!tap_acc && s.kind == ST_GEMM) {
+                if (s.epi != EPI_REQUANT) return fail(ACCERL_EINVAL, "layer %d: activation tap not available", c.layer);
+                tap_elems = s.gp.N;
+            }
+            tap_esz = tap_acc ? 4 : (a.precision == ACCERL_INT8 && s.el == EL_I8 && s.kind != ST_LSTM_PACK) ? 1 : 4;
+        }
+        if (c.out_bytes != c.B * tap_elems * tap_esz)
+            return fail(ACCERL_EINVAL, "tap needs %lld bytes, got %lld", (long long)(c.B * tap_elems * tap_esz), (long long)c.out_bytes);
+    }
+    int64_t chunk = p->chunk > 0 ? p->chunk : c.B;
+    if (chunk > c.B) chunk = c.B;
+    int rc = ensure_workspace(p, chunk, c.stream);
+    if (rc) return rc;
+    for (int64_t c0 = 0; c0 < c.B; c0 += chunk) {
+        const int64_t n = (c.B - c0 < chunk) ? (c.B - c0) : chunk;
+        const char* states = (const char*)c.states + c0 * p->obs_bytes;
+        float* logits = c.logits ? c.logits + c0 * A : nullptr;
+        float* value = c.value ? c.value + c0 : nullptr;
+        int32_t* action = c.action ? c.action + c0 : nullptr;
+        const float* uni = c.uniforms ? c.uniforms + c0 : nullptr;
+        char* tap_out = c.debug ? (char*)c.out + c0 * tap_elems * tap_esz : nullptr;
+        auto bufp = [&](int b) -> char* { return b < 0 ? const_cast<char*>(states) : p->ws + p->bufs[b].off; };
+        for (int si = 0; si <= last_step; ++si) {
+            const Step& s = p->steps[si];
+            const bool tap_here = c.debug && !fused && si == last_step;
+            hipError_t e = hipSuccess;
+            switch (s.kind) {
+                case ST_MLP: {
+                    MlpParams m = s.mp;
+                    m.obs = (const float*)states; m.uniforms = uni; m.logits = logits; m.value = value; m.action = action;
+                    m.B = n;
+                    m.wfrag = (const v4i*)(p->consts + s.o_w);
+                    m.bias = (const int32_t*)(p->consts + s.o_bias);
+                    m.mult = (const float*)(p->consts + s.o_mult);
+                    m.tap_layer = -2; m.tap_acc = nullptr; m.tap_act = nullptr; m.tap_n = 0;
+                    if (c.debug) {
+                        m.tap_layer = c.layer; m.tap_n = (int)tap_elems;
+                        if (tap_acc) m.tap_acc = (int32_t*)tap_out; else m.tap_act = (int8_t*)tap_out;
+                    }
+                    e = launch_mlp_i8(m, c.stream);
+                    break;
+                }
+                case ST_QUANT_OBS:
+                    e = launch_quant_obs((const float*)states, n, s.D, s.Dpad, s.inv_s0, (int8_t*)bufp(s.out_buf), c.stream);
+                    break;
+                case ST_CONV: {
+                    ConvParams cp = s.cp;
+                    cp.in = bufp(s.in_buf); cp.out = bufp(s.out_buf);
+                    cp.res = s.res_buf >= 0 ? bufp(s.res_buf) : nullptr;
+                    cp.tap_acc = (tap_here && tap_acc) ? (int32_t*)tap_out : nullptr;
+                    cp.wfrag = p->consts + s.o_w;
+                    cp.bias = p->consts + s.o_bias;
+                    cp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
+                    cp.lut = s.o_lut >= 0 ? (const uint16_t*)(p->consts + s.o_lut) : nullptr;
+                    cp.B = n;
+                    int64_t groups = 2048 / cp.n_bands;
+                    if (groups < 1) groups = 1;
+                    if (groups > n) groups = n;
+                    cp.imgs_per_block = (int)((n + groups - 1) / groups);
+                    e = launch_conv(cp, s.el, s.NT, s.align, c.stream);
+                    break;
+                }
+                case ST_MAXPOOL:
+                    e = launch_maxpool(bufp(s.in_buf), bufp(s.out_buf), n, s.H, s.W, s.Cs, s.Ho, s.Wo, s.k, s.s, s.pad, s.el, c.stream);
+                    break;
+                case ST_GEMM: {
+                    GemmParams gp = s.gp;
+                    gp.x = bufp(s.in_buf);
+                    gp.out = s.out_buf >= 0 ? bufp(s.out_buf) : nullptr;
+                    gp.wfrag = p->consts + s.o_w;
+                    gp.bias = p->consts + s.o_bias;
+                    gp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
+                    gp.tap_acc = (tap_here && tap_acc) ? (int32_t*)tap_out : nullptr;
+                    gp.logits = logits; gp.value = value;
+                    gp.h = c.h ? c.h + c0 * p->lstm_hidden : nullptr;
+                    gp.c = c.c ? c.c + c0 * p->lstm_hidden : nullptr;
+                    gp.B = n;
+                    e = launch_gemm(gp, s.el, s.epi, c.stream);
+                    break;
+                }
+                case ST_GEMM_F32: {
+                    GemmF32Params f = s.fp;
+                    f.x = (const float*)bufp(s.in_buf);
+                    f.w = (const float*)(p->consts + s.o_w);
+                    f.bias = (const float*)(p->consts + s.o_bias);
+                    f.out = s.out_buf >= 0 ? (float*)bufp(s.out_buf) : nullptr;
+                    f.logits = logits; f.value = value; f.B = n;
+                    e = launch_gemm_f32(f, c.stream);
+                    break;
+                }
+                case ST_LSTM_PACK: {
+                    LstmPackParams lp = s.lp;
+                    lp.x = bufp(s.in_buf);
+                    lp.done = c.done ? c.done + c0 : nullptr;
+                    lp.h = c.h + c0 * p->lstm_hidden; lp.c = c.c + c0 * p->lstm_hidden;
+                    lp.xh = (uint16_t*)bufp(s.out_buf);
+                    lp.B = n;
+                    e = launch_lstm_pack(lp, c.stream);
+                    break;
+                }
+                case ST_SAMPLE:
+                    e = launch_sample(logits, uni, action, n, A, c.stream);
+                    break;
+            }
+            if (e != hipSuccess) return fail(ACCERL_EHIP, "step %d (kind %d, layer %d): %s", si, (int)s.kind, s.layer, hipGetErrorString(e));
+            if (tap_here && !tap_acc) {
+                const char* src = bufp(s.out_buf);
+                if (s.kind == ST_GEMM) {
+                    HIP_TRY(hipMemcpy2DAsync(tap_out, (size_t)s.gp.N, src, (size_t)s.gp.Np, (size_t)s.gp.N, (size_t)n,
+                                             hipMemcpyDeviceToDevice, c.stream));
+                } else if (tap_esz == 1 || s.kind == ST_GEMM_F32) {
+                    HIP_TRY(hipMemcpyAsync(tap_out, src, (size_t)(n * tap_elems * tap_esz), hipMemcpyDeviceToDevice, c.stream));
+                } else {
+                    HIP_TRY(launch_bf16_to_f32((const uint16_t*)src, (float*)tap_out, n * tap_elems, c.stream));
+                }
+            }
+        }
+    }
+    if (c.debug) HIP_TRY(hipStreamSynchronize(c.stream));
+    return ACCERL_OK;
+}
+
+int check_common(accerl_policy* p, const void* states, int64_t B, bool need_outputs, const float* uniforms,
+                 float* logits, float* value, int32_t* action) {
+    if (!p) return fail(ACCERL_EINVAL, "policy is NULL");
+    if (B < 0) return fail(ACCERL_EINVAL, "B is negative");
+    if (B == 0) return ACCERL_OK;
+    if (!states) return fail(ACCERL_EINVAL, "states is NULL");
+    if ((uintptr_t)states & 15) return fail(ACCERL_EINVAL, "states is not 16-byte aligned");
+    if (need_outputs) {
+        if (!uniforms || !logits || !value || !action) return fail(ACCERL_EINVAL, "an output or uniforms pointer is NULL");
+        if (((uintptr_t)uniforms | (uintptr_t)logits | (uintptr_t)value | (uintptr_t)action) & 15)
+            return fail(ACCERL_EINVAL, "a device pointer is not 16-byte aligned");
+    }
+    return ACCERL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int accerl_blob_sizes(const accerl_arch* arch, int64_t* weights_bytes, int64_t* n_scales) {
+    Parsed P;
+    int rc = parse_arch(arch, P);
+    if (rc) return rc;
+    if (weights_bytes) *weights_bytes = P.weights_bytes;
+    if (n_scales) *n_scales = P.n_scales;
+    return ACCERL_OK;
+}
+
+int accerl_policy_create(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
+                         const float* quant_scales, int64_t n_scales, accerl_policy** out) {
+    if (!out) return fail(ACCERL_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!weights) return fail(ACCERL_EINVAL, "weights is NULL");
+    accerl_policy* pol = new (std::nothrow) accerl_policy();
+    if (!pol) return fail(ACCERL_ENOMEM, "host allocation failed");
+    int rc = parse_arch(arch, pol->P);
+    if (rc) { delete pol; return rc; }
+    pol->arch = *arch;
+    if (weights_bytes != pol->P.weights_bytes) {
+        rc = fail(ACCERL_EINVAL, "weight blob is %lld bytes, arch needs %lld", (long long)weights_bytes, (long long)pol->P.weights_bytes);
+        delete pol; return rc;
+    }
+    if (n_scales != pol->P.n_scales || (n_scales > 0 && !quant_scales)) {
+        rc = fail(ACCERL_EINVAL, "scale array has %lld entries, arch needs %lld", (long long)n_scales, (long long)pol->P.n_scales);
+        delete pol; return rc;
+    }
+    if (arch->precision == ACCERL_INT8) {
+        for (const auto& t : pol->P.tensors) {
+            if (t.wt != W_I8) continue;
+            const int8_t* w = (const int8_t*)((const char*)weights + t.w_off);
+            for (int64_t i = 0; i < t.rows * t.cols; ++i)
+                if (w[i] == -128) { rc = fail(ACCERL_EINVAL, "int8 weight -128 is outside the symmetric range"); delete pol; return rc; }
+        }
+    }
+    Builder B{arch, pol->P, (const char*)weights, quant_scales, pol, {}};
+    rc = build_plan(B);
+    if (rc) { delete pol; return rc; }
+    hipError_t e = hipGetDevice(&pol->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&pol->consts, B.cst.size() + 256);
+    if (e == hipSuccess) e = hipMemcpy(pol->consts, B.cst.data(), B.cst.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        rc = fail(e == hipErrorOutOfMemory ? ACCERL_ENOMEM : ACCERL_EHIP, "uploading constants: %s", hipGetErrorString(e));
+        (void)hipGetLastError();
+        if (pol->consts) (void)hipFree(pol->consts);
+        delete pol;
+        return rc;
+    }
+    pol->ws_per_state = 0;
+    for (const auto& b : pol->bufs) pol->ws_per_state += b.per_state;
+    // states per pass: keep one pass's intermediates near the size of the on-package cache
+    pol->chunk = 0;
+    if (pol->ws_per_state > 0) {
+        int64_t ch = (160ll << 20) / pol->ws_per_state;
+        if (ch < 256) ch = 256;
+        if (ch > 8192) ch = 8192;
+        pol->chunk = ch;
+    }
+    if (const char* env = getenv("ACCERL_CHUNK")) { const long v = atol(env); if (v > 0) pol->chunk = v; }
+    *out = pol;
+    return ACCERL_OK;
+}
+
+void accerl_policy_destroy(accerl_policy* p) {
+    if (!p) return;
+    if (p->ws) (void)hipFree(p->ws);
+    if (p->consts) (void)hipFree(p->consts);
+    delete p;
+}
+
+static int forward_impl(accerl_policy* p, bool want_student, const void* states, int64_t B, const float* uniforms,
+                        float* out_logits, float* out_value, int32_t* out_action, void* stream) {
+    int rc = check_common(p, states, B, true, uniforms, out_logits, out_value, out_action);
+    if (rc) return rc;
+    if (want_student != (p->arch.precision == ACCERL_INT8))
+        return fail(ACCERL_EINVAL, want_student ? "accerl_actor_forward needs an int8 policy" : "accerl_actor_forward_teacher needs an fp32 or bf16 policy");
+    if (p->recurrent) return fail(ACCERL_EINVAL, "recurrent policy: use accerl_actor_forward_recurrent");
+    Call c{states, B, uniforms, nullptr, nullptr, nullptr, out_logits, out_value, out_action, (hipStream_t)stream};
+    return run(p, c);
+}
+
+int accerl_actor_forward(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
+                         float* out_logits, float* out_value, int32_t* out_action, void* stream) {
+    return forward_impl(p, true, states, B, uniforms, out_logits, out_value, out_action, stream);
+}
+
+int accerl_actor_forward_teacher(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
+                                 float* out_logits, float* out_value, int32_t* out_action, void* stream) {
+    return forward_impl(p, false, states, B, uniforms, out_logits, out_value, out_action, stream);
+}
+
+int accerl_actor_forward_recurrent(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
+                                   const uint8_t* done, float* h, float* c,
+                                   float* out_logits, float* out_value, int32_t* out_action, void* stream) {
+    int rc = check_common(p, states, B, true, uniforms, out_logits, out_value, out_action);
+    if (rc) return rc;
+    if (!p->recurrent) return fail(ACCERL_EINVAL, "policy has no lstm layer");
+    if (B == 0) return ACCERL_OK;
+    if (!h || !c) return fail(ACCERL_EINVAL, "h or c is NULL");
+    if (((uintptr_t)h | (uintptr_t)c) & 15) return fail(ACCERL_EINVAL, "h or c is not 16-byte aligned");
+    Call cl{states, B, uniforms, done, h, c, out_logits, out_value, out_action, (hipStream_t)stream};
+    return run(p, cl);
+}
+
+int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, int32_t layer, int32_t tap,
+                               void* out, int64_t out_bytes, void* stream) {
+    int rc = check_common(p, states, B, false, nullptr, nullptr, nullptr, nullptr);
+    if (rc) return rc;
+    if (B == 0) return ACCERL_OK;
+    if (!out) return fail(ACCERL_EINVAL, "out is NULL");
+    if ((uintptr_t)out & 15) return fail(ACCERL_EINVAL, "out is not 16-byte aligned");
+    if (tap < ACCERL_TAP_ACC || tap > ACCERL_TAP_ACT_A) return fail(ACCERL_EINVAL, "bad tap kind");
+    if ((tap == ACCERL_TAP_ACC || tap == ACCERL_TAP_ACC_A) && p->arch.precision != ACCERL_INT8)
+        return fail(ACCERL_EINVAL, "accumulator taps are student-only");
+    if (p->recurrent && layer >= p->arch.n_layers - 1) return fail(ACCERL_EINVAL, "recurrent policies: taps before the lstm only");
+    Call c{states, B, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream};
+    c.debug = true; c.layer = layer; c.tap = tap; c.out = out; c.out_bytes = out_bytes;
+    return run(p, c);
+}
+
+const char* accerl_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

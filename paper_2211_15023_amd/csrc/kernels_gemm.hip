@@ -1,0 +1,192 @@
+// Dense layers on the matrix cores: out[b, n] = sum_k W[n, k] x[b, k], int8 (int32 accumulate) or
+// bf16 (fp32 accumulate).  Output features are the MFMA rows and states the columns, so one lane ends
+// up with 4 consecutive features of one state.  A workgroup owns 64 features x 128 states and walks K
+// in stages of 256 bytes per row staged through LDS; the epilogue is chosen at compile time:
+// requantize to int8, bias+ReLU to bf16, policy heads (logits / value in fp32), or the LSTM cell
+// (weight rows are interleaved on the host so that the 4 accumulators of a lane are the i,f,g,o
+// pre-activations of one hidden unit).
+#include "accerl_internal.h"
+
+namespace accerl {
+
+constexpr int GM_THREADS = 256;
+constexpr int GM_NT = 4;          // feature tiles (of 16) per workgroup
+constexpr int GM_ROWS = 128;      // states per workgroup
+constexpr int GM_KS = 4;          // MFMA steps per LDS stage (64 bytes of K each)
+constexpr int GM_XPITCH = GM_KS * 64 + 16;
+
+__device__ __forceinline__ uint32_t g_relu_i8x4(uint32_t x) {
+    const uint32_t neg = (x & 0x80808080u) >> 7;
+    return x & ~(neg * 0xffu);
+}
+__device__ __forceinline__ uint32_t g_relu_bf16x2(uint32_t x) {
+    const uint32_t neg = (x & 0x80008000u) >> 15;
+    return x & ~(neg * 0xffffu);
+}
+__device__ __forceinline__ uint32_t g_f2bf(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return u >> 16;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float g_sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+template <int EL, int EPI>
+__global__ __launch_bounds__(GM_THREADS) void gemm_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(16))) char s_w[GM_NT * GM_KS * 1024];
+    __shared__ __attribute__((aligned(16))) char s_x[GM_ROWS * GM_XPITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int64_t b0 = (int64_t)blockIdx.x * GM_ROWS;
+    const int nt0 = blockIdx.y * GM_NT;
+    const int nts = (p.n_tiles - nt0 < GM_NT) ? (p.n_tiles - nt0) : GM_NT;
+
+    v4i acc_i[2][GM_NT];
+    v4f acc_f[2][GM_NT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int t = 0; t < GM_NT; ++t) {
+            acc_i[u][t] = (v4i){0, 0, 0, 0};
+            acc_f[u][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+
+    for (int s0 = 0; s0 < p.k_steps; s0 += GM_KS) {
+        const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
+        __syncthreads();
+        // weights: for each feature tile the ns fragments of this stage are contiguous in global
+        for (int i = tid; i < GM_NT * GM_KS * 64; i += GM_THREADS) {
+            const int t = i / (GM_KS * 64), rem = i - t * (GM_KS * 64);
+            const int st = rem >> 6;
+            v4i v = {0, 0, 0, 0};
+            if (t < nts && st < ns)
+                v = ((const v4i*)p.wfrag)[((int64_t)(nt0 + t) * p.k_steps + s0 + st) * 64 + (rem & 63)];
+            ((v4i*)s_w)[i] = v;
+        }
+        // states: 128 rows x 16 chunks
+        for (int i = tid; i < GM_ROWS * GM_KS * 4; i += GM_THREADS) {
+            const int rr = i / (GM_KS * 4), c = i - rr * (GM_KS * 4);
+            const int64_t b = b0 + rr;
+            const int kb = s0 * 64 + c * 16;
+            v4i v = {0, 0, 0, 0};
+            if (b < p.B && kb < p.Kp_bytes) {
+                v = *(const v4i*)((const char*)p.x + b * p.Kp_bytes + kb);
+                if (p.relu_in) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = (int)((EL == EL_I8) ? g_relu_i8x4((uint32_t)v[e]) : g_relu_bf16x2((uint32_t)v[e]));
+                }
+            }
+            *(v4i*)(s_x + rr * GM_XPITCH + c * 16) = v;
+        }
+        __syncthreads();
+        for (int st = 0; st < ns; ++st) {
+            v4i bq[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                bq[u] = *(const v4i*)(s_x + ((wave * 2 + u) * 16 + j) * GM_XPITCH + st * 64 + g * 16);
+#pragma unroll
+            for (int t = 0; t < GM_NT; ++t) {
+                const v4i a = *(const v4i*)(s_w + ((t * GM_KS + st) * 64 + lane) * 16);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if constexpr (EL == EL_I8) {
+                        acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bq[u], acc_i[u][t], 0, 0, 0);
+                    } else {
+                        acc_f[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, bq[u]), acc_f[u][t], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: lane holds features n0 .. n0+3 of state b
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int64_t b = b0 + (wave * 2 + u) * 16 + j;
+        if (b >= p.B) continue;
+#pragma unroll
+        for (int t = 0; t < GM_NT; ++t) {
+            if (t >= nts) continue;
+            const int n0 = (nt0 + t) * 16 + 4 * g;
+            if (n0 >= p.N) continue;
+            if constexpr (EPI == EPI_REQUANT) {
+                const v4i bi = *(const v4i*)((const int*)p.bias + n0);
+                const v4f ml = *(const v4f*)(p.mult + n0);
+                const float lo = p.relu ? 0.0f : -127.0f;
+                uint32_t pk = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int v = acc_i[u][t][r] + bi[r];
+                    if (p.tap_acc && n0 + r < p.N) p.tap_acc[b * p.N + n0 + r] = v;
+                    float y = rintf((float)v * ml[r]);
+                    y = fmaxf(fminf(y, 127.0f), lo);
+                    pk |= (uint32_t)(uint8_t)(int8_t)(int)y << (8 * r);
+                }
+                *(uint32_t*)((int8_t*)p.out + b * p.Np + n0) = pk;
+            } else if constexpr (EPI == EPI_HEADS_I8) {
+                const v4i bi = *(const v4i*)((const int*)p.bias + n0);
+                const v4f ml = *(const v4f*)(p.mult + n0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int n = n0 + r;
+                    if (n > p.A) continue;
+                    const int v = acc_i[u][t][r] + bi[r];
+                    if (p.tap_acc) p.tap_acc[b * (p.A + 1) + n] = v;
+                    const float o = (float)v * ml[r];
+                    if (p.logits) { if (n < p.A) p.logits[b * p.A + n] = o; else p.value[b] = o; }
+                }
+            } else if constexpr (EPI == EPI_BF16) {
+                const v4f bs = *(const v4f*)((const float*)p.bias + n0);
+                float v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    v[r] = acc_f[u][t][r] + bs[r];
+                    if (p.relu) v[r] = fmaxf(v[r], 0.0f);
+                }
+                uint32_t* d = (uint32_t*)((uint16_t*)p.out + b * p.Np + n0);
+                d[0] = g_f2bf(v[0]) | (g_f2bf(v[1]) << 16);
+                d[1] = g_f2bf(v[2]) | (g_f2bf(v[3]) << 16);
+            } else if constexpr (EPI == EPI_HEADS_F32ACC) {
+                const v4f bs = *(const v4f*)((const float*)p.bias + n0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int n = n0 + r;
+                    if (n > p.A) continue;
+                    const float o = acc_f[u][t][r] + bs[r];
+                    if (p.logits) { if (n < p.A) p.logits[b * p.A + n] = o; else p.value[b] = o; }
+                }
+            } else {   // EPI_LSTM: rows 4*unit + {i,f,g,o}
+                const v4f bs = *(const v4f*)((const float*)p.bias + n0);
+                const int unit = n0 >> 2;
+                const float pi = acc_f[u][t][0] + bs[0], pf = acc_f[u][t][1] + bs[1];
+                const float pg = acc_f[u][t][2] + bs[2], po = acc_f[u][t][3] + bs[3];
+                const float si = g_sigmoid(pi), sf = g_sigmoid(pf), tg = tanhf(pg), so = g_sigmoid(po);
+                const float c_old = p.c[b * p.Hd + unit];
+                const float t1 = sf * c_old;
+                const float t2 = si * tg;
+                const float cn = t1 + t2;
+                const float hn = so * tanhf(cn);
+                p.c[b * p.Hd + unit] = cn;
+                p.h[b * p.Hd + unit] = hn;
+                ((uint16_t*)p.out)[b * p.Np + unit] = (uint16_t)g_f2bf(hn);   // bf16 copy for the heads
+            }
+        }
+    }
+}
+
+hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s) {
+    if (p.B <= 0) return hipSuccess;
+    dim3 grid((unsigned)((p.B + GM_ROWS - 1) / GM_ROWS), (unsigned)((p.n_tiles + GM_NT - 1) / GM_NT));
+    dim3 block(GM_THREADS);
+    if (el == EL_I8 && epi == EPI_REQUANT) gemm_kernel<EL_I8, EPI_REQUANT><<<grid, block, 0, s>>>(p);
+    else if (el == EL_I8 && epi == EPI_HEADS_I8) gemm_kernel<EL_I8, EPI_HEADS_I8><<<grid, block, 0, s>>>(p);
+    else if (el == EL_BF16 && epi == EPI_BF16) gemm_kernel<EL_BF16, EPI_BF16><<<grid, block, 0, s>>>(p);
+    else if (el == EL_BF16 && epi == EPI_HEADS_F32ACC) gemm_kernel<EL_BF16, EPI_HEADS_F32ACC><<<grid, block, 0, s>>>(p);
+    else if (el == EL_BF16 && epi == EPI_LSTM) gemm_kernel<EL_BF16, EPI_LSTM><<<grid, block, 0, s>>>(p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace accerl

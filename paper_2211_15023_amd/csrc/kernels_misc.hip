@@ -1,0 +1,251 @@
+// Small kernels around the MFMA layers: sampler, observation quantizer, fp32 dense layer (teacher
+// MLP), NHWC max pooling, LSTM operand packing, debug conversions.
+#include "accerl_internal.h"
+
+namespace accerl {
+
+// ------------------------------------------------------------------ inverse-CDF sampler
+// One lane per state: m = max logit, Z = sum exp(l - m) in index order, first a with cum > u*Z.
+__global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ logits, const float* __restrict__ u,
+                                                     int32_t* __restrict__ action, int64_t B, int A) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const float* lg = logits + b * A;
+    float m = lg[0];
+    for (int a = 1; a < A; ++a) m = fmaxf(m, lg[a]);
+    float Z = 0.0f;
+    for (int a = 0; a < A; ++a) Z += expf(lg[a] - m);
+    const float thr = u[b] * Z;
+    float cum = 0.0f;
+    int act = A - 1;
+    for (int a = 0; a < A; ++a) {
+        cum += expf(lg[a] - m);
+        if (cum > thr) { act = a; break; }
+    }
+    action[b] = act;
+}
+
+hipError_t launch_sample(const float* logits, const float* uniforms, int32_t* action, int64_t B, int A, hipStream_t s) {
+    if (B <= 0) return hipSuccess;
+    sample_kernel<<<dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s>>>(logits, uniforms, action, B, A);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fp32 observation -> int8 rows (padded)
+__global__ __launch_bounds__(256) void quant_obs_kernel(const float* __restrict__ obs, int64_t B, int D, int Dpad,
+                                                        float inv_s0, int8_t* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * Dpad) return;
+    const int64_t b = i / Dpad;
+    const int f = (int)(i - b * Dpad);
+    int8_t q = 0;
+    if (f < D) {
+        float r = rintf(obs[b * D + f] * inv_s0);
+        r = fminf(r, 127.0f);
+        r = fmaxf(r, -127.0f);
+        q = (int8_t)(int)r;
+    }
+    out[i] = q;
+}
+
+hipError_t launch_quant_obs(const float* obs, int64_t B, int D, int Dpad, float inv_s0, int8_t* out, hipStream_t s) {
+    if (B <= 0) return hipSuccess;
+    const int64_t n = B * Dpad;
+    quant_obs_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(obs, B, D, Dpad, inv_s0, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fp32 dense layer
+// 64 x 64 output tile per workgroup, 4 x 4 per lane, K staged through LDS 16 at a time; products are
+// summed in ascending k with separate multiply and add (no contraction).
+constexpr int GF_T = 64, GF_K = 16;
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
+    __shared__ float sx[GF_K][GF_T + 4];
+    __shared__ float sw[GF_K][GF_T + 4];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t b0 = (int64_t)blockIdx.x * GF_T;
+    const int n0 = blockIdx.y * GF_T;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) acc[i][jn] = 0.0f;
+    for (int k0 = 0; k0 < p.K; k0 += GF_K) {
+        for (int i = threadIdx.x; i < GF_T * GF_K; i += 256) {
+            const int rr = i / GF_K, kk = i - rr * GF_K;
+            const int64_t b = b0 + rr;
+            const int n = n0 + rr;
+            sx[kk][rr] = (b < p.B && k0 + kk < p.K) ? p.x[b * p.ldx + k0 + kk] : 0.0f;
+            sw[kk][rr] = (n < p.N && k0 + kk < p.K) ? p.w[(int64_t)n * p.K + k0 + kk] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < GF_K; ++kk) {
+            float xv[4], wv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { xv[i] = sx[kk][ty * 4 + i]; wv[i] = sw[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jn = 0; jn < 4; ++jn) acc[i][jn] = fmaf(xv[i], wv[jn], acc[i][jn]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t b = b0 + ty * 4 + i;
+        if (b >= p.B) continue;
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) {
+            const int n = n0 + tx * 4 + jn;
+            if (n >= p.N) continue;
+            float v = acc[i][jn] + p.bias[n];
+            if (p.relu) v = fmaxf(v, 0.0f);
+            if (p.heads) {
+                if (n < p.A) p.logits[b * p.A + n] = v; else p.value[b] = v;
+            } else {
+                p.out[b * p.ldo + n] = v;
+            }
+        }
+    }
+}
+
+hipError_t launch_gemm_f32(const GemmF32Params& p, hipStream_t s) {
+    if (p.B <= 0) return hipSuccess;
+    dim3 grid((unsigned)((p.B + GF_T - 1) / GF_T), (unsigned)((p.N + GF_T - 1) / GF_T));
+    gemm_f32_kernel<<<grid, dim3(256), 0, s>>>(p);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ max pooling, NHWC, padding ignored
+// One lane per output pixel and group of 4 stored channels (int8: one dword; bf16: two dwords).
+__device__ __forceinline__ uint32_t max_i8x4(uint32_t a, uint32_t b) {
+    uint32_t r = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int x = (int)(int8_t)(a >> (8 * e)), y = (int)(int8_t)(b >> (8 * e));
+        r |= (uint32_t)(uint8_t)(int8_t)(x > y ? x : y) << (8 * e);
+    }
+    return r;
+}
+
+__device__ __forceinline__ float bf16_to_float(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+__device__ __forceinline__ uint32_t max_bf16x2(uint32_t a, uint32_t b) {
+    const float a0 = bf16_to_float((uint16_t)a), a1 = bf16_to_float((uint16_t)(a >> 16));
+    const float b0 = bf16_to_float((uint16_t)b), b1 = bf16_to_float((uint16_t)(b >> 16));
+    const uint32_t lo = (b0 > a0) ? (b & 0xffffu) : (a & 0xffffu);
+    const uint32_t hi = (b1 > a1) ? (b >> 16) : (a >> 16);
+    return lo | (hi << 16);
+}
+
+template <int EL>
+__global__ __launch_bounds__(256) void maxpool_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+                                                      int64_t B, int H, int W, int Cg, int Ho, int Wo, int k, int s, int pad) {
+    // Cg = groups of 4 channels per pixel; a group is 1 dword (int8) or 2 dwords (bf16)
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = B * Ho * Wo * Cg;
+    if (i >= total) return;
+    const int cg = (int)(i % Cg);
+    int64_t t = i / Cg;
+    const int ox = (int)(t % Wo); t /= Wo;
+    const int oy = (int)(t % Ho);
+    const int64_t b = t / Ho;
+    constexpr int DW = (EL == EL_I8) ? 1 : 2;
+    uint32_t m[DW];
+    bool first = true;
+    for (int ky = 0; ky < k; ++ky) {
+        const int iy = oy * s + ky - pad;
+        if (iy < 0 || iy >= H) continue;
+        for (int kx = 0; kx < k; ++kx) {
+            const int ix = ox * s + kx - pad;
+            if (ix < 0 || ix >= W) continue;
+            const uint32_t* src = in + (((b * H + iy) * W + ix) * Cg + cg) * DW;
+#pragma unroll
+            for (int d = 0; d < DW; ++d) {
+                const uint32_t v = src[d];
+                if (first) m[d] = v;
+                else m[d] = (EL == EL_I8) ? max_i8x4(m[d], v) : max_bf16x2(m[d], v);
+            }
+            first = false;
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DW; ++d) out[i * DW + d] = m[d];
+}
+
+hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,
+                          int k, int s, int pad, Elem el, hipStream_t stream) {
+    if (B <= 0) return hipSuccess;
+    const int Cg = Cs / 4;
+    const int64_t total = B * Ho * Wo * Cg;
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (el == EL_I8)
+        maxpool_kernel<EL_I8><<<grid, block, 0, stream>>>((const uint32_t*)in, (uint32_t*)out, B, H, W, Cg, Ho, Wo, k, s, pad);
+    else
+        maxpool_kernel<EL_BF16><<<grid, block, 0, stream>>>((const uint32_t*)in, (uint32_t*)out, B, H, W, Cg, Ho, Wo, k, s, pad);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ LSTM operand packing
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)(u >> 16);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__global__ __launch_bounds__(256) void lstm_pack_kernel(LstmPackParams p) {
+    const int K = p.In + p.Hd;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= p.B * K) return;
+    const int64_t b = i / K;
+    const int f = (int)(i - b * K);
+    const bool dn = p.done && p.done[b] != 0;
+    float v;
+    if (f < p.In) {
+        const char* row = (const char*)p.x + b * p.x_pitch_bytes;
+        if (p.x_elem == EL_I8) {
+            int q = ((const int8_t*)row)[f];
+            if (p.x_relu && q < 0) q = 0;
+            v = (float)q * p.x_scale;
+        } else if (p.x_elem == EL_BF16) {
+            v = bf16_to_float(((const uint16_t*)row)[f]);
+            if (p.x_relu) v = fmaxf(v, 0.0f);
+        } else {
+            v = ((const float*)row)[f];
+            if (p.x_relu) v = fmaxf(v, 0.0f);
+        }
+    } else {
+        const int jh = f - p.In;
+        float hv = p.h[b * p.Hd + jh];
+        if (dn) {
+            hv = 0.0f;
+            p.h[b * p.Hd + jh] = 0.0f;
+            p.c[b * p.Hd + jh] = 0.0f;
+        }
+        v = hv;
+    }
+    p.xh[i] = f32_to_bf16_rne(v);
+}
+
+hipError_t launch_lstm_pack(const LstmPackParams& p, hipStream_t s) {
+    if (p.B <= 0) return hipSuccess;
+    const int64_t n = p.B * (p.In + p.Hd);
+    lstm_pack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ debug conversion
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(const uint16_t* __restrict__ in, float* __restrict__ out, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = bf16_to_float(in[i]);
+}
+
+hipError_t launch_bf16_to_f32(const uint16_t* in, float* out, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    bf16_to_f32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(in, out, n);
+    return hipGetLastError();
+}
+
+}  // namespace accerl

@@ -39,3 +39,30 @@ def rel_err_rows(got, ref):
     else:
         den = np.maximum(np.abs(ref).max(axis=1, keepdims=True), 1e-6)
     return np.abs(got - ref) / den
+
+
+# ------------------------------------------------------------------ GPU-side helpers
+def student_tensors(qp):
+    return qp.tensors
+
+
+def teacher_tensors(params):
+    return [dict(w=w, b=b) for _, w, b in params]
+
+
+def action_margin(ref_logits, u):
+    """Distance of each uniform to the nearest CDF boundary of the oracle's distribution (float64)."""
+    l = np.asarray(ref_logits, np.float64)
+    e = np.exp(l - l.max(axis=1, keepdims=True))
+    cdf = np.cumsum(e, axis=1) / e.sum(axis=1, keepdims=True)
+    return np.abs(cdf[:, :-1] - np.asarray(u, np.float64)[:, None]).min(axis=1) if l.shape[1] > 1 else np.ones(len(u))
+
+
+def check_actions(got, ref_action, ref_logits, u, delta):
+    got = np.asarray(got)
+    assert got.min() >= 0 and got.max() < ref_logits.shape[1]
+    bad = got != ref_action
+    if bad.any():
+        m = action_margin(ref_logits, u)
+        assert np.all(m[bad] <= delta), f"{bad.sum()} actions differ, margins {m[bad][:8]}"
+    return int(bad.sum())

@@ -1,0 +1,104 @@
+"""The C-ABI library loads, exports every declared symbol and rejects bad arguments without a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2211_15023_amd as A
+    A.load_library()
+    return A
+
+
+def test_exports_every_declared_symbol(A):
+    hdr = open(os.path.join(ROOT, "include", "accerl.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(accerl_[a-z_0-9]+)\s*\(", hdr))
+    assert {"accerl_policy_create", "accerl_actor_forward", "accerl_actor_forward_teacher",
+            "accerl_actor_forward_recurrent", "accerl_actor_forward_debug", "accerl_policy_destroy",
+            "accerl_last_error", "accerl_blob_sizes"} <= names
+    lib = A.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_blob_sizes_match_parameter_counts(A):
+    for ci, cfg in wl.CONFIGS.items():
+        for role, prec in (("student", "int8"), ("teacher", cfg["teacher_precision"])):
+            net = cfg[role]
+            wb, ns = A.blob_sizes(A.make_arch(net, prec))
+            shapes = wl.param_shapes(net)
+            has_lstm = any(l["kind"] == "lstm" for l in net.layers)
+            off, nsw = 0, 0
+            for name, ws, bs in shapes:
+                q = prec == "int8" and "lstm" not in name and not (name == "heads" and has_lstm)
+                off = (off + 15) // 16 * 16 + int(np.prod(ws)) * (1 if q else 4)
+                if bs is not None:
+                    off = (off + 15) // 16 * 16 + int(np.prod(bs)) * 4
+                nsw += ws[0] if q else 0
+            assert wb == off, (ci, role)
+            if prec == "int8":
+                n_act = 1 + sum(1 for l in net.layers if l["kind"] in ("conv", "dense")) + \
+                    2 * sum(1 for l in net.layers if l["kind"] == "resblock")
+                assert ns == n_act + nsw
+            else:
+                assert ns == 0
+
+
+def test_bad_arguments_are_rejected_before_any_gpu_work(A):
+    lib = A.load_library()
+    net = wl.CONFIGS[0]["student"]
+    arch = A.make_arch(net, "int8")
+    wb, ns = A.blob_sizes(arch)
+    h = C.c_void_p()
+    blob = np.zeros(wb, np.uint8)
+    sc = np.ones(ns, np.float32)
+    vp = lambda a: a.ctypes.data_as(C.c_void_p)
+    assert lib.accerl_policy_create(None, vp(blob), wb, vp(sc), ns, C.byref(h)) == -1
+    assert "NULL" in A.accerl_last_error()
+    assert lib.accerl_policy_create(C.byref(arch), None, wb, vp(sc), ns, C.byref(h)) == -1
+    assert lib.accerl_policy_create(C.byref(arch), vp(blob), wb - 1, vp(sc), ns, C.byref(h)) == -1
+    assert lib.accerl_policy_create(C.byref(arch), vp(blob), wb, vp(sc), ns + 1, C.byref(h)) == -1
+    assert lib.accerl_policy_create(C.byref(arch), vp(blob), wb, None, ns, C.byref(h)) == -1
+    bad = np.ones(ns, np.float32)
+    bad[1] = 0.0
+    assert lib.accerl_policy_create(C.byref(arch), vp(blob), wb, vp(bad), ns, C.byref(h)) == -1
+    blob128 = blob.copy()
+    blob128[0] = 0x80                                    # int8 -128 is outside the symmetric range
+    assert lib.accerl_policy_create(C.byref(arch), vp(blob128), wb, vp(sc), ns, C.byref(h)) == -1
+    # inconsistent arch: dense input width does not match
+    arch2 = A.make_arch(net, "int8")
+    arch2.layers[1].cin = 63
+    assert lib.accerl_blob_sizes(C.byref(arch2), None, None) == -1
+    arch3 = A.make_arch(net, "int8")
+    arch3.n_actions = 0
+    assert lib.accerl_blob_sizes(C.byref(arch3), None, None) == -1
+    # image policy without flatten before the heads
+    cnn = wl.nature_cnn()
+    a4 = A.make_arch(cnn, "int8")
+    a4.n_layers = 3
+    assert lib.accerl_blob_sizes(C.byref(a4), None, None) == -1
+    # forward with a NULL policy
+    assert lib.accerl_actor_forward(None, None, 4, None, None, None, None, None) == -1
+    assert h.value is None
+
+
+def test_product_code_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2211_15023_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("no CPU fallback", ""), f
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "oracle")):
+        for f in files:
+            if f.endswith((".py", ".c")):
+                assert "paper_2211_15023_amd" not in open(os.path.join(dirpath, f)).read(), f
