@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the actor forward on one MI355X.
+
+A "step" is one accerl_actor_forward call of the int8 student over one batch of synthetic Atari-like
+frames already resident in HBM (Nature-DQN CNN, B = 4096: the network the paper's own "Original"
+row and its 6 ms -> 3 ms int8 figure refer to).  `value` is states per second of that call.  The
+same line carries: the B = 160 forward latency (the paper's batch size), the bf16 teacher's numbers
+and the student/teacher speedup, the per-kernel breakdown, the roofline figure of the dominant
+kernel (HIP events around every launch, in a second pass over the same steps), and the CPU oracle
+timed on this machine's host cores on a sample of the same states.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--batch 4096]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"int8": 5.0e15, "bf16": 2.5e15, "fp32": 157.3e12, "hbm": 8.0e12}
+
+
+def layer_macs(net, shapes_in):
+    """Useful multiply-accumulates per state of each parametrised layer, keyed by arch layer index
+    (resblock: both convolutions; n_layers: the heads)."""
+    import workloads as wl
+    out = {}
+    shp = tuple(net.obs_shape)
+    outs = wl.trace_shapes(net)
+    for i, L in enumerate(net.layers):
+        o = outs[i]
+        if L["kind"] == "conv":
+            out[i] = o[1] * o[2] * L["cout"] * L["cin"] * L["k"] ** 2
+        elif L["kind"] == "resblock":
+            out[i] = 2 * o[1] * o[2] * L["ch"] * L["ch"] * 9
+        elif L["kind"] == "dense":
+            out[i] = L["cin"] * L["cout"]
+        elif L["kind"] == "lstm":
+            out[i] = 4 * L["hidden"] * (L["cin"] + L["hidden"])
+        shp = o
+    out[len(net.layers)] = (net.n_actions + 1) * wl.feature_dim(net)
+    return out
+
+
+def io_bytes(net):
+    """Algorithmic HBM bytes per state: observation in, uniform in, logits / value / action out."""
+    import numpy as np
+    obs = int(np.prod(net.obs_shape)) * (1 if net.obs_dtype == "u8" else 4)
+    return obs + 4 + net.n_actions * 4 + 4 + 4
+
+
+def time_forward(pol, x, u, outs, steps, warmup, **kw):
+    import torch
+    for _ in range(warmup):
+        pol.forward(x, u, outputs=outs, **kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        pol.forward(x, u, outputs=outs, **kw)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-extra", action="store_true", help="only the headline workload")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU only (states are independent rows; a fleet of actors "
+              "shards by row with no exchange on the forward path). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2211_15023_amd as A
+    from paper_2211_15023_amd import compressor
+
+    A.load_library()
+    ci = args.config
+    cfg = wl.CONFIGS[ci]
+    nt, ns = cfg["teacher"], cfg["student"]
+    B = args.batch or (cfg["batches"][1] if ci == 2 else cfg["batches"][-1])
+    tprec = cfg["teacher_precision"]
+
+    def states(net, n, stream):
+        if net.obs_dtype == "u8":
+            return wl.make_frames_u8(n, *net.obs_shape, stream=stream)
+        return wl.make_obs_f32(n, net.obs_shape[0], stream=stream)
+
+    # ---- policies (Compressor output on the host, once)
+    pt = wl.init_params(nt, wl.STREAM["weights_teacher"])
+    if cfg["student_from"] == "quantize":
+        ps = pt
+    elif cfg["student_from"] == "independent":
+        ps = wl.init_params(ns, wl.STREAM["weights_student"])
+    else:
+        ps = compressor.prune_policy(nt, pt, ns)
+    tensors, act_scales = compressor.quantize_policy(ns, ps, states(ns, cfg["calib"], wl.STREAM["calibration"]))
+    student = A.Policy(ns, "int8", tensors, act_scales)
+    teacher = A.Policy(nt, tprec, compressor.teacher_tensors(pt))
+
+    # ---- inputs, resident in HBM before any timed region
+    x_host = states(ns, B, wl.STREAM["states"])
+    u_host = wl.make_uniforms(B)
+    x, u = torch.from_numpy(x_host).cuda(), torch.from_numpy(u_host).cuda()
+    kw = {}
+    if student.recurrent:
+        h, c = wl.make_hc(B, 256)
+        kw = dict(done=torch.from_numpy(wl.make_done(1, B)[0]).cuda(), h=torch.from_numpy(h).cuda(), c=torch.from_numpy(c).cuda())
+    outs = student.alloc_outputs(B)
+    torch.cuda.synchronize()
+
+    # ---- headline: K timed steps of the student
+    sec = time_forward(student, x, u, outs, args.steps, args.warmup, **kw)
+    value = B / sec
+
+    # ---- second pass with HIP events around every launch: per-kernel breakdown and roofline
+    A.accerl_profile_begin(student.handle)
+    for _ in range(args.steps):
+        student.forward(x, u, outputs=outs, **kw)
+    torch.cuda.synchronize()
+    prof = A.accerl_profile_end(student.handle)
+    macs = layer_macs(ns, None)
+    n_launch_step = sum(p["launches"] for p in prof) / args.steps
+    breakdown = []
+    for p in prof:
+        if not p["launches"]:
+            continue
+        per_step_ms = p["total_ms"] / args.steps
+        ent = dict(step=p["step"], kind=p["kind"], layer=p["layer"], ms_per_step=round(per_step_ms, 5),
+                   launches_per_step=p["launches"] / args.steps)
+        if p["kind"] in ("conv", "gemm"):
+            m = macs.get(p["layer"], 0)
+            if ns.layers[p["layer"]]["kind"] == "resblock" if p["layer"] < len(ns.layers) else False:
+                m //= 2
+            ent["tops"] = round(2 * m * B / (per_step_ms * 1e-3) / 1e12, 2)
+        breakdown.append(ent)
+    dom = max(breakdown, key=lambda e: e["ms_per_step"])
+    launches = dom["launches_per_step"]
+    avg_launch_s = dom["ms_per_step"] * 1e-3 / launches
+    if dom["kind"] in ("conv", "gemm"):
+        m = macs[dom["layer"]]
+        if dom["layer"] < len(ns.layers) and ns.layers[dom["layer"]]["kind"] == "resblock":
+            m //= 2
+        is_bf16 = student.recurrent and dom["layer"] >= len(ns.layers) - 1
+        ops_launch = 2.0 * m * B / launches
+        peak = PEAK["bf16" if is_bf16 else "int8"]
+        roofline = dict(bound="mfma", achieved=round(ops_launch / avg_launch_s / 1e12, 3), peak=peak / 1e12,
+                        unit="TFLOP/s", frac=round(ops_launch / avg_launch_s / peak, 4), traffic=None,
+                        kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                        launches_per_step=launches)
+    else:
+        bytes_launch = io_bytes(ns) * B / launches
+        roofline = dict(bound="hbm", achieved=round(bytes_launch / avg_launch_s / 1e9, 2), peak=PEAK["hbm"] / 1e9,
+                        unit="GB/s", frac=round(bytes_launch / avg_launch_s / PEAK["hbm"], 4), traffic=None,
+                        kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                        launches_per_step=launches)
+    tfile = os.path.join(ROOT, "profiles", f"traffic_cfg{ci}_B{B}.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch"):
+                roofline["traffic"] = float(line.split("=")[1])
+
+    total_macs = sum(macs.values())
+    whole = dict(useful_tops=round(2 * total_macs * B / sec / 1e12, 2), frac_int8_peak=round(2 * total_macs * B / sec / PEAK["int8"], 4),
+                 io_gbps=round(io_bytes(ns) * B / sec / 1e9, 2), frac_hbm_peak=round(io_bytes(ns) * B / sec / PEAK["hbm"], 4))
+
+    extra = dict(kernels=breakdown, whole_forward=whole, launches_per_step=n_launch_step)
+    if not args.no_extra:
+        # teacher at the same batch, and both at the paper's batch size of 160
+        touts = teacher.alloc_outputs(B)
+        xt = x if nt.obs_dtype == ns.obs_dtype and nt.obs_shape == ns.obs_shape else torch.from_numpy(states(nt, B, wl.STREAM["states"])).cuda()
+        tsec = time_forward(teacher, xt, u, touts, max(5, args.steps // 4), 3, **kw)
+        extra["teacher"] = dict(precision=tprec, states_per_s=round(B / tsec, 1), ms_per_step=round(tsec * 1e3, 4))
+        extra["student_over_teacher"] = round(tsec / sec, 3)
+        b160 = min(160, B)
+        o160 = student.alloc_outputs(b160)
+        kw160 = {k: v[:b160].contiguous() for k, v in kw.items()}
+        s160 = time_forward(student, x[:b160].contiguous(), u[:b160].contiguous(), o160, 200, 20, **kw160)
+        t160 = time_forward(teacher, xt[:b160].contiguous(), u[:b160].contiguous(), teacher.alloc_outputs(b160), 100, 10, **kw160)
+        extra["latency_B160_us"] = dict(student=round(s160 * 1e6, 2), teacher=round(t160 * 1e6, 2))
+
+    # ---- the CPU oracle on a sample of the same states (rank 0, N = 1 only)
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        from oracle import layers as OL
+        nsamp = {0: B, 1: B, 2: 512, 3: 256, 4: 128}.get(ci, 256)
+        nsamp = min(nsamp, B)
+        qp = oracle.QuantPolicy(tensors=tensors, act_scales=act_scales)
+        okw = {}
+        if student.recurrent:
+            hh, cc = wl.make_hc(B, 256)
+            okw = dict(h=hh[:nsamp], c=cc[:nsamp], done=wl.make_done(1, B)[0][:nsamp])
+        reps = 1
+        oracle.forward_int8(ns, qp, x_host[:min(nsamp, 8)], u_host[:min(nsamp, 8)], **{k: v[:min(nsamp, 8)] for k, v in okw.items()})
+        t0 = time.perf_counter()
+        ref = oracle.forward_int8(ns, qp, x_host[:nsamp], u_host[:nsamp], **okw)
+        dt = time.perf_counter() - t0
+        while dt * reps < 2.0 and reps < 4096:       # tiny networks: repeat to get a stable figure
+            reps *= 4
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                oracle.forward_int8(ns, qp, x_host[:nsamp], u_host[:nsamp], **okw)
+            dt = (time.perf_counter() - t0) / reps
+        cpu = dict(value=round(nsamp / dt, 1), unit="states/s", cores=OL.num_threads(), kind="oracle",
+                   sample=f"first {nsamp} of the {B} benchmark states, int8 student, {dt:.2f} s per pass")
+        # the same sample doubles as an end-of-run parity check of the timed configuration
+        got = outs[0][:nsamp].cpu().numpy()
+        extra["parity_sample_logits_equal"] = bool(np.array_equal(got, ref["logits"])) if not student.recurrent else None
+
+    line = {
+        "metric": "actor states/sec (int8 student vs fp32/bf16 teacher); B=160 forward latency",
+        "value": round(value, 1), "unit": "states/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"config {ci} ({cfg['name']}): int8 student {ns.name}, B={B}, "
+                               f"obs {ns.obs_dtype}{list(ns.obs_shape)}, {ns.n_actions} actions", "batch": B},
+        "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

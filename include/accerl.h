@@ -177,6 +177,20 @@ typedef enum {
 int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, int32_t layer, int32_t tap,
                                void* out, int64_t out_bytes, void* stream);
 
+/*
+ * Measurement aid (not part of the method).  Between accerl_profile_begin and accerl_profile_end
+ * every forward call on the policy records a pair of HIP events around each kernel launch of its
+ * plan, on the stream of that call.  accerl_profile_end waits for those events and returns, per
+ * plan step, the summed elapsed time in ms, the number of launches, the arch layer the step
+ * belongs to (n_layers = heads / sampler) and the step kind (0 fused MLP, 1 observation quantizer,
+ * 2 convolution, 3 MFMA dense, 4 fp32 dense, 5 max pooling, 6 LSTM packing, 7 sampler).  All arrays
+ * are HOST, `cap` entries each; *n_steps receives the number of plan steps (also on ACCERL_EINVAL
+ * when cap is too small).
+ */
+int accerl_profile_begin(accerl_policy* p);
+int accerl_profile_end(accerl_policy* p, int32_t cap, int32_t* n_steps, float* total_ms, int64_t* launches,
+                       int32_t* layer, int32_t* kind);
+
 /* Message of the last error on this thread ("" if none). */
 const char* accerl_last_error(void);
 

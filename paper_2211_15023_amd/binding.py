@@ -51,9 +51,12 @@ def load_library():
     lib.accerl_actor_forward_teacher.argtypes = fwd
     lib.accerl_actor_forward_recurrent.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.accerl_actor_forward_debug.argtypes = [vp, vp, i64, i32, i32, vp, i64, vp]
+    lib.accerl_profile_begin.argtypes = [vp]
+    lib.accerl_profile_end.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.accerl_last_error.restype = C.c_char_p
     for f in ("accerl_blob_sizes", "accerl_policy_create", "accerl_actor_forward", "accerl_actor_forward_teacher",
-              "accerl_actor_forward_recurrent", "accerl_actor_forward_debug"):
+              "accerl_actor_forward_recurrent", "accerl_actor_forward_debug", "accerl_profile_begin",
+              "accerl_profile_end"):
         getattr(lib, f).restype = C.c_int
     _lib = lib
     return lib
@@ -189,6 +192,26 @@ def accerl_actor_forward_debug(handle, states, layer, tap, out, stream=None):
     B = states.shape[0]
     _check(load_library().accerl_actor_forward_debug(handle, _ptr(states), B, int(layer), int(tap), _ptr(out),
                                                      out.numel() * out.element_size(), _stream(stream)))
+
+
+STEP_KINDS = ("mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample")
+
+
+def accerl_profile_begin(handle):
+    _check(load_library().accerl_profile_begin(handle))
+
+
+def accerl_profile_end(handle):
+    """Returns a list of dicts: step, layer, kind, launches, total_ms."""
+    cap = 256
+    n = C.c_int32()
+    ms = (C.c_float * cap)()
+    cnt = (C.c_int64 * cap)()
+    layer = (C.c_int32 * cap)()
+    kind = (C.c_int32 * cap)()
+    _check(load_library().accerl_profile_end(handle, cap, C.byref(n), ms, cnt, layer, kind))
+    return [dict(step=i, layer=layer[i], kind=STEP_KINDS[kind[i]], launches=cnt[i], total_ms=ms[i])
+            for i in range(n.value)]
 
 
 class Policy:

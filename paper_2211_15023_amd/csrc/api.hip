@@ -186,6 +186,10 @@ struct accerl_policy {
     int64_t obs_bytes = 0;
     bool recurrent = false;
     int lstm_hidden = 0;
+    // measurement aid: event pairs around every launch while profiling is on
+    bool profiling = false;
+    struct Ev { int step; hipEvent_t a, b; };
+    std::vector<Ev> events;
 };
 
 namespace {
@@ -768,6 +772,12 @@ int run(accerl_policy* p, const Call& c) {
             const Step& s = p->steps[si];
             const bool tap_here = c.debug && !fused && si == last_step;
             hipError_t e = hipSuccess;
+            accerl_policy::Ev ev{si, nullptr, nullptr};
+            if (p->profiling) {
+                HIP_TRY(hipEventCreate(&ev.a));
+                HIP_TRY(hipEventCreate(&ev.b));
+                HIP_TRY(hipEventRecord(ev.a, c.stream));
+            }
             switch (s.kind) {
                 case ST_MLP: {
                     MlpParams m = s.mp;
@@ -847,6 +857,10 @@ int run(accerl_policy* p, const Call& c) {
                     break;
             }
             if (e != hipSuccess) return fail(ACCERL_EHIP, "step %d (kind %d, layer %d): %s", si, (int)s.kind, s.layer, hipGetErrorString(e));
+            if (p->profiling) {
+                HIP_TRY(hipEventRecord(ev.b, c.stream));
+                p->events.push_back(ev);
+            }
             if (tap_here && !tap_acc) {
                 const char* src = bufp(s.out_buf);
                 if (s.kind == ST_GEMM) {
@@ -948,6 +962,7 @@ int accerl_policy_create(const accerl_arch* arch, const void* weights, int64_t w
 
 void accerl_policy_destroy(accerl_policy* p) {
     if (!p) return;
+    for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
     if (p->ws) (void)hipFree(p->ws);
     if (p->consts) (void)hipFree(p->consts);
     delete p;
@@ -1001,6 +1016,38 @@ int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, 
     Call c{states, B, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream};
     c.debug = true; c.layer = layer; c.tap = tap; c.out = out; c.out_bytes = out_bytes;
     return run(p, c);
+}
+
+int accerl_profile_begin(accerl_policy* p) {
+    if (!p) return fail(ACCERL_EINVAL, "policy is NULL");
+    for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+    p->events.clear();
+    p->profiling = true;
+    return ACCERL_OK;
+}
+
+int accerl_profile_end(accerl_policy* p, int32_t cap, int32_t* n_steps, float* total_ms, int64_t* launches,
+                       int32_t* layer, int32_t* kind) {
+    if (!p || !n_steps) return fail(ACCERL_EINVAL, "policy or n_steps is NULL");
+    p->profiling = false;
+    const int n = (int)p->steps.size();
+    *n_steps = n;
+    int rc = ACCERL_OK;
+    if (cap < n || !total_ms || !launches || !layer || !kind) rc = fail(ACCERL_EINVAL, "profile arrays need %d entries", n);
+    if (rc == ACCERL_OK) {
+        for (int i = 0; i < n; ++i) { total_ms[i] = 0.f; launches[i] = 0; layer[i] = p->steps[i].layer; kind[i] = (int)p->steps[i].kind; }
+        for (auto& ev : p->events) {
+            float ms = 0.f;
+            hipError_t e = hipEventSynchronize(ev.b);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+            if (e != hipSuccess) { rc = fail(ACCERL_EHIP, "reading profile events: %s", hipGetErrorString(e)); break; }
+            total_ms[ev.step] += ms;
+            launches[ev.step] += 1;
+        }
+    }
+    for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+    p->events.clear();
+    return rc;
 }
 
 const char* accerl_last_error(void) { return g_err.c_str(); }

@@ -135,3 +135,49 @@ def test_empty_batch_and_errors(A):
         A.accerl_actor_forward(pol.handle, x, uu, big[1:].view(4, 2), va, ac)
     with pytest.raises(A.AccerlError):      # recurrent entry point on a feed-forward policy
         A.accerl_actor_forward_recurrent(pol.handle, x, uu, None, None, None, lo, va, ac)
+
+
+@pytest.mark.parametrize("role", ["student", "teacher"])
+def test_recurrent_unroll(A, role):
+    """Config 4: a few environment steps with done flags; h and c carried on both sides separately."""
+    nt, pt, ns, ps, qp = policies(4)
+    net = ns if role == "student" else nt
+    pol = gpu_policy(A, 4, role)
+    B, T = 37, 4
+    h0, c0 = wl.make_hc(B, 256)
+    done = wl.make_done(T, B, p=0.2)
+    assert done.any()
+    h_ref, c_ref = h0.copy(), c0.copy()
+    dh, dc = dev(h0), dev(c0)
+    for t in range(T):
+        print(f"recurrent {role} step {t}", flush=True)
+        x = make_states(net, B, wl.STREAM["states"], first=t * B)
+        u = wl.make_uniforms(B, first=t * B)
+        if role == "student":
+            ref = oracle.forward_int8(ns, qp, x, u, h=h_ref, c=c_ref, done=done[t])
+        else:
+            ref = oracle.forward_float(nt, pt, x, u, "bf16", h=h_ref, c=c_ref, done=done[t])
+        h_ref, c_ref = ref["h"], ref["c"]
+        logits, value, action = pol.forward(dev(x), dev(u), done=dev(done[t]), h=dh, c=dc)
+        torch.cuda.synchronize()
+        assert rel_err_rows(logits.cpu().numpy(), ref["logits"]).max() <= 2e-2
+        assert rel_err_rows(value.cpu().numpy(), ref["value"]).max() <= 2e-2
+        assert np.abs(dh.cpu().numpy() - h_ref).max() <= 2e-2 * np.abs(h_ref).max()
+        assert np.abs(dc.cpu().numpy() - c_ref).max() <= 2e-2 * np.abs(c_ref).max()
+        check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 2e-2)
+    # rows that were reset at the last step carry no trace of their earlier state
+    assert np.isfinite(dh.cpu().numpy()).all()
+
+
+def test_recurrent_torso_taps_bit_exact(A):
+    nt, pt, ns, ps, qp = policies(4)
+    pol = gpu_policy(A, 4, "student")
+    B = 19
+    x = make_states(ns, B, wl.STREAM["states"])
+    otaps = {}
+    h0, c0 = wl.make_hc(B, 256)
+    oracle.forward_int8(ns, qp, x, wl.make_uniforms(B), h=h0, c=c0, taps=otaps)
+    i_fc = max(i for i, l in enumerate(ns.layers) if l["kind"] == "dense")
+    exp = otaps[(i_fc, "act")]
+    got = pol.tap(dev(x), i_fc, A.TAP_ACT, exp.shape, torch.int8).cpu().numpy()
+    assert np.array_equal(got, exp)
