@@ -191,6 +191,14 @@ int accerl_profile_begin(accerl_policy* p);
 int accerl_profile_end(accerl_policy* p, int32_t cap, int32_t* n_steps, float* total_ms, int64_t* launches,
                        int32_t* layer, int32_t* kind);
 
+/*
+ * Host-only aid: builds the launch plan exactly as accerl_policy_create would (same arguments, no
+ * GPU needed) and writes a one-line-per-kernel description of it into `text` (HOST, `cap` bytes,
+ * always NUL-terminated, truncated if too small).
+ */
+int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
+                         const float* quant_scales, int64_t n_scales, char* text, int64_t cap);
+
 /* Message of the last error on this thread ("" if none). */
 const char* accerl_last_error(void);
 

@@ -51,6 +51,8 @@ def load_library():
     lib.accerl_actor_forward_teacher.argtypes = fwd
     lib.accerl_actor_forward_recurrent.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.accerl_actor_forward_debug.argtypes = [vp, vp, i64, i32, i32, vp, i64, vp]
+    lib.accerl_plan_describe.argtypes = [C.POINTER(_Arch), vp, i64, vp, i64, C.c_char_p, i64]
+    lib.accerl_plan_describe.restype = C.c_int
     lib.accerl_profile_begin.argtypes = [vp]
     lib.accerl_profile_end.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.accerl_last_error.restype = C.c_char_p
@@ -139,6 +141,19 @@ def accerl_policy_create(arch, weights, quant_scales=None):
     h = C.c_void_p()
     _check(lib.accerl_policy_create(C.byref(arch), weights.ctypes.data_as(C.c_void_p), weights.size, sp, ns, C.byref(h)))
     return h
+
+
+def accerl_plan_describe(arch, weights, quant_scales=None):
+    """Text description of the launch plan (host only, no GPU needed)."""
+    lib = load_library()
+    weights = np.ascontiguousarray(weights, np.uint8)
+    ns, sp = 0, None
+    if quant_scales is not None and len(quant_scales):
+        quant_scales = np.ascontiguousarray(quant_scales, np.float32)
+        ns, sp = quant_scales.size, quant_scales.ctypes.data_as(C.c_void_p)
+    buf = C.create_string_buffer(1 << 16)
+    _check(lib.accerl_plan_describe(C.byref(arch), weights.ctypes.data_as(C.c_void_p), weights.size, sp, ns, buf, len(buf)))
+    return buf.value.decode()
 
 
 def accerl_policy_destroy(handle):

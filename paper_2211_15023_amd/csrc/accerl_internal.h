@@ -41,37 +41,50 @@ hipError_t launch_mlp_i8(const MlpParams& p, hipStream_t s);
 // ---------------------------------------------------------------- observation quantizer (generic path)
 hipError_t launch_quant_obs(const float* obs, int64_t B, int D, int Dpad, float inv_s0, int8_t* out, hipStream_t s);
 
-// ---------------------------------------------------------------- convolution (NHWC tile in LDS, MFMA)
+// ---------------------------------------------------------------- convolution (input tiles in LDS, MFMA)
+enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2 };
 struct ConvParams {
-    const void* in;          // NHWC elements, or NCHW uint8 observations (src_nchw_u8)
+    const void* in;          // NHWC elements, or NCHW uint8 observations (modes FLAT+planar, U8T)
     void* out;               // NHWC elements [B, Ho, Wo, Cs_out]
     const void* res;         // residual stream, same shape as out (NULL = none)
     int32_t* tap_acc;        // int32 [B, Ho, Wo, Cs_out] (NULL = off)
-    const void* wfrag;       // [k_steps][NT][64 lanes][16 B]
+    const void* wfrag;       // [k_step][n_tile][64 lanes][16 B]
     const void* bias;        // int32 (int8 path, zero-point correction folded in) or fp32, [NT*16]
     const float* mult;       // [NT*16] (int8 path)
     const uint16_t* lut;     // 256 bf16 values obs/255 (bf16 path with uint8 source)
     int64_t B;
     int H, W;                // input image
     int Cin_real;            // channels present in the source
-    int Cs_in;               // stored channels per input pixel (multiple of 4)
+    int Cs_in;               // stored channels per input pixel (multiple of 4; planar: 1)
     int Ho, Wo, Cs_out;
     int k, s, pad;
     int TH;                  // output rows per band
     int n_bands;
     int in_rows;             // (TH-1)*s + k
     int pitch;               // bytes per LDS input row
-    int tile_bytes;          // LDS bytes of the input tile including read slack
+    int plane_stride;        // planar: bytes between channel planes in LDS
+    int tile_stride;         // LDS bytes per image tile including read slack (multiple of 16)
     int cpr;                 // 16-byte chunks per kernel row
     int k_steps;             // MFMA steps (4 chunks each)
     int w_bytes;             // bytes of wfrag
     int relu_in;             // max(x, 0) on load
     int relu;                // teacher: ReLU after bias; student: lower clamp 0
-    int src_nchw_u8;
+    int src_u8;              // source is uint8 observations
+    int mode;                // ConvMode: how a tile is staged
+    int planar;              // chunk = 8 bytes of kernel row ky and 8 of ky+1, per channel plane
+    int G;                   // images staged and multiplied together
+    int img_bytes;           // FLAT: contiguous bytes per image
+    int units_img;           // 16-byte staging units per image tile
+    int row_units;           // ROWS / U8T: units per tile row
+    int vec_ok;              // ROWS: every unit is one aligned 16-byte load or pure padding
+    uint32_t magic_npix, magic_wo, magic_units, magic_rowunits;   // ceil(2^32/d), 0 for d = 1
     float r;                 // residual ratio (int8 path)
-    int imgs_per_block;      // images one workgroup walks through
+    int groups;              // grid.y
 };
-hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int align, hipStream_t s);
+// KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.
+// RD: 16 / 8 / 4 = alignment of a chunk read in LDS, 2 = planar (two 8-byte rows).
+hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, hipStream_t s);
+bool conv_has_reg_variant(Elem el, int NT, int KS, int RD);
 
 // ---------------------------------------------------------------- max pooling on NHWC
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,

@@ -151,7 +151,7 @@ struct Step {
     int in_buf = -1, out_buf = -1, res_buf = -1;   // -1 = the caller's states (in) / none
     ConvParams cp{};
     Elem el = EL_I8;
-    int NT = 1, align = 16;
+    int NT = 1, KS = 0, RD = 16;
     GemmParams gp{};
     GemmEpi epi = EPI_REQUANT;
     GemmF32Params fp{};
@@ -230,6 +230,9 @@ struct Builder {
     }
 };
 
+uint32_t magic_of(int d) { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + (uint64_t)d - 1) / (uint64_t)d); }
+int gcd_int(int a, int b) { while (b) { const int t = a % b; a = b; b = t; } return a; }
+
 // One convolution (a conv layer or half of a resblock) -> a conv step.
 int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool src_u8,
               int Cin, int H, int W, int Cout, int k, int s, int pad, bool relu, bool relu_in,
@@ -243,60 +246,110 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     st.res_buf = res_buf;
     st.el = el;
     const int esz = el == EL_I8 ? 1 : 2;
-    const int Cs_in = (int)up(Cin, 4), Cs_out = (int)up(Cout, 4);
+    const int Cs_out = (int)up(Cout, 4);
     if (src_u8 && Cin > 4) return fail(ACCERL_EUNSUPPORTED, "uint8 observations with more than 4 channels");
     if (src_u8 && (W & 3)) return fail(ACCERL_EUNSUPPORTED, "uint8 observation width must be a multiple of 4");
     const int NT = (Cout <= 16) ? 1 : (Cout <= 32) ? 2 : (Cout <= 64) ? 4 : 0;
     if (!NT) return fail(ACCERL_EUNSUPPORTED, "layer %d: more than 64 output channels", layer);
-    const int pix = Cs_in * esz;
-    const int run = k * pix;                        // bytes of one kernel row of one pixel
-    const int cpr = (run + 15) / 16;
-    const int chunks = k * cpr;
-    const int k_steps = (chunks + 3) / 4;
     const int Ho = out_hw(H, k, s, pad), Wo = out_hw(W, k, s, pad);
-    const int pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16);
+    // uint8 frames under an 8-wide kernel stay planar: no transposition, plain contiguous staging
+    const bool planar = src_u8 && el == EL_I8 && k == 8 && pad == 0 && ((Cin * H * W) % 16) == 0;
+    const int Cs_in = planar ? 1 : (int)up(Cin, 4);
+    const int pix = planar ? 1 : Cs_in * esz;
+    const int run = k * pix;                        // bytes of one kernel row of one pixel
+    const int cpr = planar ? 0 : (run + 15) / 16;
+    const int chunks = planar ? Cin * (k / 2) : k * cpr;
+    const int k_steps = (chunks + 3) / 4;
     const int w_bytes = k_steps * NT * 1024;
-    // band height: the largest that keeps weights + patch within the LDS budget
-    const int lds_cap = 160 * 1024 - 1024;
-    int budget = 72 * 1024;
-    if (w_bytes + 40 * 1024 > budget) budget = w_bytes + 40 * 1024;
-    if (budget > lds_cap) budget = lds_cap;
-    int TH = Ho;
-    auto tile_bytes = [&](int th) { return ((th - 1) * s + k) * pitch + 32; };
-    while (TH > 1 && w_bytes + k_steps * 16 + tile_bytes(TH) > budget) --TH;
-    if (w_bytes + k_steps * 16 + tile_bytes(TH) > lds_cap)
-        return fail(ACCERL_EUNSUPPORTED, "layer %d: weights and one input band exceed LDS", layer);
-    const int n_bands = (Ho + TH - 1) / TH;
-    TH = (Ho + n_bands - 1) / n_bands;              // even out the bands
+    const int row_bytes = W * pix;
 
     ConvParams& c = st.cp;
+    int mode, pitch;
+    if (planar) { mode = CM_FLAT; pitch = W; }
+    else if (src_u8) { mode = CM_U8T; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
+    else if (pad == 0 && ((H * row_bytes) % 16) == 0) { mode = CM_FLAT; pitch = row_bytes; }
+    else { mode = CM_ROWS; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
+
+    const int RD = planar ? 2 : [&] { int al = gcd_int(16, gcd_int(s * pix, pitch)); return al < 4 ? 4 : al; }();
+    const int KS = conv_has_reg_variant(el, NT, k_steps, RD) ? k_steps : 0;
+    const int w_lds = KS > 0 ? 0 : w_bytes + k_steps * 16;
+
+    // band height: units to stage per tile <= 4096 (16 per thread), LDS within budget
+    const int lds_cap = 160 * 1024 - 2048;
+    int budget = 64 * 1024;
+    if (w_lds + 36 * 1024 > budget) budget = w_lds + 36 * 1024;
+    if (budget > lds_cap) budget = lds_cap;
+    auto rows_of = [&](int th) { return (th - 1) * s + k; };
+    auto tile_of = [&](int th) { return (int)up(planar ? (int64_t)Cin * H * W + 16 : (int64_t)rows_of(th) * pitch + 32, 16); };
+    auto units_of = [&](int th) {
+        if (planar) return Cin * H * W / 16;
+        if (mode == CM_FLAT) return H * row_bytes / 16;
+        if (mode == CM_U8T) return rows_of(th) * (W / 4);
+        return rows_of(th) * (pitch / 16);
+    };
+    int TH = Ho;
+    if (mode != CM_FLAT) {
+        while (TH > 1 && (units_of(TH) > 4096 || w_lds + tile_of(TH) > budget)) --TH;
+        const int nb = (Ho + TH - 1) / TH;
+        TH = (Ho + nb - 1) / nb;
+    }
+    if (units_of(TH) > 4096 || w_lds + tile_of(TH) > lds_cap)
+        return fail(ACCERL_EUNSUPPORTED, "layer %d: one input band does not fit the staging limits", layer);
+    const int n_bands = (Ho + TH - 1) / TH;
+    const int tile_stride = tile_of(TH), units_img = units_of(TH), n_pix = TH * Wo;
+    // images per batch: best use of the 8 pixel-tile slots (4 waves x 2 tiles) a workgroup fills per round
+    int G = 1;
+    if (n_bands == 1) {
+        double best = -1.0;
+        for (int gg = 1; gg <= 16; ++gg) {
+            if (gg * units_img > 4096 || w_lds + gg * tile_stride > budget) break;
+            const int slots = (gg * n_pix + 127) / 128 * 128;
+            const double util = (double)gg * n_pix / slots;
+            if (util > best + 0.02) { best = util; G = gg; }
+        }
+    }
     c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_out;
-    c.k = k; c.s = s; c.pad = pad; c.TH = TH; c.n_bands = (Ho + TH - 1) / TH;
-    c.in_rows = (TH - 1) * s + k; c.pitch = pitch; c.tile_bytes = tile_bytes(TH);
+    c.k = k; c.s = s; c.pad = pad; c.TH = TH; c.n_bands = n_bands;
+    c.in_rows = planar ? H : rows_of(TH); c.pitch = pitch; c.plane_stride = H * W; c.tile_stride = tile_stride;
     c.cpr = cpr; c.k_steps = k_steps; c.w_bytes = w_bytes;
-    c.relu_in = relu_in; c.relu = relu; c.src_nchw_u8 = src_u8;
-    st.NT = NT;
-    int al = 16;
-    while ((s * pix) % al) al >>= 1;
-    st.align = al < 4 ? 4 : al;
+    c.relu_in = relu_in; c.relu = relu; c.src_u8 = src_u8;
+    c.mode = mode; c.planar = planar; c.G = G;
+    c.img_bytes = planar ? Cin * H * W : H * row_bytes;
+    c.units_img = units_img;
+    c.row_units = mode == CM_U8T ? W / 4 : pitch / 16;
+    c.vec_ok = ((pad * pix) % 16 == 0) && (row_bytes % 16 == 0);
+    c.magic_npix = magic_of(n_pix); c.magic_wo = magic_of(Wo);
+    c.magic_units = magic_of(units_img); c.magic_rowunits = magic_of(c.row_units);
+    st.NT = NT; st.KS = KS; st.RD = RD;
     st.out_elems = (int64_t)Ho * Wo * Cs_out;
     st.acc_elems = el == EL_I8 ? st.out_elems : 0;
 
-    // ---- weight fragments: [k_step][n_tile][lane][16 bytes]
+    // ---- weight fragments: [k_step][n_tile][lane][16 bytes]; MFMA row i of tile tt is channel
+    //      4*NT*(i/4) + 4*tt + i%4, so that a lane's accumulators are consecutive channels
     std::vector<char> frag((size_t)w_bytes, 0);
     const int epc = 16 / esz;                       // elements per chunk
     std::vector<int64_t> wsum(NT * 16, 0);
     for (int stp = 0; stp < k_steps; ++stp)
         for (int tt = 0; tt < NT; ++tt)
             for (int lane = 0; lane < 64; ++lane) {
-                const int n = 16 * tt + (lane & 15), g = lane >> 4;
+                const int i = lane & 15, g = lane >> 4;
+                const int n = 4 * NT * (i >> 2) + 4 * tt + (i & 3);
                 const int q = 4 * stp + g;
-                const int ky = q / cpr, cx = q - ky * cpr;
+                if (n >= Cout) continue;
                 char* dst = frag.data() + ((size_t)(stp * NT + tt) * 64 + lane) * 16;
                 for (int e = 0; e < epc; ++e) {
-                    const int idx = cx * epc + e;   // element index inside the kernel row run
-                    const int kx = idx / Cs_in, ci = idx - kx * Cs_in;
-                    if (ky >= k || kx >= k || ci >= Cin || n >= Cout) continue;
+                    int ci, ky, kx;
+                    if (planar) {
+                        ci = q / (k / 2);
+                        ky = 2 * (q % (k / 2)) + (e >> 3);
+                        kx = e & 7;
+                    } else {
+                        ky = q / cpr;
+                        const int idx = (q - ky * cpr) * epc + e;   // element index inside the kernel row run
+                        kx = idx / Cs_in;
+                        ci = idx - kx * Cs_in;
+                    }
+                    if (ky >= k || kx >= k || ci >= Cin) continue;
                     const int64_t src = (((int64_t)n * Cin + ci) * k + ky) * k + kx;
                     if (el == EL_I8) {
                         const int8_t v = B.wq(t)[src];
@@ -807,11 +860,14 @@ int run(accerl_policy* p, const Call& c) {
                     cp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
                     cp.lut = s.o_lut >= 0 ? (const uint16_t*)(p->consts + s.o_lut) : nullptr;
                     cp.B = n;
-                    int64_t groups = 2048 / cp.n_bands;
-                    if (groups < 1) groups = 1;
-                    if (groups > n) groups = n;
-                    cp.imgs_per_block = (int)((n + groups - 1) / groups);
-                    e = launch_conv(cp, s.el, s.NT, s.align, c.stream);
+                    {
+                        const int64_t n_batch = (n + cp.G - 1) / cp.G;
+                        int64_t groups = 768 / cp.n_bands;
+                        if (groups < 1) groups = 1;
+                        if (groups > n_batch) groups = n_batch;
+                        cp.groups = (int)groups;
+                    }
+                    e = launch_conv(cp, s.el, s.NT, s.KS, s.RD, c.stream);
                     break;
                 }
                 case ST_MAXPOOL:
@@ -906,45 +962,29 @@ int accerl_blob_sizes(const accerl_arch* arch, int64_t* weights_bytes, int64_t* 
     return ACCERL_OK;
 }
 
-int accerl_policy_create(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
-                         const float* quant_scales, int64_t n_scales, accerl_policy** out) {
-    if (!out) return fail(ACCERL_EINVAL, "out is NULL");
-    *out = nullptr;
+// Host half of policy creation: parse, check, build the plan and the host image of the constants.
+static int create_host(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
+                       const float* quant_scales, int64_t n_scales, accerl_policy* pol, std::vector<char>& cst) {
     if (!weights) return fail(ACCERL_EINVAL, "weights is NULL");
-    accerl_policy* pol = new (std::nothrow) accerl_policy();
-    if (!pol) return fail(ACCERL_ENOMEM, "host allocation failed");
     int rc = parse_arch(arch, pol->P);
-    if (rc) { delete pol; return rc; }
+    if (rc) return rc;
     pol->arch = *arch;
-    if (weights_bytes != pol->P.weights_bytes) {
-        rc = fail(ACCERL_EINVAL, "weight blob is %lld bytes, arch needs %lld", (long long)weights_bytes, (long long)pol->P.weights_bytes);
-        delete pol; return rc;
-    }
-    if (n_scales != pol->P.n_scales || (n_scales > 0 && !quant_scales)) {
-        rc = fail(ACCERL_EINVAL, "scale array has %lld entries, arch needs %lld", (long long)n_scales, (long long)pol->P.n_scales);
-        delete pol; return rc;
-    }
+    if (weights_bytes != pol->P.weights_bytes)
+        return fail(ACCERL_EINVAL, "weight blob is %lld bytes, arch needs %lld", (long long)weights_bytes, (long long)pol->P.weights_bytes);
+    if (n_scales != pol->P.n_scales || (n_scales > 0 && !quant_scales))
+        return fail(ACCERL_EINVAL, "scale array has %lld entries, arch needs %lld", (long long)n_scales, (long long)pol->P.n_scales);
     if (arch->precision == ACCERL_INT8) {
         for (const auto& t : pol->P.tensors) {
             if (t.wt != W_I8) continue;
             const int8_t* w = (const int8_t*)((const char*)weights + t.w_off);
             for (int64_t i = 0; i < t.rows * t.cols; ++i)
-                if (w[i] == -128) { rc = fail(ACCERL_EINVAL, "int8 weight -128 is outside the symmetric range"); delete pol; return rc; }
+                if (w[i] == -128) return fail(ACCERL_EINVAL, "int8 weight -128 is outside the symmetric range");
         }
     }
     Builder B{arch, pol->P, (const char*)weights, quant_scales, pol, {}};
     rc = build_plan(B);
-    if (rc) { delete pol; return rc; }
-    hipError_t e = hipGetDevice(&pol->device);
-    if (e == hipSuccess) e = hipMalloc((void**)&pol->consts, B.cst.size() + 256);
-    if (e == hipSuccess) e = hipMemcpy(pol->consts, B.cst.data(), B.cst.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        rc = fail(e == hipErrorOutOfMemory ? ACCERL_ENOMEM : ACCERL_EHIP, "uploading constants: %s", hipGetErrorString(e));
-        (void)hipGetLastError();
-        if (pol->consts) (void)hipFree(pol->consts);
-        delete pol;
-        return rc;
-    }
+    if (rc) return rc;
+    cst.swap(B.cst);
     pol->ws_per_state = 0;
     for (const auto& b : pol->bufs) pol->ws_per_state += b.per_state;
     // states per pass: keep one pass's intermediates near the size of the on-package cache
@@ -956,7 +996,64 @@ int accerl_policy_create(const accerl_arch* arch, const void* weights, int64_t w
         pol->chunk = ch;
     }
     if (const char* env = getenv("ACCERL_CHUNK")) { const long v = atol(env); if (v > 0) pol->chunk = v; }
+    return ACCERL_OK;
+}
+
+int accerl_policy_create(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
+                         const float* quant_scales, int64_t n_scales, accerl_policy** out) {
+    if (!out) return fail(ACCERL_EINVAL, "out is NULL");
+    *out = nullptr;
+    accerl_policy* pol = new (std::nothrow) accerl_policy();
+    if (!pol) return fail(ACCERL_ENOMEM, "host allocation failed");
+    std::vector<char> cst;
+    int rc = create_host(arch, weights, weights_bytes, quant_scales, n_scales, pol, cst);
+    if (rc) { delete pol; return rc; }
+    hipError_t e = hipGetDevice(&pol->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&pol->consts, cst.size() + 256);
+    if (e == hipSuccess) e = hipMemcpy(pol->consts, cst.data(), cst.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        rc = fail(e == hipErrorOutOfMemory ? ACCERL_ENOMEM : ACCERL_EHIP, "uploading constants: %s", hipGetErrorString(e));
+        (void)hipGetLastError();
+        if (pol->consts) (void)hipFree(pol->consts);
+        delete pol;
+        return rc;
+    }
     *out = pol;
+    return ACCERL_OK;
+}
+
+int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
+                         const float* quant_scales, int64_t n_scales, char* text, int64_t cap) {
+    if (!text || cap < 1) return fail(ACCERL_EINVAL, "text buffer is NULL or empty");
+    accerl_policy pol;
+    std::vector<char> cst;
+    int rc = create_host(arch, weights, weights_bytes, quant_scales, n_scales, &pol, cst);
+    if (rc) return rc;
+    std::string out;
+    char line[512];
+    static const char* kinds[] = {"mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample"};
+    snprintf(line, sizeof line, "steps=%d const_bytes=%lld ws_bytes_per_state=%lld chunk=%lld\n", (int)pol.steps.size(),
+             (long long)cst.size(), (long long)pol.ws_per_state, (long long)pol.chunk);
+    out += line;
+    for (size_t i = 0; i < pol.steps.size(); ++i) {
+        const Step& s = pol.steps[i];
+        if (s.kind == ST_CONV) {
+            const ConvParams& c = s.cp;
+            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16) + (long)c.G * c.tile_stride;
+            snprintf(line, sizeof line,
+                     "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d planar=%d NT=%d KS=%d "
+                     "k_steps=%d RD=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld vec_ok=%d\n",
+                     i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode, c.planar,
+                     s.NT, s.KS, c.k_steps, s.RD, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.vec_ok);
+        } else if (s.kind == ST_GEMM) {
+            snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d\n",
+                     i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu);
+        } else {
+            snprintf(line, sizeof line, "step %zu %s layer=%d\n", i, kinds[s.kind], s.layer);
+        }
+        out += line;
+    }
+    snprintf(text, (size_t)cap, "%s", out.c_str());
     return ACCERL_OK;
 }
 

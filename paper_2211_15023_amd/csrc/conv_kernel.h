@@ -1,0 +1,429 @@
+// Convolution as an implicit GEMM on the matrix cores, one kernel family for the int8 student and
+// the bf16 teacher.
+//
+// Work split.  A workgroup (4 wavefronts) walks over batches of G images.  For a batch it stages the
+// input tiles in LDS once and every wavefront then takes tiles of 16 output pixels -- numbered across
+// the G images, so ragged image sizes (81 or 49 pixels) do not waste MFMA columns -- as the columns of
+// 16x16 MFMA tiles whose rows are output channels.  K runs over (ky, kx, c) of the channels-last tile:
+// for a fixed ky the taps of a pixel are one contiguous run, read as 16-byte chunks (64 int8 or 32 bf16
+// per MFMA step).  uint8 observations with an 8-wide kernel stay planar instead ([c][y][x], K order
+// (c, ky, kx)): a chunk is then 8 bytes of row ky and 8 of row ky+1, and the frame is staged by a
+// plain contiguous copy.
+//
+// Weights are the A operand.  When they fit (KS steps x NT tiles x 4 VGPRs) they live in registers for
+// the whole kernel, so LDS only feeds the pixel operand: one 16-byte read per lane serves NT MFMAs.
+// Otherwise they sit in LDS in fragment order.
+//
+// Latency.  The global loads of batch i+1 are issued into registers before the MFMA work of batch i
+// and written to LDS afterwards, so HBM latency hides behind compute inside one workgroup.
+//
+// Epilogue.  MFMA row i of tile t is output channel 4*NT*(i/4) + 4*t + i%4 (weights are laid out that
+// way on the host), so a lane ends up with 4*NT consecutive channels of one pixel: bias, requantize
+// (or bias/ReLU/bf16 rounding), optional residual join, one contiguous store.
+#pragma once
+#include "accerl_internal.h"
+
+namespace accerl {
+
+constexpr int CONV_THREADS = 256;
+constexpr int CONV_WAVES = CONV_THREADS / 64;
+constexpr int CONV_PT = 2;   // pixel tiles per wave iteration
+
+__device__ __forceinline__ uint32_t relu_i8x4(uint32_t x) {
+    const uint32_t neg = (x & 0x80808080u) >> 7;
+    return x & ~(neg * 0xffu);
+}
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t x) {
+    const uint32_t neg = (x & 0x80008000u) >> 15;
+    return x & ~(neg * 0xffffu);
+}
+__device__ __forceinline__ float bf2f(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ uint32_t f2bf(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return u >> 16;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; }
+
+template <int RD>
+__device__ __forceinline__ v4i read_chunk(const char* p, int pitch) {
+    if constexpr (RD == 16) {
+        return *(const v4i*)p;
+    } else if constexpr (RD == 8) {
+        typedef int v2i __attribute__((ext_vector_type(2)));
+        const v2i a = *(const v2i*)p, b = *(const v2i*)(p + 8);
+        return (v4i){a[0], a[1], b[0], b[1]};
+    } else if constexpr (RD == 4) {
+        const int* q = (const int*)p;
+        return (v4i){q[0], q[1], q[2], q[3]};
+    } else {   // planar: 8 bytes of this row, 8 of the next
+        const int* q0 = (const int*)p;
+        const int* q1 = (const int*)(p + pitch);
+        return (v4i){q0[0], q0[1], q1[0], q1[1]};
+    }
+}
+
+template <int EL, int NT, int KS, int RD, int PF>
+__global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int ESZ = (EL == EL_I8) ? 1 : 2;
+    constexpr int KSR = KS > 0 ? KS : 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int pix = p.planar ? 1 : p.Cs_in * ESZ;          // bytes per stored input pixel
+    char* wl = smem;                                        // KS == 0: weight fragments + chunk offsets
+    int* koff_lds = (int*)(smem + p.w_bytes);
+    char* tiles = (KS > 0) ? smem : smem + p.w_bytes + p.k_steps * 16;
+
+    auto chunk_off = [&](int q) -> int {
+        if (p.planar) {
+            const int half = p.k >> 1;
+            const int c = q / half, kyp = q - c * half;
+            return (c < p.Cin_real) ? c * p.plane_stride + 2 * kyp * p.pitch : 0;
+        }
+        const int ky = q / p.cpr, cx = q - ky * p.cpr;
+        return (ky < p.k) ? ky * p.pitch + cx * 16 : 0;
+    };
+
+    // ---- once per workgroup: weights (registers or LDS), chunk offsets, tiles filled with padding
+    v4i wreg[KSR][NT];
+    int koffr[KSR];
+    if constexpr (KS > 0) {
+#pragma unroll
+        for (int st = 0; st < KS; ++st) {
+            koffr[st] = chunk_off(4 * st + g);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) wreg[st][t] = ((const v4i*)p.wfrag)[(st * NT + t) * 64 + lane];
+        }
+    } else {
+        for (int i = tid; i < p.w_bytes / 16; i += CONV_THREADS) ((v4i*)wl)[i] = ((const v4i*)p.wfrag)[i];
+        for (int i = tid; i < p.k_steps * 4; i += CONV_THREADS) koff_lds[i] = chunk_off(i);
+    }
+    {
+        const int padv = (EL == EL_I8 && p.src_u8) ? (int)0x80808080u : 0;
+        for (int i = tid; i < p.G * p.tile_stride / 4; i += CONV_THREADS) ((int*)tiles)[i] = padv;
+    }
+
+    // per-lane epilogue constants: channels 4*NT*g .. 4*NT*g + 4*NT - 1
+    v4i bi[NT];
+    v4f bfl[NT];
+    v4f ml[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if constexpr (EL == EL_I8) {
+            bi[t] = *(const v4i*)((const int*)p.bias + 4 * NT * g + 4 * t);
+            ml[t] = *(const v4f*)(p.mult + 4 * NT * g + 4 * t);
+        } else {
+            bfl[t] = *(const v4f*)((const float*)p.bias + 4 * NT * g + 4 * t);
+        }
+    }
+
+    const int band = blockIdx.x;
+    const int oy0 = band * p.TH;
+    const int th = (p.Ho - oy0 < p.TH) ? (p.Ho - oy0) : p.TH;
+    const int iy0 = oy0 * p.s - p.pad;
+    const int n_pix = th * p.Wo;
+    const int row_bytes_img = p.W * pix;
+    const int lead = p.pad * pix;
+    const int64_t n_batch = (p.B + p.G - 1) / p.G;
+
+    // ---- staging: issue the loads of a batch into registers / write them to LDS
+    v4i pre[PF];
+    auto prefetch = [&](int64_t batch) {
+        const int64_t b0 = batch * p.G;
+        const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
+        const int total = gc * p.units_img;
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            const int u = tid + i * CONV_THREADS;
+            if (u >= total) break;
+            const int img = (int)fdiv((uint32_t)u, p.magic_units);
+            const int w = u - img * p.units_img;
+            if (p.mode == CM_FLAT) {
+                pre[i] = *(const v4i*)((const char*)p.in + (b0 + img) * (int64_t)p.img_bytes + w * 16);
+            } else if (p.mode == CM_ROWS) {
+                const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
+                const int o = (w - rr * p.row_units) * 16;
+                const int iy = iy0 + rr;
+                const bool rin = iy >= 0 && iy < p.H;
+                const char* srow = (const char*)p.in + ((b0 + img) * (int64_t)p.H + iy) * row_bytes_img - lead;
+                v4i v = {0, 0, 0, 0};
+                if (rin) {
+                    if (p.vec_ok) {
+                        if (o >= lead && o < lead + row_bytes_img) v = *(const v4i*)(srow + o);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int oo = o + 4 * e;
+                            if (oo >= lead && oo < lead + row_bytes_img) v[e] = *(const int*)(srow + oo);
+                        }
+                    }
+                }
+                pre[i] = v;
+            } else {   // CM_U8T: one dword (4 pixels) from each channel plane
+                const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
+                const int xq = w - rr * p.row_units;
+                const int iy = iy0 + rr;
+                v4i v = {0, 0, 0, 0};
+                if (iy >= 0 && iy < p.H) {
+                    const uint8_t* src = (const uint8_t*)p.in + (b0 + img) * (int64_t)p.Cin_real * p.H * p.W + iy * p.W + 4 * xq;
+                    const int plane = p.H * p.W;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (c < p.Cin_real) v[c] = *(const int*)(src + c * plane);
+                }
+                pre[i] = v;
+            }
+        }
+    };
+    auto commit = [&](int64_t batch) {
+        const int64_t b0 = batch * p.G;
+        const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
+        const int total = gc * p.units_img;
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            const int u = tid + i * CONV_THREADS;
+            if (u >= total) break;
+            const int img = (int)fdiv((uint32_t)u, p.magic_units);
+            const int w = u - img * p.units_img;
+            char* tile = tiles + img * p.tile_stride;
+            v4i v = pre[i];
+            if (p.mode != CM_U8T) {
+                if (p.src_u8) {
+                    if constexpr (EL == EL_I8) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] ^= (int)0x80808080u;
+                    }
+                } else if (p.relu_in) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = (int)((EL == EL_I8) ? relu_i8x4((uint32_t)v[e]) : relu_bf16x2((uint32_t)v[e]));
+                }
+                if (p.mode == CM_FLAT) {
+                    *(v4i*)(tile + w * 16) = v;
+                } else {
+                    const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
+                    *(v4i*)(tile + rr * p.pitch + (w - rr * p.row_units) * 16) = v;
+                }
+            } else {
+                const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
+                const int xq = w - rr * p.row_units;
+                const int iy = iy0 + rr;
+                if (iy < 0 || iy >= p.H) continue;            // stays padding
+                const uint32_t P0 = (uint32_t)v[0], P1 = (uint32_t)v[1], P2 = (uint32_t)v[2], P3 = (uint32_t)v[3];
+                const uint32_t lo01 = __builtin_amdgcn_perm(P1, P0, 0x05010400u);
+                const uint32_t hi01 = __builtin_amdgcn_perm(P1, P0, 0x07030602u);
+                const uint32_t lo23 = __builtin_amdgcn_perm(P3, P2, 0x05010400u);
+                const uint32_t hi23 = __builtin_amdgcn_perm(P3, P2, 0x07030602u);
+                uint32_t px[4];
+                px[0] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+                px[1] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+                px[2] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+                px[3] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+                if constexpr (EL == EL_I8) {
+                    uint32_t* d = (uint32_t*)(tile + rr * p.pitch + lead + 16 * xq);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) d[e] = px[e] ^ 0x80808080u;
+                } else {
+                    uint32_t* d = (uint32_t*)(tile + rr * p.pitch + lead + 32 * xq);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        uint32_t c0 = p.lut[px[e] & 0xff], c1 = p.lut[(px[e] >> 8) & 0xff];
+                        uint32_t c2 = p.lut[(px[e] >> 16) & 0xff], c3 = p.lut[px[e] >> 24];
+                        if (p.Cin_real < 2) c1 = 0;
+                        if (p.Cin_real < 3) c2 = 0;
+                        if (p.Cin_real < 4) c3 = 0;
+                        d[2 * e] = c0 | (c1 << 16);
+                        d[2 * e + 1] = c2 | (c3 << 16);
+                    }
+                }
+            }
+        }
+    };
+
+    int64_t batch = blockIdx.y;
+    if (batch < n_batch) prefetch(batch);
+    __syncthreads();   // padding fill (and LDS weights) visible before the first commit / compute
+    for (; batch < n_batch; batch += gridDim.y) {
+        commit(batch);
+        __syncthreads();
+        if (batch + gridDim.y < n_batch) prefetch(batch + gridDim.y);
+
+        const int64_t b0 = batch * p.G;
+        const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
+        const int total_pix = gc * n_pix;
+        const int n_tiles = (total_pix + 15) >> 4;
+        for (int t0 = wave * CONV_PT; t0 < n_tiles; t0 += CONV_WAVES * CONV_PT) {
+            int pb[CONV_PT], ppix[CONV_PT];
+#pragma unroll
+            for (int u = 0; u < CONV_PT; ++u) {
+                int pp = (t0 + u) * 16 + j;
+                ppix[u] = pp;
+                if (pp >= total_pix) pp = total_pix - 1;     // clamp to a valid pixel; result not stored
+                const int img = (int)fdiv((uint32_t)pp, p.magic_npix);
+                const int rem = pp - img * n_pix;
+                const int ty = (int)fdiv((uint32_t)rem, p.magic_wo), ox = rem - ty * p.Wo;
+                pb[u] = img * p.tile_stride + ty * p.s * p.pitch + ox * p.s * pix;
+            }
+            v4i acc_i[CONV_PT][NT];
+            v4f acc_f[CONV_PT][NT];
+#pragma unroll
+            for (int u = 0; u < CONV_PT; ++u)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    acc_i[u][t] = (v4i){0, 0, 0, 0};
+                    acc_f[u][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+                }
+            auto step = [&](const v4i (&a)[NT], int off) {
+                v4i bq[CONV_PT];
+#pragma unroll
+                for (int u = 0; u < CONV_PT; ++u) bq[u] = read_chunk<RD>(tiles + pb[u] + off, p.pitch);
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int u = 0; u < CONV_PT; ++u) {
+                        if constexpr (EL == EL_I8) {
+                            acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t], bq[u], acc_i[u][t], 0, 0, 0);
+                        } else {
+                            acc_f[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(v8bf, a[t]), __builtin_bit_cast(v8bf, bq[u]), acc_f[u][t], 0, 0, 0);
+                        }
+                    }
+            };
+            if constexpr (KS > 0) {
+#pragma unroll
+                for (int st = 0; st < KS; ++st) step(wreg[st], koffr[st]);
+            } else {
+                for (int st = 0; st < p.k_steps; ++st) {
+                    v4i a[NT];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) a[t] = *(const v4i*)(wl + ((st * NT + t) * 64 + lane) * 16);
+                    step(a, koff_lds[st * 4 + g]);
+                }
+            }
+            // ---- epilogue: this lane owns channels c0 .. c0 + 4*NT - 1 of its pixel
+#pragma unroll
+            for (int u = 0; u < CONV_PT; ++u) {
+                if (ppix[u] >= total_pix) continue;
+                const int img = (int)fdiv((uint32_t)ppix[u], p.magic_npix);
+                const int rem = ppix[u] - img * n_pix;
+                const int ty = (int)fdiv((uint32_t)rem, p.magic_wo), ox = rem - ty * p.Wo;
+                const int64_t opix = ((b0 + img) * p.Ho + (oy0 + ty)) * p.Wo + ox;
+                const int c0 = 4 * NT * g;
+                const int64_t o = opix * p.Cs_out + c0;
+                if constexpr (EL == EL_I8) {
+                    uint32_t pk[NT];
+                    uint32_t xr[NT];
+                    if (p.res) {
+#pragma unroll
+                        for (int t = 0; t < NT; ++t)
+                            xr[t] = (c0 + 4 * t < p.Cs_out) ? *(const uint32_t*)((const int8_t*)p.res + o + 4 * t) : 0u;
+                    }
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        v4i v;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = acc_i[u][t][r] + bi[t][r];
+                        if (p.tap_acc && c0 + 4 * t < p.Cs_out) *(v4i*)(p.tap_acc + o + 4 * t) = v;
+                        uint32_t w = 0;
+                        if (p.res) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const float tr = (float)(int)(int8_t)(xr[t] >> (8 * r)) * p.r;
+                                float y = rintf(fmaf((float)v[r], ml[t][r], tr));
+                                y = fmaxf(fminf(y, 127.0f), -127.0f);
+                                w |= (uint32_t)(uint8_t)(int8_t)(int)y << (8 * r);
+                            }
+                        } else {
+                            const float lo = p.relu ? 0.0f : -127.0f;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                float y = rintf((float)v[r] * ml[t][r]);
+                                y = fmaxf(fminf(y, 127.0f), lo);
+                                w |= (uint32_t)(uint8_t)(int8_t)(int)y << (8 * r);
+                            }
+                        }
+                        pk[t] = w;
+                    }
+                    int8_t* dst = (int8_t*)p.out + o;
+                    if (NT == 4 && c0 + 16 <= p.Cs_out) {
+                        *(v4i*)dst = (v4i){(int)pk[0], (int)pk[1 % NT], (int)pk[2 % NT], (int)pk[3 % NT]};
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < NT; ++t)
+                            if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(dst + 4 * t) = pk[t];
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        if (c0 + 4 * t >= p.Cs_out) continue;
+                        float v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = acc_f[u][t][r] + bfl[t][r];
+                        if (p.res) {
+                            const uint32_t* xr = (const uint32_t*)((const uint16_t*)p.res + o + 4 * t);
+                            const uint32_t x0 = xr[0], x1 = xr[1];
+                            v[0] = bf2f(x0 & 0xffffu) + v[0];
+                            v[1] = bf2f(x0 >> 16) + v[1];
+                            v[2] = bf2f(x1 & 0xffffu) + v[2];
+                            v[3] = bf2f(x1 >> 16) + v[3];
+                        }
+                        if (p.relu) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.0f);
+                        }
+                        uint32_t* d = (uint32_t*)((uint16_t*)p.out + o + 4 * t);
+                        d[0] = f2bf(v[0]) | (f2bf(v[1]) << 16);
+                        d[1] = f2bf(v[2]) | (f2bf(v[3]) << 16);
+                    }
+                }
+            }
+        }
+        __syncthreads();   // every wave is done reading the tiles before the next commit overwrites them
+    }
+}
+
+
+template <int EL, int NT, int KS, int RD, int PF>
+hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
+    auto kfn = conv_kernel<EL, NT, KS, RD, PF>;
+    static size_t set_lds = 0;   // per instantiation: raise the dynamic LDS limit when needed
+    if (lds > set_lds) {
+        hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        set_lds = lds;
+    }
+    kfn<<<grid, dim3(CONV_THREADS), lds, s>>>(p);
+    return hipGetLastError();
+}
+
+template <int EL, int NT, int KS, int RD>
+hipError_t conv_go_pf(const ConvParams& p, int pf, dim3 grid, size_t lds, hipStream_t s) {
+    return pf <= 8 ? conv_go<EL, NT, KS, RD, 8>(p, grid, lds, s) : conv_go<EL, NT, KS, RD, 16>(p, grid, lds, s);
+}
+
+// register-resident weight variants: (element, NT, KS, RD)
+#define ACCERL_REG_VARIANTS_I8(X)                                                                  \
+    X(EL_I8, 1, 1, 4) X(EL_I8, 1, 1, 8) X(EL_I8, 1, 2, 8) X(EL_I8, 1, 2, 16) X(EL_I8, 1, 3, 16)   \
+    X(EL_I8, 1, 4, 2) X(EL_I8, 2, 4, 2) X(EL_I8, 2, 4, 16) X(EL_I8, 4, 8, 16) X(EL_I8, 4, 9, 16)
+#define ACCERL_REG_VARIANTS_BF16(X)                                                                \
+    X(EL_BF16, 1, 2, 8) X(EL_BF16, 1, 5, 16) X(EL_BF16, 2, 5, 16) X(EL_BF16, 2, 8, 16) X(EL_BF16, 2, 9, 16)
+
+template <int EL, int NT>
+hipError_t conv_go_generic(const ConvParams& p, int rd, int pf, dim3 grid, size_t lds, hipStream_t s) {
+    switch (rd) {
+        case 16: return conv_go_pf<EL, NT, 0, 16>(p, pf, grid, lds, s);
+        case 8: return conv_go_pf<EL, NT, 0, 8>(p, pf, grid, lds, s);
+        case 4: return conv_go_pf<EL, NT, 0, 4>(p, pf, grid, lds, s);
+        default: return conv_go_pf<EL, NT, 0, 2>(p, pf, grid, lds, s);
+    }
+}
+
+// one translation unit per family keeps the build parallel
+hipError_t conv_launch_reg_i8(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_reg_bf16(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_gen_i8(const ConvParams& p, int NT, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_gen_bf16(const ConvParams& p, int NT, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+
+}  // namespace accerl
