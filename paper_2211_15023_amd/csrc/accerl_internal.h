@@ -42,7 +42,7 @@ hipError_t launch_mlp_i8(const MlpParams& p, hipStream_t s);
 hipError_t launch_quant_obs(const float* obs, int64_t B, int D, int Dpad, float inv_s0, int8_t* out, hipStream_t s);
 
 // ---------------------------------------------------------------- convolution (input tiles in LDS, MFMA)
-enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2 };
+enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2, CM_S2D = 3 };
 struct ConvParams {
     const void* in;          // NHWC elements, or NCHW uint8 observations (modes FLAT+planar, U8T)
     void* out;               // NHWC elements [B, Ho, Wo, Cs_out]
@@ -62,16 +62,16 @@ struct ConvParams {
     int n_bands;
     int in_rows;             // (TH-1)*s + k
     int pitch;               // bytes per LDS input row
-    int plane_stride;        // planar: bytes between channel planes in LDS
-    int tile_stride;         // LDS bytes per image tile including read slack (multiple of 16)
+    int tile_stride;         // LDS bytes per image tile (multiple of 16)
+    int lds_tiles;           // LDS bytes of all G tiles plus read slack
     int cpr;                 // 16-byte chunks per kernel row
     int k_steps;             // MFMA steps (4 chunks each)
     int w_bytes;             // bytes of wfrag
     int relu_in;             // max(x, 0) on load
     int relu;                // teacher: ReLU after bias; student: lower clamp 0
     int src_u8;              // source is uint8 observations
-    int mode;                // ConvMode: how a tile is staged
-    int planar;              // chunk = 8 bytes of kernel row ky and 8 of ky+1, per channel plane
+    int mode;                // ConvMode: how a tile is staged (S2D: H, W describe the uint8 source frame,
+                             // k, s, pitch, Cs_in the 2x2 stride-1 problem over 64-byte blocks)
     int G;                   // images staged and multiplied together
     int img_bytes;           // FLAT: contiguous bytes per image
     int units_img;           // 16-byte staging units per image tile
@@ -82,9 +82,10 @@ struct ConvParams {
     int groups;              // grid.y
 };
 // KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.
-// RD: 16 / 8 / 4 = alignment of a chunk read in LDS, 2 = planar (two 8-byte rows).
-hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, hipStream_t s);
-bool conv_has_reg_variant(Elem el, int NT, int KS, int RD);
+// RD: alignment (16 / 8 / 4) of a chunk read in LDS.  PF: staging units per lane the kernel holds.
+hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s);
+bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, int* KS, int* PF);
+int conv_pixel_tiles(int NT);
 
 // ---------------------------------------------------------------- max pooling on NHWC
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,

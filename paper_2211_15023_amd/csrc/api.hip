@@ -151,7 +151,7 @@ struct Step {
     int in_buf = -1, out_buf = -1, res_buf = -1;   // -1 = the caller's states (in) / none
     ConvParams cp{};
     Elem el = EL_I8;
-    int NT = 1, KS = 0, RD = 16;
+    int NT = 1, KS = 0, RD = 16, PF = 16;
     GemmParams gp{};
     GemmEpi epi = EPI_REQUANT;
     GemmF32Params fp{};
@@ -252,75 +252,84 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     const int NT = (Cout <= 16) ? 1 : (Cout <= 32) ? 2 : (Cout <= 64) ? 4 : 0;
     if (!NT) return fail(ACCERL_EUNSUPPORTED, "layer %d: more than 64 output channels", layer);
     const int Ho = out_hw(H, k, s, pad), Wo = out_hw(W, k, s, pad);
-    // uint8 frames under an 8-wide kernel stay planar: no transposition, plain contiguous staging
-    const bool planar = src_u8 && el == EL_I8 && k == 8 && pad == 0 && ((Cin * H * W) % 16) == 0;
-    const int Cs_in = planar ? 1 : (int)up(Cin, 4);
-    const int pix = planar ? 1 : Cs_in * esz;
-    const int run = k * pix;                        // bytes of one kernel row of one pixel
-    const int cpr = planar ? 0 : (run + 15) / 16;
-    const int chunks = planar ? Cin * (k / 2) : k * cpr;
+    // uint8 frames under a 2s x 2s kernel at stride s = 4: space-to-depth (4x4x4 blocks of 64 bytes),
+    // the layer becomes a 2x2 stride-1 convolution over (H/4) x (W/4) blocks
+    const bool s2d = src_u8 && el == EL_I8 && Cin == 4 && s == 4 && k == 8 && pad == 0 && (H % 4) == 0 && ((Cin * H * W) % 16) == 0;
+    const int Cs_in = s2d ? 64 : (int)up(Cin, 4);
+    const int pix = Cs_in * esz;
+    const int kk = s2d ? 2 : k, ss = s2d ? 1 : s;   // the kernel size and stride the MFMA loop sees
+    const int Wt = s2d ? W / 4 : W, Ht = s2d ? H / 4 : H;
+    const int run = kk * pix;                       // bytes of one kernel row of one pixel
+    const int cpr = (run + 15) / 16;
+    const int chunks = kk * cpr;
     const int k_steps = (chunks + 3) / 4;
     const int w_bytes = k_steps * NT * 1024;
-    const int row_bytes = W * pix;
+    const int row_bytes = Wt * pix;
 
     ConvParams& c = st.cp;
     int mode, pitch;
-    if (planar) { mode = CM_FLAT; pitch = W; }
+    if (s2d) { mode = CM_S2D; pitch = row_bytes; }
     else if (src_u8) { mode = CM_U8T; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
     else if (pad == 0 && ((H * row_bytes) % 16) == 0) { mode = CM_FLAT; pitch = row_bytes; }
     else { mode = CM_ROWS; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
+    const bool whole = mode == CM_FLAT || mode == CM_S2D;   // tiles are whole images, staged contiguously
 
-    const int RD = planar ? 2 : [&] { int al = gcd_int(16, gcd_int(s * pix, pitch)); return al < 4 ? 4 : al; }();
-    const int KS = conv_has_reg_variant(el, NT, k_steps, RD) ? k_steps : 0;
-    const int w_lds = KS > 0 ? 0 : w_bytes + k_steps * 16;
+    int RD = [&] { int al = gcd_int(16, gcd_int(ss * pix, pitch)); return al < 4 ? 4 : al; }();
+    const int w_lds_max = w_bytes + k_steps * 16;
+    const int PT = conv_pixel_tiles(NT);
 
-    // band height: units to stage per tile <= 4096 (16 per thread), LDS within budget
+    // band height: units to stage per tile <= 4096 (16 per lane), LDS within budget
     const int lds_cap = 160 * 1024 - 2048;
     int budget = 64 * 1024;
-    if (w_lds + 36 * 1024 > budget) budget = w_lds + 36 * 1024;
+    if (w_lds_max + 40 * 1024 > budget) budget = w_lds_max + 40 * 1024;
     if (budget > lds_cap) budget = lds_cap;
-    auto rows_of = [&](int th) { return (th - 1) * s + k; };
-    auto tile_of = [&](int th) { return (int)up(planar ? (int64_t)Cin * H * W + 16 : (int64_t)rows_of(th) * pitch + 32, 16); };
+    auto rows_of = [&](int th) { return (th - 1) * ss + kk; };
+    auto tile_of = [&](int th) { return whole ? Ht * row_bytes : (int)up((int64_t)rows_of(th) * pitch, 16); };
     auto units_of = [&](int th) {
-        if (planar) return Cin * H * W / 16;
-        if (mode == CM_FLAT) return H * row_bytes / 16;
+        if (whole) return tile_of(th) / 16;
         if (mode == CM_U8T) return rows_of(th) * (W / 4);
         return rows_of(th) * (pitch / 16);
     };
     int TH = Ho;
-    if (mode != CM_FLAT) {
-        while (TH > 1 && (units_of(TH) > 4096 || w_lds + tile_of(TH) > budget)) --TH;
+    if (!whole) {
+        while (TH > 1 && (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + 32 > budget)) --TH;
         const int nb = (Ho + TH - 1) / TH;
         TH = (Ho + nb - 1) / nb;
     }
-    if (units_of(TH) > 4096 || w_lds + tile_of(TH) > lds_cap)
+    if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + 32 > lds_cap)
         return fail(ACCERL_EUNSUPPORTED, "layer %d: one input band does not fit the staging limits", layer);
     const int n_bands = (Ho + TH - 1) / TH;
     const int tile_stride = tile_of(TH), units_img = units_of(TH), n_pix = TH * Wo;
-    // images per batch: best use of the 8 pixel-tile slots (4 waves x 2 tiles) a workgroup fills per round
+    // images per batch: best use of the pixel-tile slots (4 waves x PT tiles of 16) a workgroup fills per round
     int G = 1;
     if (n_bands == 1) {
+        const int slot = 4 * PT * 16;
+        const int unit_cap = (mode == CM_S2D) ? 2048 : 2560;
         double best = -1.0;
         for (int gg = 1; gg <= 16; ++gg) {
-            if (gg * units_img > 4096 || w_lds + gg * tile_stride > budget) break;
-            const int slots = (gg * n_pix + 127) / 128 * 128;
-            const double util = (double)gg * n_pix / slots;
+            if (gg > 1 && (gg * units_img > unit_cap || w_lds_max + gg * tile_stride + 32 > budget)) break;
+            const double util = (double)gg * n_pix / ((gg * n_pix + slot - 1) / slot * slot);
             if (util > best + 0.02) { best = util; G = gg; }
         }
     }
+    int KS = 0, PF = 16;
+    if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, &KS, &PF))
+        return fail(ACCERL_EUNSUPPORTED, "layer %d: no convolution kernel covers this shape", layer);
+    if (!KS && RD == 8) RD = 4;                     // the generic LDS-weight kernels read chunks at 16 or 4 bytes
     c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_out;
-    c.k = k; c.s = s; c.pad = pad; c.TH = TH; c.n_bands = n_bands;
-    c.in_rows = planar ? H : rows_of(TH); c.pitch = pitch; c.plane_stride = H * W; c.tile_stride = tile_stride;
+    c.k = kk; c.s = ss; c.pad = pad; c.TH = TH; c.n_bands = n_bands;
+    c.in_rows = whole ? Ht : rows_of(TH); c.pitch = pitch; c.tile_stride = tile_stride;
+    c.lds_tiles = G * tile_stride + 32;
     c.cpr = cpr; c.k_steps = k_steps; c.w_bytes = w_bytes;
     c.relu_in = relu_in; c.relu = relu; c.src_u8 = src_u8;
-    c.mode = mode; c.planar = planar; c.G = G;
-    c.img_bytes = planar ? Cin * H * W : H * row_bytes;
+    c.mode = mode; c.G = G;
+    c.img_bytes = s2d ? Cin * H * W : H * row_bytes;
     c.units_img = units_img;
     c.row_units = mode == CM_U8T ? W / 4 : pitch / 16;
     c.vec_ok = ((pad * pix) % 16 == 0) && (row_bytes % 16 == 0);
     c.magic_npix = magic_of(n_pix); c.magic_wo = magic_of(Wo);
     c.magic_units = magic_of(units_img); c.magic_rowunits = magic_of(c.row_units);
-    st.NT = NT; st.KS = KS; st.RD = RD;
+    st.NT = NT; st.KS = KS; st.RD = RD; st.PF = PF;
     st.out_elems = (int64_t)Ho * Wo * Cs_out;
     st.acc_elems = el == EL_I8 ? st.out_elems : 0;
 
@@ -339,15 +348,18 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
                 char* dst = frag.data() + ((size_t)(stp * NT + tt) * 64 + lane) * 16;
                 for (int e = 0; e < epc; ++e) {
                     int ci, ky, kx;
-                    if (planar) {
-                        ci = q / (k / 2);
-                        ky = 2 * (q % (k / 2)) + (e >> 3);
-                        kx = e & 7;
-                    } else {
-                        ky = q / cpr;
-                        const int idx = (q - ky * cpr) * epc + e;   // element index inside the kernel row run
-                        kx = idx / Cs_in;
-                        ci = idx - kx * Cs_in;
+                    {
+                        const int kby = q / cpr;
+                        const int idx = (q - kby * cpr) * epc + e;  // element index inside the kernel row run
+                        const int kbx = idx / Cs_in, rem = idx - kbx * Cs_in;
+                        if (s2d) {                                  // block byte (dy, c, dx) of block (kby, kbx)
+                            ky = 4 * kby + (rem >> 4);
+                            ci = (rem >> 2) & 3;
+                            kx = 4 * kbx + (rem & 3);
+                            if (kby >= 2 || kbx >= 2) continue;
+                        } else {
+                            ky = kby; kx = kbx; ci = rem;
+                        }
                     }
                     if (ky >= k || kx >= k || ci >= Cin) continue;
                     const int64_t src = (((int64_t)n * Cin + ci) * k + ky) * k + kx;
@@ -867,7 +879,7 @@ int run(accerl_policy* p, const Call& c) {
                         if (groups > n_batch) groups = n_batch;
                         cp.groups = (int)groups;
                     }
-                    e = launch_conv(cp, s.el, s.NT, s.KS, s.RD, c.stream);
+                    e = launch_conv(cp, s.el, s.NT, s.KS, s.RD, s.PF, c.stream);
                     break;
                 }
                 case ST_MAXPOOL:
@@ -1039,12 +1051,12 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
         const Step& s = pol.steps[i];
         if (s.kind == ST_CONV) {
             const ConvParams& c = s.cp;
-            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16) + (long)c.G * c.tile_stride;
+            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16) + (long)c.lds_tiles;
             snprintf(line, sizeof line,
-                     "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d planar=%d NT=%d KS=%d "
-                     "k_steps=%d RD=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld vec_ok=%d\n",
-                     i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode, c.planar,
-                     s.NT, s.KS, c.k_steps, s.RD, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.vec_ok);
+                     "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
+                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld vec_ok=%d\n",
+                     i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
+                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.vec_ok);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu);

@@ -6,9 +6,10 @@
 // the G images, so ragged image sizes (81 or 49 pixels) do not waste MFMA columns -- as the columns of
 // 16x16 MFMA tiles whose rows are output channels.  K runs over (ky, kx, c) of the channels-last tile:
 // for a fixed ky the taps of a pixel are one contiguous run, read as 16-byte chunks (64 int8 or 32 bf16
-// per MFMA step).  uint8 observations with an 8-wide kernel stay planar instead ([c][y][x], K order
-// (c, ky, kx)): a chunk is then 8 bytes of row ky and 8 of row ky+1, and the frame is staged by a
-// plain contiguous copy.
+// per MFMA step).  uint8 observations under a kernel of 2s x 2s at stride s = 4 (the 8x8/4 first layer
+// of the paper's networks) are staged space-to-depth: every 4x4x4 block of the frame becomes one
+// 64-byte "pixel", the layer turns into a 2x2 stride-1 convolution, and staging is a contiguous read
+// of the planar frame with each dword scattered to its block (LDS addresses precomputed per lane).
 //
 // Weights are the A operand.  When they fit (KS steps x NT tiles x 4 VGPRs) they live in registers for
 // the whole kernel, so LDS only feeds the pixel operand: one 16-byte read per lane serves NT MFMAs.
@@ -27,7 +28,6 @@ namespace accerl {
 
 constexpr int CONV_THREADS = 256;
 constexpr int CONV_WAVES = CONV_THREADS / 64;
-constexpr int CONV_PT = 2;   // pixel tiles per wave iteration
 
 __device__ __forceinline__ uint32_t relu_i8x4(uint32_t x) {
     const uint32_t neg = (x & 0x80808080u) >> 7;
@@ -45,43 +45,37 @@ __device__ __forceinline__ uint32_t f2bf(float x) {
     return u >> 16;
 }
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; }
+// LDS swizzle for tiles whose pixels are 64 bytes apart: the 16-byte slot inside each 64-byte group is
+// XORed with bits 9:8 of the (tile-relative) address, so that 16 consecutive pixels spread over all banks
+__device__ __forceinline__ int swz64(int a) { return a ^ (((a >> 8) & 3) << 4); }
 
 template <int RD>
-__device__ __forceinline__ v4i read_chunk(const char* p, int pitch) {
+__device__ __forceinline__ v4i read_chunk(const char* p) {
     if constexpr (RD == 16) {
         return *(const v4i*)p;
     } else if constexpr (RD == 8) {
         typedef int v2i __attribute__((ext_vector_type(2)));
         const v2i a = *(const v2i*)p, b = *(const v2i*)(p + 8);
         return (v4i){a[0], a[1], b[0], b[1]};
-    } else if constexpr (RD == 4) {
+    } else {
         const int* q = (const int*)p;
         return (v4i){q[0], q[1], q[2], q[3]};
-    } else {   // planar: 8 bytes of this row, 8 of the next
-        const int* q0 = (const int*)p;
-        const int* q1 = (const int*)(p + pitch);
-        return (v4i){q0[0], q0[1], q1[0], q1[1]};
     }
 }
 
-template <int EL, int NT, int KS, int RD, int PF>
-__global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
+template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT>
+__global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int ESZ = (EL == EL_I8) ? 1 : 2;
     constexpr int KSR = KS > 0 ? KS : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, g = lane >> 4;
-    const int pix = p.planar ? 1 : p.Cs_in * ESZ;          // bytes per stored input pixel
+    const int pix = p.Cs_in * ESZ;                          // bytes per stored input pixel
     char* wl = smem;                                        // KS == 0: weight fragments + chunk offsets
     int* koff_lds = (int*)(smem + p.w_bytes);
     char* tiles = (KS > 0) ? smem : smem + p.w_bytes + p.k_steps * 16;
 
     auto chunk_off = [&](int q) -> int {
-        if (p.planar) {
-            const int half = p.k >> 1;
-            const int c = q / half, kyp = q - c * half;
-            return (c < p.Cin_real) ? c * p.plane_stride + 2 * kyp * p.pitch : 0;
-        }
         const int ky = q / p.cpr, cx = q - ky * p.cpr;
         return (ky < p.k) ? ky * p.pitch + cx * 16 : 0;
     };
@@ -102,7 +96,27 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
     }
     {
         const int padv = (EL == EL_I8 && p.src_u8) ? (int)0x80808080u : 0;
-        for (int i = tid; i < p.G * p.tile_stride / 4; i += CONV_THREADS) ((int*)tiles)[i] = padv;
+        for (int i = tid; i < p.lds_tiles / 4; i += CONV_THREADS) ((int*)tiles)[i] = padv;
+    }
+
+    // space-to-depth staging: LDS byte address of each dword this lane will stage (same for every batch)
+    constexpr int NTAB = (MODE == CM_S2D) ? PF * 4 : 1;
+    int s2d_dst[NTAB];
+    if constexpr (MODE == CM_S2D) {
+        const int w4 = p.W >> 2, plane4 = p.H * w4;            // dwords per source row / per plane
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            const int u = tid + i * CONV_THREADS;
+            const int img = (int)fdiv((uint32_t)u, p.magic_units);
+            const int wu = u - img * p.units_img;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int d = wu * 4 + e;
+                const int c = d / plane4, rem = d - c * plane4;
+                const int y = rem / w4, bx = rem - y * w4;
+                s2d_dst[i * 4 + e] = img * p.tile_stride + swz64(((y >> 2) * w4 + bx) * 64 + ((y & 3) * 4 + c) * 4);
+            }
+        }
     }
 
     // per-lane epilogue constants: channels 4*NT*g .. 4*NT*g + 4*NT - 1
@@ -130,49 +144,59 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
 
     // ---- staging: issue the loads of a batch into registers / write them to LDS
     v4i pre[PF];
+    // All loads are unconditional (out-of-range units re-read a valid address and are dropped at commit
+    // time): loads under divergent branches would be serialised by the wait-count insertion.
     auto prefetch = [&](int64_t batch) {
         const int64_t b0 = batch * p.G;
         const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
-        const int total = gc * p.units_img;
+        const int last = gc * p.units_img - 1;
+        if constexpr (MODE == CM_FLAT || MODE == CM_S2D) {
+            // a batch of images is one contiguous range, read unit by unit
+            const char* src = (const char*)p.in + b0 * (int64_t)p.img_bytes;
 #pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int u = tid + i * CONV_THREADS;
-            if (u >= total) break;
-            const int img = (int)fdiv((uint32_t)u, p.magic_units);
-            const int w = u - img * p.units_img;
-            if (p.mode == CM_FLAT) {
-                pre[i] = *(const v4i*)((const char*)p.in + (b0 + img) * (int64_t)p.img_bytes + w * 16);
-            } else if (p.mode == CM_ROWS) {
+            for (int i = 0; i < PF; ++i) {
+                const int u = min(tid + i * CONV_THREADS, last);
+                pre[i] = *(const v4i*)(src + (uint32_t)u * 16u);
+            }
+        } else if constexpr (MODE == CM_ROWS) {
+#pragma unroll
+            for (int i = 0; i < PF; ++i) {
+                const int u = min(tid + i * CONV_THREADS, last);
+                const int img = (int)fdiv((uint32_t)u, p.magic_units);
+                const int w = u - img * p.units_img;
                 const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
-                const int o = (w - rr * p.row_units) * 16;
+                const int o = (w - rr * p.row_units) * 16 - lead;          // byte offset inside the image row
                 const int iy = iy0 + rr;
                 const bool rin = iy >= 0 && iy < p.H;
-                const char* srow = (const char*)p.in + ((b0 + img) * (int64_t)p.H + iy) * row_bytes_img - lead;
-                v4i v = {0, 0, 0, 0};
-                if (rin) {
-                    if (p.vec_ok) {
-                        if (o >= lead && o < lead + row_bytes_img) v = *(const v4i*)(srow + o);
-                    } else {
+                const char* srow = (const char*)p.in + ((b0 + img) * (int64_t)p.H + min(max(iy, 0), p.H - 1)) * row_bytes_img;
+                v4i v;
+                if (p.vec_ok) {
+                    v = *(const v4i*)(srow + min(max(o, 0), row_bytes_img - 16));
+                    if (!(rin && o >= 0 && o < row_bytes_img)) v = (v4i){0, 0, 0, 0};
+                } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int oo = o + 4 * e;
-                            if (oo >= lead && oo < lead + row_bytes_img) v[e] = *(const int*)(srow + oo);
-                        }
+                    for (int e = 0; e < 4; ++e) {
+                        const int oo = o + 4 * e;
+                        const int x = *(const int*)(srow + min(max(oo, 0), row_bytes_img - 4));
+                        v[e] = (rin && oo >= 0 && oo < row_bytes_img) ? x : 0;
                     }
                 }
                 pre[i] = v;
-            } else {   // CM_U8T: one dword (4 pixels) from each channel plane
+            }
+        } else {   // CM_U8T: one dword (4 pixels) from each channel plane
+            const int plane = p.H * p.W;
+#pragma unroll
+            for (int i = 0; i < PF; ++i) {
+                const int u = min(tid + i * CONV_THREADS, last);
+                const int img = (int)fdiv((uint32_t)u, p.magic_units);
+                const int w = u - img * p.units_img;
                 const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
                 const int xq = w - rr * p.row_units;
-                const int iy = iy0 + rr;
-                v4i v = {0, 0, 0, 0};
-                if (iy >= 0 && iy < p.H) {
-                    const uint8_t* src = (const uint8_t*)p.in + (b0 + img) * (int64_t)p.Cin_real * p.H * p.W + iy * p.W + 4 * xq;
-                    const int plane = p.H * p.W;
+                const int iy = min(max(iy0 + rr, 0), p.H - 1);             // rows outside the image are dropped at commit
+                const uint8_t* src = (const uint8_t*)p.in + (b0 + img) * (int64_t)p.Cin_real * plane + iy * p.W + 4 * xq;
+                v4i v;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (c < p.Cin_real) v[c] = *(const int*)(src + c * plane);
-                }
+                for (int c = 0; c < 4; ++c) v[c] = *(const int*)(src + min(c, p.Cin_real - 1) * plane);
                 pre[i] = v;
             }
         }
@@ -185,11 +209,11 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
         for (int i = 0; i < PF; ++i) {
             const int u = tid + i * CONV_THREADS;
             if (u >= total) break;
-            const int img = (int)fdiv((uint32_t)u, p.magic_units);
-            const int w = u - img * p.units_img;
-            char* tile = tiles + img * p.tile_stride;
             v4i v = pre[i];
-            if (p.mode != CM_U8T) {
+            if constexpr (MODE == CM_S2D) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) *(int*)(tiles + s2d_dst[i * 4 + e]) = v[e] ^ (int)0x80808080u;
+            } else if constexpr (MODE != CM_U8T) {
                 if (p.src_u8) {
                     if constexpr (EL == EL_I8) {
 #pragma unroll
@@ -200,13 +224,18 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
                     for (int e = 0; e < 4; ++e)
                         v[e] = (int)((EL == EL_I8) ? relu_i8x4((uint32_t)v[e]) : relu_bf16x2((uint32_t)v[e]));
                 }
-                if (p.mode == CM_FLAT) {
-                    *(v4i*)(tile + w * 16) = v;
+                if constexpr (MODE == CM_FLAT) {
+                    *(v4i*)(tiles + u * 16) = v;               // tiles of a batch are contiguous like the images
                 } else {
+                    const int img = (int)fdiv((uint32_t)u, p.magic_units);
+                    const int w = u - img * p.units_img;
                     const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
-                    *(v4i*)(tile + rr * p.pitch + (w - rr * p.row_units) * 16) = v;
+                    *(v4i*)(tiles + img * p.tile_stride + rr * p.pitch + (w - rr * p.row_units) * 16) = v;
                 }
             } else {
+                const int img = (int)fdiv((uint32_t)u, p.magic_units);
+                const int w = u - img * p.units_img;
+                char* tile = tiles + img * p.tile_stride;
                 const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
                 const int xq = w - rr * p.row_units;
                 const int iy = iy0 + rr;
@@ -254,35 +283,37 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
         const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
         const int total_pix = gc * n_pix;
         const int n_tiles = (total_pix + 15) >> 4;
-        for (int t0 = wave * CONV_PT; t0 < n_tiles; t0 += CONV_WAVES * CONV_PT) {
-            int pb[CONV_PT], ppix[CONV_PT];
+        for (int t0 = wave * PT; t0 < n_tiles; t0 += CONV_WAVES * PT) {
+            int pb[PT], pimg[PT], ppix[PT];   // tile-relative pixel offset, tile offset, pixel number
 #pragma unroll
-            for (int u = 0; u < CONV_PT; ++u) {
+            for (int u = 0; u < PT; ++u) {
                 int pp = (t0 + u) * 16 + j;
                 ppix[u] = pp;
                 if (pp >= total_pix) pp = total_pix - 1;     // clamp to a valid pixel; result not stored
                 const int img = (int)fdiv((uint32_t)pp, p.magic_npix);
                 const int rem = pp - img * n_pix;
                 const int ty = (int)fdiv((uint32_t)rem, p.magic_wo), ox = rem - ty * p.Wo;
-                pb[u] = img * p.tile_stride + ty * p.s * p.pitch + ox * p.s * pix;
+                pb[u] = ty * p.s * p.pitch + ox * p.s * pix;
+                pimg[u] = img * p.tile_stride;
             }
-            v4i acc_i[CONV_PT][NT];
-            v4f acc_f[CONV_PT][NT];
+            v4i acc_i[PT][NT];
+            v4f acc_f[PT][NT];
 #pragma unroll
-            for (int u = 0; u < CONV_PT; ++u)
+            for (int u = 0; u < PT; ++u)
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    acc_i[u][t] = (v4i){0, 0, 0, 0};
-                    acc_f[u][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+                    if constexpr (EL == EL_I8) acc_i[u][t] = bi[t];   // the bias rides in the accumulator
+                    else acc_f[u][t] = bfl[t];
                 }
             auto step = [&](const v4i (&a)[NT], int off) {
-                v4i bq[CONV_PT];
+                v4i bq[PT];
 #pragma unroll
-                for (int u = 0; u < CONV_PT; ++u) bq[u] = read_chunk<RD>(tiles + pb[u] + off, p.pitch);
+                for (int u = 0; u < PT; ++u)
+                    bq[u] = read_chunk<RD>(tiles + pimg[u] + (MODE == CM_S2D ? swz64(pb[u] + off) : pb[u] + off));
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
-                    for (int u = 0; u < CONV_PT; ++u) {
+                    for (int u = 0; u < PT; ++u) {
                         if constexpr (EL == EL_I8) {
                             acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t], bq[u], acc_i[u][t], 0, 0, 0);
                         } else {
@@ -304,7 +335,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
             }
             // ---- epilogue: this lane owns channels c0 .. c0 + 4*NT - 1 of its pixel
 #pragma unroll
-            for (int u = 0; u < CONV_PT; ++u) {
+            for (int u = 0; u < PT; ++u) {
                 if (ppix[u] >= total_pix) continue;
                 const int img = (int)fdiv((uint32_t)ppix[u], p.magic_npix);
                 const int rem = ppix[u] - img * n_pix;
@@ -317,31 +348,31 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
                     uint32_t xr[NT];
                     if (p.res) {
 #pragma unroll
-                        for (int t = 0; t < NT; ++t)
-                            xr[t] = (c0 + 4 * t < p.Cs_out) ? *(const uint32_t*)((const int8_t*)p.res + o + 4 * t) : 0u;
+                        for (int t = 0; t < NT; ++t)   // lanes past the last channel re-read a valid group (not stored)
+                            xr[t] = *(const uint32_t*)((const int8_t*)p.res + opix * p.Cs_out + min(c0 + 4 * t, p.Cs_out - 4));
                     }
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
-                        v4i v;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = acc_i[u][t][r] + bi[t][r];
+                        const v4i v = acc_i[u][t];
                         if (p.tap_acc && c0 + 4 * t < p.Cs_out) *(v4i*)(p.tap_acc + o + 4 * t) = v;
                         uint32_t w = 0;
                         if (p.res) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
                                 const float tr = (float)(int)(int8_t)(xr[t] >> (8 * r)) * p.r;
-                                float y = rintf(fmaf((float)v[r], ml[t][r], tr));
-                                y = fmaxf(fminf(y, 127.0f), -127.0f);
-                                w |= (uint32_t)(uint8_t)(int8_t)(int)y << (8 * r);
+                                const float y = __builtin_amdgcn_fmed3f(rintf(fmaf((float)v[r], ml[t][r], tr)), -127.0f, 127.0f);
+                                w |= ((uint32_t)(int)y & 0xffu) << (8 * r);
                             }
+                        } else if (p.relu) {
+                            // clamp(rint(y), 0, 127): the pack instruction rounds to nearest even and saturates at 0
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                w = __builtin_amdgcn_cvt_pk_u8_f32(fminf((float)v[r] * ml[t][r], 127.0f), r, w);
                         } else {
-                            const float lo = p.relu ? 0.0f : -127.0f;
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                float y = rintf((float)v[r] * ml[t][r]);
-                                y = fmaxf(fminf(y, 127.0f), lo);
-                                w |= (uint32_t)(uint8_t)(int8_t)(int)y << (8 * r);
+                                const float y = __builtin_amdgcn_fmed3f(rintf((float)v[r] * ml[t][r]), -127.0f, 127.0f);
+                                w |= ((uint32_t)(int)y & 0xffu) << (8 * r);
                             }
                         }
                         pk[t] = w;
@@ -355,15 +386,23 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
                             if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(dst + 4 * t) = pk[t];
                     }
                 } else {
+                    uint32_t xres[NT][2];
+                    if (p.res) {
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {   // unconditional: lanes past the last channel re-read a valid group
+                            const uint32_t* xr = (const uint32_t*)((const uint16_t*)p.res + opix * p.Cs_out + min(c0 + 4 * t, p.Cs_out - 4));
+                            xres[t][0] = xr[0];
+                            xres[t][1] = xr[1];
+                        }
+                    }
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         if (c0 + 4 * t >= p.Cs_out) continue;
                         float v[4];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = acc_f[u][t][r] + bfl[t][r];
+                        for (int r = 0; r < 4; ++r) v[r] = acc_f[u][t][r];
                         if (p.res) {
-                            const uint32_t* xr = (const uint32_t*)((const uint16_t*)p.res + o + 4 * t);
-                            const uint32_t x0 = xr[0], x1 = xr[1];
+                            const uint32_t x0 = xres[t][0], x1 = xres[t][1];
                             v[0] = bf2f(x0 & 0xffffu) + v[0];
                             v[1] = bf2f(x0 >> 16) + v[1];
                             v[2] = bf2f(x1 & 0xffffu) + v[2];
@@ -385,9 +424,9 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(ConvParams p) {
 }
 
 
-template <int EL, int NT, int KS, int RD, int PF>
+template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT>
 hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
-    auto kfn = conv_kernel<EL, NT, KS, RD, PF>;
+    auto kfn = conv_kernel<EL, NT, KS, RD, MODE, PF, PT>;
     static size_t set_lds = 0;   // per instantiation: raise the dynamic LDS limit when needed
     if (lds > set_lds) {
         hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -398,32 +437,39 @@ hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int EL, int NT, int KS, int RD>
-hipError_t conv_go_pf(const ConvParams& p, int pf, dim3 grid, size_t lds, hipStream_t s) {
-    return pf <= 8 ? conv_go<EL, NT, KS, RD, 8>(p, grid, lds, s) : conv_go<EL, NT, KS, RD, 16>(p, grid, lds, s);
-}
+// Pixel tiles per wave iteration: 4 when a layer has 4 channel tiles (each weight fragment read from
+// LDS then serves 4 MFMAs), else 2.
+constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
 
-// register-resident weight variants: (element, NT, KS, RD)
-#define ACCERL_REG_VARIANTS_I8(X)                                                                  \
-    X(EL_I8, 1, 1, 4) X(EL_I8, 1, 1, 8) X(EL_I8, 1, 2, 8) X(EL_I8, 1, 2, 16) X(EL_I8, 1, 3, 16)   \
-    X(EL_I8, 1, 4, 2) X(EL_I8, 2, 4, 2) X(EL_I8, 2, 4, 16) X(EL_I8, 4, 8, 16) X(EL_I8, 4, 9, 16)
-#define ACCERL_REG_VARIANTS_BF16(X)                                                                \
-    X(EL_BF16, 1, 2, 8) X(EL_BF16, 1, 5, 16) X(EL_BF16, 2, 5, 16) X(EL_BF16, 2, 8, 16) X(EL_BF16, 2, 9, 16)
+// Tuned variants: (element, NT, KS, RD, staging mode, PF).  KS > 0 keeps the weights in registers and
+// unrolls that many MFMA steps; KS = 0 reads them from LDS for any number of steps.
+#define ACCERL_TUNED_I8(X)                                                                              \
+    X(EL_I8, 2, 4, 16, CM_S2D, 8) X(EL_I8, 1, 4, 16, CM_S2D, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
+    X(EL_I8, 4, 0, 16, CM_FLAT, 10) X(EL_I8, 2, 4, 16, CM_FLAT, 8) X(EL_I8, 1, 2, 16, CM_FLAT, 8)      \
+    X(EL_I8, 1, 1, 8, CM_FLAT, 8) X(EL_I8, 1, 1, 4, CM_U8T, 8) X(EL_I8, 1, 2, 8, CM_ROWS, 8)           \
+    X(EL_I8, 1, 3, 16, CM_ROWS, 8)
+#define ACCERL_TUNED_BF16(X)                                                                            \
+    X(EL_BF16, 2, 8, 16, CM_U8T, 8) X(EL_BF16, 1, 2, 8, CM_U8T, 8) X(EL_BF16, 1, 5, 16, CM_ROWS, 16)   \
+    X(EL_BF16, 2, 5, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 8) \
+    X(EL_BF16, 4, 0, 16, CM_FLAT, 8)
 
+// everything else: weights in LDS, chunk reads at 16- or 4-byte alignment, 16 staging units per lane
 template <int EL, int NT>
-hipError_t conv_go_generic(const ConvParams& p, int rd, int pf, dim3 grid, size_t lds, hipStream_t s) {
-    switch (rd) {
-        case 16: return conv_go_pf<EL, NT, 0, 16>(p, pf, grid, lds, s);
-        case 8: return conv_go_pf<EL, NT, 0, 8>(p, pf, grid, lds, s);
-        case 4: return conv_go_pf<EL, NT, 0, 4>(p, pf, grid, lds, s);
-        default: return conv_go_pf<EL, NT, 0, 2>(p, pf, grid, lds, s);
+hipError_t conv_go_generic(const ConvParams& p, int rd, dim3 grid, size_t lds, hipStream_t s) {
+    const bool a16 = rd == 16;
+    constexpr int PT = conv_pt(NT);
+    switch (p.mode) {
+        case CM_FLAT: return a16 ? conv_go<EL, NT, 0, 16, CM_FLAT, 16, PT>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_FLAT, 16, PT>(p, grid, lds, s);
+        case CM_ROWS: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWS, 16, PT>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWS, 16, PT>(p, grid, lds, s);
+        case CM_U8T: return a16 ? conv_go<EL, NT, 0, 16, CM_U8T, 16, PT>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_U8T, 16, PT>(p, grid, lds, s);
+        default: return hipErrorInvalidValue;
     }
 }
 
 // one translation unit per family keeps the build parallel
-hipError_t conv_launch_reg_i8(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
-hipError_t conv_launch_reg_bf16(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
-hipError_t conv_launch_gen_i8(const ConvParams& p, int NT, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
-hipError_t conv_launch_gen_bf16(const ConvParams& p, int NT, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_tuned_i8(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_tuned_bf16(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_gen_i8(const ConvParams& p, int NT, int RD, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_gen_bf16(const ConvParams& p, int NT, int RD, dim3 grid, size_t lds, hipStream_t s);
 
 }  // namespace accerl

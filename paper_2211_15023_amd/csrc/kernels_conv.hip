@@ -3,26 +3,41 @@
 
 namespace accerl {
 
-bool conv_has_reg_variant(Elem el, int NT, int KS, int RD) {
-#define X(E, N, K, R) if (el == E && NT == N && KS == K && RD == R) return true;
-    ACCERL_REG_VARIANTS_I8(X)
-    ACCERL_REG_VARIANTS_BF16(X)
+// Pick the kernel variant for a layer: a tuned variant with register-resident weights (KS = k_steps)
+// if one is listed, else a tuned LDS-weight variant, else the generic family.  Returns the staging
+// depth (units per lane) of the chosen kernel in *PF, 0 in *KS for LDS weights; false if `pf` units
+// per lane cannot be staged by any kernel.
+bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, int* KS, int* PF) {
+    int best_reg = 0, best_lds = 0;
+#define X(E, N, K, R, M, P)                                                                  \
+    if (el == E && NT == N && RD == R && mode == M && pf <= P) {                             \
+        if (K == k_steps && (best_reg == 0 || P < best_reg)) best_reg = P;                   \
+        if (K == 0 && (best_lds == 0 || P < best_lds)) best_lds = P;                         \
+    }
+    ACCERL_TUNED_I8(X)
+    ACCERL_TUNED_BF16(X)
 #undef X
-    return false;
+    if (best_reg) { *KS = k_steps; *PF = best_reg; return true; }
+    if (best_lds) { *KS = 0; *PF = best_lds; return true; }
+    if (pf > 16 || mode == CM_S2D) return false;
+    *KS = 0; *PF = 16;
+    return true;
 }
 
-hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, hipStream_t s) {
+int conv_pixel_tiles(int NT) { return conv_pt(NT); }
+
+hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
-    const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16) + (size_t)p.G * p.tile_stride;
-    const int pf = (p.G * p.units_img + CONV_THREADS - 1) / CONV_THREADS;
-    if (pf > 16 || p.groups < 1) return hipErrorInvalidValue;
+    const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16) + (size_t)p.lds_tiles;
+    if ((p.G * p.units_img + CONV_THREADS - 1) / CONV_THREADS > PF || p.groups < 1) return hipErrorInvalidValue;
     dim3 grid((unsigned)p.n_bands, (unsigned)p.groups);
-    if (KS > 0) {
-        if (!conv_has_reg_variant(el, NT, KS, RD)) return hipErrorInvalidValue;
-        return el == EL_I8 ? conv_launch_reg_i8(p, NT, KS, RD, pf, grid, lds, s) : conv_launch_reg_bf16(p, NT, KS, RD, pf, grid, lds, s);
-    }
-    if (el == EL_I8) return conv_launch_gen_i8(p, NT, RD, pf, grid, lds, s);
-    if (el == EL_BF16) return conv_launch_gen_bf16(p, NT, RD, pf, grid, lds, s);
+    hipError_t e = el == EL_I8 ? conv_launch_tuned_i8(p, NT, KS, RD, PF, grid, lds, s)
+                               : conv_launch_tuned_bf16(p, NT, KS, RD, PF, grid, lds, s);
+    if (e != hipErrorNotFound) return e;
+    if (KS != 0 || PF != 16) return hipErrorInvalidValue;
+    const int rd = RD == 16 ? 16 : 4;
+    if (el == EL_I8) return conv_launch_gen_i8(p, NT, rd, grid, lds, s);
+    if (el == EL_BF16) return conv_launch_gen_bf16(p, NT, rd, grid, lds, s);
     return hipErrorInvalidValue;
 }
 
