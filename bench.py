@@ -139,7 +139,7 @@ def main():
         per_step_ms = p["total_ms"] / args.steps
         ent = dict(step=p["step"], kind=p["kind"], layer=p["layer"], ms_per_step=round(per_step_ms, 5),
                    launches_per_step=p["launches"] / args.steps)
-        if p["kind"] in ("conv", "gemm"):
+        if p["kind"] in ("conv", "gemm", "heads"):
             m = macs.get(p["layer"], 0)
             if ns.layers[p["layer"]]["kind"] == "resblock" if p["layer"] < len(ns.layers) else False:
                 m //= 2
@@ -148,7 +148,7 @@ def main():
     dom = max(breakdown, key=lambda e: e["ms_per_step"])
     launches = dom["launches_per_step"]
     avg_launch_s = dom["ms_per_step"] * 1e-3 / launches
-    if dom["kind"] in ("conv", "gemm"):
+    if dom["kind"] in ("conv", "gemm", "heads"):
         m = macs[dom["layer"]]
         if dom["layer"] < len(ns.layers) and ns.layers[dom["layer"]]["kind"] == "resblock":
             m //= 2

@@ -183,7 +183,7 @@ int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, 
  * plan, on the stream of that call.  accerl_profile_end waits for those events and returns, per
  * plan step, the summed elapsed time in ms, the number of launches, the arch layer the step
  * belongs to (n_layers = heads / sampler) and the step kind (0 fused MLP, 1 observation quantizer,
- * 2 convolution, 3 MFMA dense, 4 fp32 dense, 5 max pooling, 6 LSTM packing, 7 sampler).  All arrays
+ * 2 convolution, 3 MFMA dense, 4 fp32 dense, 5 max pooling, 6 LSTM packing, 7 sampler, 8 heads + sampler).  All arrays
  * are HOST, `cap` entries each; *n_steps receives the number of plan steps (also on ACCERL_EINVAL
  * when cap is too small).
  */

@@ -209,7 +209,7 @@ def accerl_actor_forward_debug(handle, states, layer, tap, out, stream=None):
                                                      out.numel() * out.element_size(), _stream(stream)))
 
 
-STEP_KINDS = ("mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample")
+STEP_KINDS = ("mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample", "heads")
 
 
 def accerl_profile_begin(handle):

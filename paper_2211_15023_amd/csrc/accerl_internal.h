@@ -42,9 +42,9 @@ hipError_t launch_mlp_i8(const MlpParams& p, hipStream_t s);
 hipError_t launch_quant_obs(const float* obs, int64_t B, int D, int Dpad, float inv_s0, int8_t* out, hipStream_t s);
 
 // ---------------------------------------------------------------- convolution (input tiles in LDS, MFMA)
-enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2, CM_S2D = 3 };
+enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2 };
 struct ConvParams {
-    const void* in;          // NHWC elements, or NCHW uint8 observations (modes FLAT+planar, U8T)
+    const void* in;          // NHWC elements, or NCHW uint8 observations (mode U8T)
     void* out;               // NHWC elements [B, Ho, Wo, Cs_out]
     const void* res;         // residual stream, same shape as out (NULL = none)
     int32_t* tap_acc;        // int32 [B, Ho, Wo, Cs_out] (NULL = off)
@@ -55,7 +55,7 @@ struct ConvParams {
     int64_t B;
     int H, W;                // input image
     int Cin_real;            // channels present in the source
-    int Cs_in;               // stored channels per input pixel (multiple of 4; planar: 1)
+    int Cs_in;               // stored channels per input pixel (multiple of 4)
     int Ho, Wo, Cs_out;
     int k, s, pad;
     int TH;                  // output rows per band
@@ -70,8 +70,7 @@ struct ConvParams {
     int relu_in;             // max(x, 0) on load
     int relu;                // teacher: ReLU after bias; student: lower clamp 0
     int src_u8;              // source is uint8 observations
-    int mode;                // ConvMode: how a tile is staged (S2D: H, W describe the uint8 source frame,
-                             // k, s, pitch, Cs_in the 2x2 stride-1 problem over 64-byte blocks)
+    int mode;                // ConvMode: how a tile is staged
     int G;                   // images staged and multiplied together
     int img_bytes;           // FLAT: contiguous bytes per image
     int units_img;           // 16-byte staging units per image tile
@@ -117,6 +116,21 @@ struct GemmParams {
     int Hd;                  // lstm hidden
 };
 hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s);
+
+// policy heads + sampler in one kernel (K up to 16 MFMA steps; wider inputs go through launch_gemm + launch_sample)
+struct HeadsParams {
+    const void* x;           // [B, Kp] elements
+    const void* wfrag;       // [n_tiles][k_steps][64 lanes][16 B]
+    const void* bias;        // int32 or fp32, [n_tiles*16]
+    const float* mult;       // [n_tiles*16] dequantisation (int8)
+    const float* uniforms;
+    float* logits; float* value; int32_t* action;
+    int32_t* tap_acc;        // int32 [B, A+1] (NULL = off)
+    int64_t B;
+    int Kp_bytes, k_steps, A, relu_in;
+};
+bool heads_supported(int k_steps, int Kp_bytes);
+hipError_t launch_heads(const HeadsParams& p, Elem el, hipStream_t s);
 
 // fp32 dense layer (teacher MLP): out = relu?(x W^T + b); heads variant writes logits/value
 struct GemmF32Params {

@@ -143,7 +143,7 @@ int parse_arch(const accerl_arch* a, Parsed& P) {
 }
 
 // ------------------------------------------------------------------ plan
-enum StepKind { ST_MLP, ST_QUANT_OBS, ST_CONV, ST_GEMM, ST_GEMM_F32, ST_MAXPOOL, ST_LSTM_PACK, ST_SAMPLE };
+enum StepKind { ST_MLP, ST_QUANT_OBS, ST_CONV, ST_GEMM, ST_GEMM_F32, ST_MAXPOOL, ST_LSTM_PACK, ST_SAMPLE, ST_HEADS };
 
 struct Step {
     StepKind kind;
@@ -252,13 +252,10 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     const int NT = (Cout <= 16) ? 1 : (Cout <= 32) ? 2 : (Cout <= 64) ? 4 : 0;
     if (!NT) return fail(ACCERL_EUNSUPPORTED, "layer %d: more than 64 output channels", layer);
     const int Ho = out_hw(H, k, s, pad), Wo = out_hw(W, k, s, pad);
-    // uint8 frames under a 2s x 2s kernel at stride s = 4: space-to-depth (4x4x4 blocks of 64 bytes),
-    // the layer becomes a 2x2 stride-1 convolution over (H/4) x (W/4) blocks
-    const bool s2d = src_u8 && el == EL_I8 && Cin == 4 && s == 4 && k == 8 && pad == 0 && (H % 4) == 0 && ((Cin * H * W) % 16) == 0;
-    const int Cs_in = s2d ? 64 : (int)up(Cin, 4);
+    const int Cs_in = (int)up(Cin, 4);
     const int pix = Cs_in * esz;
-    const int kk = s2d ? 2 : k, ss = s2d ? 1 : s;   // the kernel size and stride the MFMA loop sees
-    const int Wt = s2d ? W / 4 : W, Ht = s2d ? H / 4 : H;
+    const int kk = k, ss = s;
+    const int Wt = W, Ht = H;
     const int run = kk * pix;                       // bytes of one kernel row of one pixel
     const int cpr = (run + 15) / 16;
     const int chunks = kk * cpr;
@@ -268,11 +265,10 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
 
     ConvParams& c = st.cp;
     int mode, pitch;
-    if (s2d) { mode = CM_S2D; pitch = row_bytes; }
-    else if (src_u8) { mode = CM_U8T; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
+    if (src_u8) { mode = CM_U8T; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
     else if (pad == 0 && ((H * row_bytes) % 16) == 0) { mode = CM_FLAT; pitch = row_bytes; }
     else { mode = CM_ROWS; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
-    const bool whole = mode == CM_FLAT || mode == CM_S2D;   // tiles are whole images, staged contiguously
+    const bool whole = mode == CM_FLAT;             // tiles are whole images, staged contiguously
 
     int RD = [&] { int al = gcd_int(16, gcd_int(ss * pix, pitch)); return al < 4 ? 4 : al; }();
     const int w_lds_max = w_bytes + k_steps * 16;
@@ -304,7 +300,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     int G = 1;
     if (n_bands == 1) {
         const int slot = 4 * PT * 16;
-        const int unit_cap = (mode == CM_S2D) ? 2048 : 2560;
+        const int unit_cap = 2560;
         double best = -1.0;
         for (int gg = 1; gg <= 16; ++gg) {
             if (gg > 1 && (gg * units_img > unit_cap || w_lds_max + gg * tile_stride + 32 > budget)) break;
@@ -323,7 +319,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     c.cpr = cpr; c.k_steps = k_steps; c.w_bytes = w_bytes;
     c.relu_in = relu_in; c.relu = relu; c.src_u8 = src_u8;
     c.mode = mode; c.G = G;
-    c.img_bytes = s2d ? Cin * H * W : H * row_bytes;
+    c.img_bytes = H * row_bytes;
     c.units_img = units_img;
     c.row_units = mode == CM_U8T ? W / 4 : pitch / 16;
     c.vec_ok = ((pad * pix) % 16 == 0) && (row_bytes % 16 == 0);
@@ -352,14 +348,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
                         const int kby = q / cpr;
                         const int idx = (q - kby * cpr) * epc + e;  // element index inside the kernel row run
                         const int kbx = idx / Cs_in, rem = idx - kbx * Cs_in;
-                        if (s2d) {                                  // block byte (dy, c, dx) of block (kby, kbx)
-                            ky = 4 * kby + (rem >> 4);
-                            ci = (rem >> 2) & 3;
-                            kx = 4 * kbx + (rem & 3);
-                            if (kby >= 2 || kbx >= 2) continue;
-                        } else {
-                            ky = kby; kx = kbx; ci = rem;
-                        }
+                        ky = kby; kx = kbx; ci = rem;
                     }
                     if (ky >= k || kx >= k || ci >= Cin) continue;
                     const int64_t src = (((int64_t)n * Cin + ci) * k + ky) * k + kx;
@@ -740,9 +729,14 @@ int build_plan(Builder& B) {
             for (int n = 0; n < N; ++n) bf[n] = B.bias(t)[n];
             st.o_bias = B.put(bf.data(), bf.size() * 4);
         }
-        pol->steps.push_back(st);
-        Step ss; ss.kind = ST_SAMPLE; ss.layer = a->n_layers;
-        pol->steps.push_back(ss);
+        if (heads_supported(k_steps, gp.Kp_bytes)) {
+            st.kind = ST_HEADS;                     // one kernel: heads GEMM + sampler
+            pol->steps.push_back(st);
+        } else {
+            pol->steps.push_back(st);
+            Step ss; ss.kind = ST_SAMPLE; ss.layer = a->n_layers;
+            pol->steps.push_back(ss);
+        }
     }
     return ACCERL_OK;
 }
@@ -781,6 +775,7 @@ int find_tap_step(const accerl_policy* p, int layer, int tap, bool& is_acc) {
     for (int i = 0; i < (int)p->steps.size(); ++i) {
         const Step& s = p->steps[i];
         if (s.kind == ST_SAMPLE || s.layer != layer) continue;
+        if (!is_acc && s.kind == ST_HEADS) continue;
         if (want_sub >= 0 && s.sub != want_sub) continue;
         if (is_acc && s.acc_elems == 0) continue;
         if (!is_acc && s.out_buf < 0) continue;
@@ -923,6 +918,18 @@ int run(accerl_policy* p, const Call& c) {
                 case ST_SAMPLE:
                     e = launch_sample(logits, uni, action, n, A, c.stream);
                     break;
+                case ST_HEADS: {
+                    HeadsParams hp{};
+                    hp.x = bufp(s.in_buf);
+                    hp.wfrag = p->consts + s.o_w;
+                    hp.bias = p->consts + s.o_bias;
+                    hp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
+                    hp.uniforms = uni; hp.logits = logits; hp.value = value; hp.action = action;
+                    hp.tap_acc = (tap_here && tap_acc) ? (int32_t*)tap_out : nullptr;
+                    hp.B = n; hp.Kp_bytes = s.gp.Kp_bytes; hp.k_steps = s.gp.k_steps; hp.A = A; hp.relu_in = s.gp.relu_in;
+                    e = launch_heads(hp, s.el, c.stream);
+                    break;
+                }
             }
             if (e != hipSuccess) return fail(ACCERL_EHIP, "step %d (kind %d, layer %d): %s", si, (int)s.kind, s.layer, hipGetErrorString(e));
             if (p->profiling) {
@@ -1043,7 +1050,7 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
     if (rc) return rc;
     std::string out;
     char line[512];
-    static const char* kinds[] = {"mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample"};
+    static const char* kinds[] = {"mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample", "heads"};
     snprintf(line, sizeof line, "steps=%d const_bytes=%lld ws_bytes_per_state=%lld chunk=%lld\n", (int)pol.steps.size(),
              (long long)cst.size(), (long long)pol.ws_per_state, (long long)pol.chunk);
     out += line;

@@ -6,10 +6,9 @@
 // the G images, so ragged image sizes (81 or 49 pixels) do not waste MFMA columns -- as the columns of
 // 16x16 MFMA tiles whose rows are output channels.  K runs over (ky, kx, c) of the channels-last tile:
 // for a fixed ky the taps of a pixel are one contiguous run, read as 16-byte chunks (64 int8 or 32 bf16
-// per MFMA step).  uint8 observations under a kernel of 2s x 2s at stride s = 4 (the 8x8/4 first layer
-// of the paper's networks) are staged space-to-depth: every 4x4x4 block of the frame becomes one
-// 64-byte "pixel", the layer turns into a 2x2 stride-1 convolution, and staging is a contiguous read
-// of the planar frame with each dword scattered to its block (LDS addresses precomputed per lane).
+// per MFMA step).  uint8 observations arrive as channel planes; staging reads one dword (4 pixels)
+// from each plane and interleaves them with byte permutes into 4-byte channels-last pixels, so that
+// under the 8x8/4 first layer of the paper's networks consecutive output pixels sit 16 bytes apart.
 //
 // Weights are the A operand.  When they fit (KS steps x NT tiles x 4 VGPRs) they live in registers for
 // the whole kernel, so LDS only feeds the pixel operand: one 16-byte read per lane serves NT MFMAs.
@@ -45,10 +44,6 @@ __device__ __forceinline__ uint32_t f2bf(float x) {
     return u >> 16;
 }
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; }
-// LDS swizzle for tiles whose pixels are 64 bytes apart: the 16-byte slot inside each 64-byte group is
-// XORed with bits 9:8 of the (tile-relative) address, so that 16 consecutive pixels spread over all banks
-__device__ __forceinline__ int swz64(int a) { return a ^ (((a >> 8) & 3) << 4); }
-
 template <int RD>
 __device__ __forceinline__ v4i read_chunk(const char* p) {
     if constexpr (RD == 16) {
@@ -99,26 +94,6 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         for (int i = tid; i < p.lds_tiles / 4; i += CONV_THREADS) ((int*)tiles)[i] = padv;
     }
 
-    // space-to-depth staging: LDS byte address of each dword this lane will stage (same for every batch)
-    constexpr int NTAB = (MODE == CM_S2D) ? PF * 4 : 1;
-    int s2d_dst[NTAB];
-    if constexpr (MODE == CM_S2D) {
-        const int w4 = p.W >> 2, plane4 = p.H * w4;            // dwords per source row / per plane
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int u = tid + i * CONV_THREADS;
-            const int img = (int)fdiv((uint32_t)u, p.magic_units);
-            const int wu = u - img * p.units_img;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int d = wu * 4 + e;
-                const int c = d / plane4, rem = d - c * plane4;
-                const int y = rem / w4, bx = rem - y * w4;
-                s2d_dst[i * 4 + e] = img * p.tile_stride + swz64(((y >> 2) * w4 + bx) * 64 + ((y & 3) * 4 + c) * 4);
-            }
-        }
-    }
-
     // per-lane epilogue constants: channels 4*NT*g .. 4*NT*g + 4*NT - 1
     v4i bi[NT];
     v4f bfl[NT];
@@ -150,7 +125,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         const int64_t b0 = batch * p.G;
         const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
         const int last = gc * p.units_img - 1;
-        if constexpr (MODE == CM_FLAT || MODE == CM_S2D) {
+        if constexpr (MODE == CM_FLAT) {
             // a batch of images is one contiguous range, read unit by unit
             const char* src = (const char*)p.in + b0 * (int64_t)p.img_bytes;
 #pragma unroll
@@ -210,10 +185,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
             const int u = tid + i * CONV_THREADS;
             if (u >= total) break;
             v4i v = pre[i];
-            if constexpr (MODE == CM_S2D) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) *(int*)(tiles + s2d_dst[i * 4 + e]) = v[e] ^ (int)0x80808080u;
-            } else if constexpr (MODE != CM_U8T) {
+            if constexpr (MODE != CM_U8T) {
                 if (p.src_u8) {
                     if constexpr (EL == EL_I8) {
 #pragma unroll
@@ -309,7 +281,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                 v4i bq[PT];
 #pragma unroll
                 for (int u = 0; u < PT; ++u)
-                    bq[u] = read_chunk<RD>(tiles + pimg[u] + (MODE == CM_S2D ? swz64(pb[u] + off) : pb[u] + off));
+                    bq[u] = read_chunk<RD>(tiles + pimg[u] + pb[u] + off);
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -444,7 +416,7 @@ constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
 // Tuned variants: (element, NT, KS, RD, staging mode, PF).  KS > 0 keeps the weights in registers and
 // unrolls that many MFMA steps; KS = 0 reads them from LDS for any number of steps.
 #define ACCERL_TUNED_I8(X)                                                                              \
-    X(EL_I8, 2, 4, 16, CM_S2D, 8) X(EL_I8, 1, 4, 16, CM_S2D, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
+    X(EL_I8, 2, 4, 16, CM_U8T, 8) X(EL_I8, 1, 4, 16, CM_U8T, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
     X(EL_I8, 4, 0, 16, CM_FLAT, 10) X(EL_I8, 2, 4, 16, CM_FLAT, 8) X(EL_I8, 1, 2, 16, CM_FLAT, 8)      \
     X(EL_I8, 1, 1, 8, CM_FLAT, 8) X(EL_I8, 1, 1, 4, CM_U8T, 8) X(EL_I8, 1, 2, 8, CM_ROWS, 8)           \
     X(EL_I8, 1, 3, 16, CM_ROWS, 8)

@@ -19,7 +19,7 @@ bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, i
 #undef X
     if (best_reg) { *KS = k_steps; *PF = best_reg; return true; }
     if (best_lds) { *KS = 0; *PF = best_lds; return true; }
-    if (pf > 16 || mode == CM_S2D) return false;
+    if (pf > 16) return false;
     *KS = 0; *PF = 16;
     return true;
 }

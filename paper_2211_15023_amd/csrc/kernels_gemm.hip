@@ -32,7 +32,7 @@ __device__ __forceinline__ uint32_t g_f2bf(float x) {
 __device__ __forceinline__ float g_sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
 
 template <int EL, int EPI>
-__global__ __launch_bounds__(GM_THREADS) void gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p) {
     __shared__ __attribute__((aligned(16))) char s_w[GM_NT * GM_KS * 1024];
     __shared__ __attribute__((aligned(16))) char s_x[GM_ROWS * GM_XPITCH];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -41,45 +41,85 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(GemmParams p) {
     const int nt0 = blockIdx.y * GM_NT;
     const int nts = (p.n_tiles - nt0 < GM_NT) ? (p.n_tiles - nt0) : GM_NT;
 
+    // accumulators start from the bias (features n = 16*(nt0+t) + 4g + r)
     v4i acc_i[2][GM_NT];
     v4f acc_f[2][GM_NT];
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int t = 0; t < GM_NT; ++t) {
+        const int n0 = (nt0 + (t < nts ? t : 0)) * 16 + 4 * g;
 #pragma unroll
-        for (int t = 0; t < GM_NT; ++t) {
-            acc_i[u][t] = (v4i){0, 0, 0, 0};
-            acc_f[u][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < 2; ++u) {
+            if constexpr (EL == EL_I8) acc_i[u][t] = *(const v4i*)((const int*)p.bias + n0);
+            else acc_f[u][t] = *(const v4f*)((const float*)p.bias + n0);
         }
+    }
 
-    for (int s0 = 0; s0 < p.k_steps; s0 += GM_KS) {
+    // Stage s0 of K: weights [GM_NT tiles][GM_KS steps] and states [GM_ROWS][GM_KS*64 bytes].  The loads of
+    // the next stage are issued into registers before the MFMA work of the current one.  They are
+    // unconditional (clamped addresses, zeroed afterwards) so that nothing serialises them.
+    constexpr int WPRE = GM_NT * GM_KS * 64 / GM_THREADS;       // 4 weight units per lane
+    constexpr int XPRE = GM_ROWS * GM_KS * 4 / GM_THREADS;      // 8 state units per lane
+    v4i wpre[WPRE], xpre[XPRE];
+    const int w_st = tid >> 6;                                  // step of this lane's weight units
+    auto prefetch = [&](int s0) {
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
-        __syncthreads();
-        // weights: for each feature tile the ns fragments of this stage are contiguous in global
-        for (int i = tid; i < GM_NT * GM_KS * 64; i += GM_THREADS) {
-            const int t = i / (GM_KS * 64), rem = i - t * (GM_KS * 64);
-            const int st = rem >> 6;
-            v4i v = {0, 0, 0, 0};
-            if (t < nts && st < ns)
-                v = ((const v4i*)p.wfrag)[((int64_t)(nt0 + t) * p.k_steps + s0 + st) * 64 + (rem & 63)];
-            ((v4i*)s_w)[i] = v;
-        }
-        // states: 128 rows x 16 chunks
-        for (int i = tid; i < GM_ROWS * GM_KS * 4; i += GM_THREADS) {
-            const int rr = i / (GM_KS * 4), c = i - rr * (GM_KS * 4);
-            const int64_t b = b0 + rr;
-            const int kb = s0 * 64 + c * 16;
-            v4i v = {0, 0, 0, 0};
-            if (b < p.B && kb < p.Kp_bytes) {
-                v = *(const v4i*)((const char*)p.x + b * p.Kp_bytes + kb);
-                if (p.relu_in) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        v[e] = (int)((EL == EL_I8) ? g_relu_i8x4((uint32_t)v[e]) : g_relu_bf16x2((uint32_t)v[e]));
-                }
+        for (int r = 0; r < WPRE; ++r) {                         // unit r: tile r, step w_st
+            const int t = (r < nts) ? r : 0, st = (w_st < ns) ? w_st : 0;
+            wpre[r] = ((const v4i*)p.wfrag)[((int64_t)(nt0 + t) * p.k_steps + s0 + st) * 64 + lane];
+        }
+#pragma unroll
+        for (int r = 0; r < XPRE; ++r) {
+            const int i = tid + r * GM_THREADS;
+            const int rr = i >> 4, c = i & 15;
+            int64_t b = b0 + rr;
+            if (b >= p.B) b = p.B - 1;
+            int kb = s0 * 64 + c * 16;
+            if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
+            xpre[r] = *(const v4i*)((const char*)p.x + b * p.Kp_bytes + kb);
+        }
+    };
+    auto commit = [&](int s0) {
+        const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
+#pragma unroll
+        for (int r = 0; r < WPRE; ++r) {
+            v4i v = wpre[r];
+            if (!(r < nts && w_st < ns)) v = (v4i){0, 0, 0, 0};
+            ((v4i*)s_w)[tid + r * GM_THREADS] = v;
+        }
+#pragma unroll
+        for (int r = 0; r < XPRE; ++r) {
+            const int i = tid + r * GM_THREADS;
+            const int rr = i >> 4, c = i & 15;
+            const int kb = s0 * 64 + c * 16;
+            v4i v = xpre[r];
+            // a unit that starts inside the row but runs past it re-read the row's last 16 bytes: rebuild
+            // it from the bytes that belong to it (rows are padded with zero weights, not zero data)
+            if (b0 + rr >= p.B || kb >= p.Kp_bytes) {
+                v = (v4i){0, 0, 0, 0};
+            } else if (kb > p.Kp_bytes - 16) {
+                const int have = p.Kp_bytes - kb;              // 4, 8 or 12 valid bytes, at the end of v
+                const int sh = (16 - have) >> 2;
+                v4i w = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (e + sh < 4) w[e] = v[(e + sh) & 3];
+                v = w;
+            }
+            if (p.relu_in) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = (int)((EL == EL_I8) ? g_relu_i8x4((uint32_t)v[e]) : g_relu_bf16x2((uint32_t)v[e]));
             }
             *(v4i*)(s_x + rr * GM_XPITCH + c * 16) = v;
         }
+    };
+
+    prefetch(0);
+    for (int s0 = 0; s0 < p.k_steps; s0 += GM_KS) {
+        const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
+        commit(s0);
         __syncthreads();
+        if (s0 + GM_KS < p.k_steps) prefetch(s0 + GM_KS);
         for (int st = 0; st < ns; ++st) {
             v4i bq[2];
 #pragma unroll
@@ -99,6 +139,7 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(GemmParams p) {
                 }
             }
         }
+        __syncthreads();
     }
 
     // ---- epilogue: lane holds features n0 .. n0+3 of state b
@@ -112,56 +153,53 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(GemmParams p) {
             const int n0 = (nt0 + t) * 16 + 4 * g;
             if (n0 >= p.N) continue;
             if constexpr (EPI == EPI_REQUANT) {
-                const v4i bi = *(const v4i*)((const int*)p.bias + n0);
                 const v4f ml = *(const v4f*)(p.mult + n0);
-                const float lo = p.relu ? 0.0f : -127.0f;
                 uint32_t pk = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int v = acc_i[u][t][r] + bi[r];
+                    const int v = acc_i[u][t][r];
                     if (p.tap_acc && n0 + r < p.N) p.tap_acc[b * p.N + n0 + r] = v;
-                    float y = rintf((float)v * ml[r]);
-                    y = fmaxf(fminf(y, 127.0f), lo);
-                    pk |= (uint32_t)(uint8_t)(int8_t)(int)y << (8 * r);
+                    if (p.relu) {   // clamp(rint(y), 0, 127): the pack instruction rounds to nearest even, saturates at 0
+                        pk = __builtin_amdgcn_cvt_pk_u8_f32(fminf((float)v * ml[r], 127.0f), r, pk);
+                    } else {
+                        const float y = __builtin_amdgcn_fmed3f(rintf((float)v * ml[r]), -127.0f, 127.0f);
+                        pk |= ((uint32_t)(int)y & 0xffu) << (8 * r);
+                    }
                 }
                 *(uint32_t*)((int8_t*)p.out + b * p.Np + n0) = pk;
             } else if constexpr (EPI == EPI_HEADS_I8) {
-                const v4i bi = *(const v4i*)((const int*)p.bias + n0);
                 const v4f ml = *(const v4f*)(p.mult + n0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int n = n0 + r;
                     if (n > p.A) continue;
-                    const int v = acc_i[u][t][r] + bi[r];
+                    const int v = acc_i[u][t][r];
                     if (p.tap_acc) p.tap_acc[b * (p.A + 1) + n] = v;
                     const float o = (float)v * ml[r];
                     if (p.logits) { if (n < p.A) p.logits[b * p.A + n] = o; else p.value[b] = o; }
                 }
             } else if constexpr (EPI == EPI_BF16) {
-                const v4f bs = *(const v4f*)((const float*)p.bias + n0);
                 float v[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    v[r] = acc_f[u][t][r] + bs[r];
+                    v[r] = acc_f[u][t][r];
                     if (p.relu) v[r] = fmaxf(v[r], 0.0f);
                 }
                 uint32_t* d = (uint32_t*)((uint16_t*)p.out + b * p.Np + n0);
                 d[0] = g_f2bf(v[0]) | (g_f2bf(v[1]) << 16);
                 d[1] = g_f2bf(v[2]) | (g_f2bf(v[3]) << 16);
             } else if constexpr (EPI == EPI_HEADS_F32ACC) {
-                const v4f bs = *(const v4f*)((const float*)p.bias + n0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int n = n0 + r;
                     if (n > p.A) continue;
-                    const float o = acc_f[u][t][r] + bs[r];
+                    const float o = acc_f[u][t][r];
                     if (p.logits) { if (n < p.A) p.logits[b * p.A + n] = o; else p.value[b] = o; }
                 }
             } else {   // EPI_LSTM: rows 4*unit + {i,f,g,o}
-                const v4f bs = *(const v4f*)((const float*)p.bias + n0);
                 const int unit = n0 >> 2;
-                const float pi = acc_f[u][t][0] + bs[0], pf = acc_f[u][t][1] + bs[1];
-                const float pg = acc_f[u][t][2] + bs[2], po = acc_f[u][t][3] + bs[3];
+                const float pi = acc_f[u][t][0], pf = acc_f[u][t][1];
+                const float pg = acc_f[u][t][2], po = acc_f[u][t][3];
                 const float si = g_sigmoid(pi), sf = g_sigmoid(pf), tg = tanhf(pg), so = g_sigmoid(po);
                 const float c_old = p.c[b * p.Hd + unit];
                 const float t1 = sf * c_old;

@@ -1,0 +1,163 @@
+// Policy heads fused with the sampler: logits and value of 16 states per wavefront on the matrix
+// cores (A = head weights staged once per workgroup in LDS, B = the states' feature rows, all of a
+// state's K chunks loaded up front), then log-softmax normaliser and inverse-CDF sampling per state.
+#include "accerl_internal.h"
+
+namespace accerl {
+
+constexpr int HD_WAVES = 4;
+constexpr int HD_KMAX = 16;          // MFMA steps of K held in registers per lane
+constexpr int HD_PITCH = 65;         // floats per state in the logits staging area
+
+__device__ __forceinline__ uint32_t h_relu_i8x4(uint32_t x) {
+    const uint32_t neg = (x & 0x80808080u) >> 7;
+    return x & ~(neg * 0xffu);
+}
+__device__ __forceinline__ uint32_t h_relu_bf16x2(uint32_t x) {
+    const uint32_t neg = (x & 0x80008000u) >> 15;
+    return x & ~(neg * 0xffffu);
+}
+
+template <int EL, int NT>
+__global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* s_w = smem;                                               // [NT][k_steps][64 lanes][16 B]
+    float* s_l = (float*)(smem + NT * p.k_steps * 1024);            // [waves][16][HD_PITCH]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int64_t row0 = ((int64_t)blockIdx.x * HD_WAVES + wave) * 16;
+    int64_t row = row0 + j;
+    const bool live = row < p.B;
+    if (!live) row = p.B - 1;
+
+    // this lane's K chunks of its state: unconditional loads, the tail chunk rebuilt below
+    v4i xb[HD_KMAX];
+    const char* xrow = (const char*)p.x + row * p.Kp_bytes;
+#pragma unroll
+    for (int st = 0; st < HD_KMAX; ++st) {
+        int kb = st * 64 + g * 16;
+        if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
+        xb[st] = *(const v4i*)(xrow + kb);
+    }
+    for (int i = tid; i < NT * p.k_steps * 64; i += HD_WAVES * 64) ((v4i*)s_w)[i] = ((const v4i*)p.wfrag)[i];
+    __syncthreads();
+
+    v4i acc_i[NT];
+    v4f acc_f[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if constexpr (EL == EL_I8) acc_i[t] = *(const v4i*)((const int*)p.bias + 16 * t + 4 * g);
+        else acc_f[t] = *(const v4f*)((const float*)p.bias + 16 * t + 4 * g);
+    }
+#pragma unroll
+    for (int st = 0; st < HD_KMAX; ++st) {
+        if (st < p.k_steps) {
+            const int kb = st * 64 + g * 16;
+            v4i v = xb[st];
+            if (kb >= p.Kp_bytes) {
+                v = (v4i){0, 0, 0, 0};
+            } else if (kb > p.Kp_bytes - 16) {
+                const int sh = (16 - (p.Kp_bytes - kb)) >> 2;
+                v4i w = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (e + sh < 4) w[e] = v[(e + sh) & 3];
+                v = w;
+            }
+            if (p.relu_in) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = (int)((EL == EL_I8) ? h_relu_i8x4((uint32_t)v[e]) : h_relu_bf16x2((uint32_t)v[e]));
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const v4i a = *(const v4i*)(s_w + ((t * p.k_steps + st) * 64 + lane) * 16);
+                if constexpr (EL == EL_I8) acc_i[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, v, acc_i[t], 0, 0, 0);
+                else acc_f[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, v), acc_f[t], 0, 0, 0);
+            }
+        }
+    }
+
+    // heads -> staging area (outputs 16t + 4g + r of state j)
+    const int A = p.A;
+    float* stage = s_l + wave * 16 * HD_PITCH;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        v4f ml = {1.f, 1.f, 1.f, 1.f};
+        if constexpr (EL == EL_I8) ml = *(const v4f*)(p.mult + 16 * t + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int n = 16 * t + 4 * g + r;
+            if (n > A) continue;
+            float o;
+            if constexpr (EL == EL_I8) {
+                o = (float)acc_i[t][r] * ml[r];
+                if (p.tap_acc && live) p.tap_acc[row * (A + 1) + n] = acc_i[t][r];
+            } else {
+                o = acc_f[t][r];
+            }
+            stage[j * HD_PITCH + n] = o;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (p.logits) {
+        const int64_t rows = (p.B - row0 < 16) ? (p.B - row0) : 16;
+        for (int64_t i = lane; i < rows * A; i += 64) {
+            const int rr = (int)(i / A), a = (int)(i - (int64_t)rr * A);
+            p.logits[row0 * A + i] = stage[rr * HD_PITCH + a];
+        }
+    }
+    if (g == 0 && live && p.action) {
+        const float* lg = stage + j * HD_PITCH;
+        p.value[row] = lg[A];
+        float m = lg[0];
+        for (int a = 1; a < A; ++a) m = fmaxf(m, lg[a]);
+        float Z = 0.0f;
+        for (int a = 0; a < A; ++a) Z += expf(lg[a] - m);
+        const float thr = p.uniforms[row] * Z;
+        float cum = 0.0f;
+        int act = A - 1;
+        for (int a = 0; a < A; ++a) {
+            cum += expf(lg[a] - m);
+            if (cum > thr) { act = a; break; }
+        }
+        p.action[row] = act;
+    }
+}
+
+template <int EL>
+static hipError_t heads_nt(const HeadsParams& p, int nt, dim3 grid, size_t lds, hipStream_t s) {
+#define GO(N)                                                                                          \
+    do {                                                                                               \
+        auto kfn = heads_kernel<EL, N>;                                                                \
+        static size_t set_lds = 0;                                                                     \
+        if (lds > set_lds) {                                                                           \
+            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (e != hipSuccess) return e;                                                             \
+            set_lds = lds;                                                                             \
+        }                                                                                              \
+        kfn<<<grid, dim3(HD_WAVES * 64), lds, s>>>(p);                                                 \
+        return hipGetLastError();                                                                      \
+    } while (0)
+    switch (nt) {
+        case 1: GO(1);
+        case 2: GO(2);
+        case 3: GO(3);
+        default: GO(4);
+    }
+#undef GO
+}
+
+bool heads_supported(int k_steps, int Kp_bytes) { return k_steps <= HD_KMAX && Kp_bytes >= 16; }
+
+hipError_t launch_heads(const HeadsParams& p, Elem el, hipStream_t s) {
+    if (p.B <= 0) return hipSuccess;
+    const int nt = (p.A + 1 + 15) / 16;
+    if (!heads_supported(p.k_steps, p.Kp_bytes) || nt > 4) return hipErrorInvalidValue;
+    const size_t lds = (size_t)nt * p.k_steps * 1024 + (size_t)HD_WAVES * 16 * HD_PITCH * 4;
+    dim3 grid((unsigned)((p.B + HD_WAVES * 16 - 1) / (HD_WAVES * 16)));
+    return el == EL_I8 ? heads_nt<EL_I8>(p, nt, grid, lds, s) : heads_nt<EL_BF16>(p, nt, grid, lds, s);
+}
+
+}  // namespace accerl
