@@ -117,10 +117,47 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
     const int lead = p.pad * pix;
     const int64_t n_batch = (p.B + p.G - 1) / p.G;
 
-    // ---- staging: issue the loads of a batch into registers / write them to LDS
+    // ---- staging: issue the loads of a batch into registers / write them to LDS.
+    // Which bytes a lane stages, and where they land in LDS, is the same for every batch, so the source
+    // offset (relative to the first image of the batch) and the LDS address of each unit are worked out
+    // once.  All loads are unconditional (a unit that does not exist in a short last batch, or that lies
+    // in the padding, re-reads a valid address and is dropped or zeroed at commit time): loads under
+    // divergent branches would be serialised by the wait-count insertion.
     v4i pre[PF];
-    // All loads are unconditional (out-of-range units re-read a valid address and are dropped at commit
-    // time): loads under divergent branches would be serialised by the wait-count insertion.
+    constexpr int NOFF = (MODE == CM_FLAT) ? 1 : PF;
+    uint32_t soff[NOFF];      // ROWS: offset of the source row; U8T: offset of the unit in plane 0
+    int ooff[NOFF];           // ROWS: byte offset of the unit inside its image row (may lie in the padding)
+    int doff[NOFF];           // LDS byte offset of the unit, -1 = never written (stays padding)
+    uint32_t smask[NOFF];     // ROWS: bit e set = dword e of the unit is real data
+    if constexpr (MODE != CM_FLAT) {
+        const int n_units = p.G * p.units_img;
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            const int u = min(tid + i * CONV_THREADS, n_units - 1);
+            const int img = (int)fdiv((uint32_t)u, p.magic_units);
+            const int w = u - img * p.units_img;
+            const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
+            const int cu = w - rr * p.row_units;
+            const int iy = iy0 + rr;
+            const bool rin = iy >= 0 && iy < p.H;
+            const int iyc = min(max(iy, 0), p.H - 1);
+            if constexpr (MODE == CM_ROWS) {
+                const int o = cu * 16 - lead;
+                uint32_t m = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) m |= (rin && o + 4 * e >= 0 && o + 4 * e < row_bytes_img) ? (1u << e) : 0u;
+                smask[i] = m;
+                ooff[i] = p.vec_ok ? min(max(o, 0), row_bytes_img - 16) : o;
+                soff[i] = (uint32_t)((img * p.H + iyc) * row_bytes_img);
+                doff[i] = img * p.tile_stride + rr * p.pitch + cu * 16;
+            } else {
+                smask[i] = 0;
+                ooff[i] = 0;
+                soff[i] = (uint32_t)(img * p.Cin_real * p.H * p.W + iyc * p.W + 4 * cu);
+                doff[i] = rin ? img * p.tile_stride + rr * p.pitch + lead + 4 * cu * pix : -1;
+            }
+        }
+    }
     auto prefetch = [&](int64_t batch) {
         const int64_t b0 = batch * p.G;
         const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
@@ -134,44 +171,29 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                 pre[i] = *(const v4i*)(src + (uint32_t)u * 16u);
             }
         } else if constexpr (MODE == CM_ROWS) {
+            const char* src = (const char*)p.in + b0 * (int64_t)p.H * row_bytes_img;
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                const int u = min(tid + i * CONV_THREADS, last);
-                const int img = (int)fdiv((uint32_t)u, p.magic_units);
-                const int w = u - img * p.units_img;
-                const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
-                const int o = (w - rr * p.row_units) * 16 - lead;          // byte offset inside the image row
-                const int iy = iy0 + rr;
-                const bool rin = iy >= 0 && iy < p.H;
-                const char* srow = (const char*)p.in + ((b0 + img) * (int64_t)p.H + min(max(iy, 0), p.H - 1)) * row_bytes_img;
-                v4i v;
+                const uint32_t so = (tid + i * CONV_THREADS <= last) ? soff[i] : 0u;   // a unit of a missing image reads image 0
                 if (p.vec_ok) {
-                    v = *(const v4i*)(srow + min(max(o, 0), row_bytes_img - 16));
-                    if (!(rin && o >= 0 && o < row_bytes_img)) v = (v4i){0, 0, 0, 0};
+                    pre[i] = *(const v4i*)(src + so + (uint32_t)ooff[i]);
                 } else {
+                    v4i v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int oo = o + 4 * e;
-                        const int x = *(const int*)(srow + min(max(oo, 0), row_bytes_img - 4));
-                        v[e] = (rin && oo >= 0 && oo < row_bytes_img) ? x : 0;
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = *(const int*)(src + so + (uint32_t)min(max(ooff[i] + 4 * e, 0), row_bytes_img - 4));
+                    pre[i] = v;
                 }
-                pre[i] = v;
             }
         } else {   // CM_U8T: one dword (4 pixels) from each channel plane
+            const uint8_t* src = (const uint8_t*)p.in + b0 * (int64_t)p.Cin_real * p.H * p.W;
             const int plane = p.H * p.W;
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                const int u = min(tid + i * CONV_THREADS, last);
-                const int img = (int)fdiv((uint32_t)u, p.magic_units);
-                const int w = u - img * p.units_img;
-                const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
-                const int xq = w - rr * p.row_units;
-                const int iy = min(max(iy0 + rr, 0), p.H - 1);             // rows outside the image are dropped at commit
-                const uint8_t* src = (const uint8_t*)p.in + (b0 + img) * (int64_t)p.Cin_real * plane + iy * p.W + 4 * xq;
+                const uint32_t so = (tid + i * CONV_THREADS <= last) ? soff[i] : 0u;
                 v4i v;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] = *(const int*)(src + min(c, p.Cin_real - 1) * plane);
+                for (int c = 0; c < 4; ++c) v[c] = *(const int*)(src + (uint32_t)(min(c, p.Cin_real - 1) * plane) + so);
                 pre[i] = v;
             }
         }
@@ -186,32 +208,19 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
             if (u >= total) break;
             v4i v = pre[i];
             if constexpr (MODE != CM_U8T) {
-                if (p.src_u8) {
-                    if constexpr (EL == EL_I8) {
+                if constexpr (MODE == CM_ROWS) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] ^= (int)0x80808080u;
-                    }
-                } else if (p.relu_in) {
+                    for (int e = 0; e < 4; ++e) v[e] = ((smask[i] >> e) & 1u) ? v[e] : 0;
+                }
+                if (p.relu_in) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         v[e] = (int)((EL == EL_I8) ? relu_i8x4((uint32_t)v[e]) : relu_bf16x2((uint32_t)v[e]));
                 }
-                if constexpr (MODE == CM_FLAT) {
-                    *(v4i*)(tiles + u * 16) = v;               // tiles of a batch are contiguous like the images
-                } else {
-                    const int img = (int)fdiv((uint32_t)u, p.magic_units);
-                    const int w = u - img * p.units_img;
-                    const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
-                    *(v4i*)(tiles + img * p.tile_stride + rr * p.pitch + (w - rr * p.row_units) * 16) = v;
-                }
+                if constexpr (MODE == CM_FLAT) *(v4i*)(tiles + u * 16) = v;   // tiles of a batch are contiguous like the images
+                else *(v4i*)(tiles + doff[i]) = v;
             } else {
-                const int img = (int)fdiv((uint32_t)u, p.magic_units);
-                const int w = u - img * p.units_img;
-                char* tile = tiles + img * p.tile_stride;
-                const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
-                const int xq = w - rr * p.row_units;
-                const int iy = iy0 + rr;
-                if (iy < 0 || iy >= p.H) continue;            // stays padding
+                if (doff[i] < 0) continue;                    // row outside the image: stays padding
                 const uint32_t P0 = (uint32_t)v[0], P1 = (uint32_t)v[1], P2 = (uint32_t)v[2], P3 = (uint32_t)v[3];
                 const uint32_t lo01 = __builtin_amdgcn_perm(P1, P0, 0x05010400u);
                 const uint32_t hi01 = __builtin_amdgcn_perm(P1, P0, 0x07030602u);
@@ -223,11 +232,16 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                 px[2] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
                 px[3] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
                 if constexpr (EL == EL_I8) {
-                    uint32_t* d = (uint32_t*)(tile + rr * p.pitch + lead + 16 * xq);
+                    if ((lead & 15) == 0) {
+                        *(v4i*)(tiles + doff[i]) = (v4i){(int)(px[0] ^ 0x80808080u), (int)(px[1] ^ 0x80808080u),
+                                                         (int)(px[2] ^ 0x80808080u), (int)(px[3] ^ 0x80808080u)};
+                    } else {
+                        uint32_t* d = (uint32_t*)(tiles + doff[i]);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) d[e] = px[e] ^ 0x80808080u;
+                        for (int e = 0; e < 4; ++e) d[e] = px[e] ^ 0x80808080u;
+                    }
                 } else {
-                    uint32_t* d = (uint32_t*)(tile + rr * p.pitch + lead + 32 * xq);
+                    uint32_t* d = (uint32_t*)(tiles + doff[i]);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         uint32_t c0 = p.lut[px[e] & 0xff], c1 = p.lut[(px[e] >> 8) & 0xff];
@@ -255,6 +269,10 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
         const int total_pix = gc * n_pix;
         const int n_tiles = (total_pix + 15) >> 4;
+        const int64_t base_el = ((b0 * p.Ho + oy0) * p.Wo) * (int64_t)p.Cs_out;   // first element this block writes
+        char* out_b = (char*)p.out + base_el * ESZ;
+        const char* res_b = (const char*)p.res + base_el * ESZ;
+        int32_t* tap_b = p.tap_acc + base_el;
         for (int t0 = wave * PT; t0 < n_tiles; t0 += CONV_WAVES * PT) {
             int pb[PT], pimg[PT], ppix[PT];   // tile-relative pixel offset, tile offset, pixel number
 #pragma unroll
@@ -309,24 +327,24 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
 #pragma unroll
             for (int u = 0; u < PT; ++u) {
                 if (ppix[u] >= total_pix) continue;
+                // pixel number relative to the first pixel this workgroup writes for the batch
                 const int img = (int)fdiv((uint32_t)ppix[u], p.magic_npix);
-                const int rem = ppix[u] - img * n_pix;
-                const int ty = (int)fdiv((uint32_t)rem, p.magic_wo), ox = rem - ty * p.Wo;
-                const int64_t opix = ((b0 + img) * p.Ho + (oy0 + ty)) * p.Wo + ox;
+                const int rel = ppix[u] + img * (p.Ho * p.Wo - n_pix);
                 const int c0 = 4 * NT * g;
-                const int64_t o = opix * p.Cs_out + c0;
+                const uint32_t o = (uint32_t)(rel * p.Cs_out + c0);
+                const uint32_t o_res = (uint32_t)(rel * p.Cs_out);
                 if constexpr (EL == EL_I8) {
                     uint32_t pk[NT];
                     uint32_t xr[NT];
                     if (p.res) {
 #pragma unroll
                         for (int t = 0; t < NT; ++t)   // lanes past the last channel re-read a valid group (not stored)
-                            xr[t] = *(const uint32_t*)((const int8_t*)p.res + opix * p.Cs_out + min(c0 + 4 * t, p.Cs_out - 4));
+                            xr[t] = *(const uint32_t*)(res_b + o_res + (uint32_t)min(c0 + 4 * t, p.Cs_out - 4));
                     }
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         const v4i v = acc_i[u][t];
-                        if (p.tap_acc && c0 + 4 * t < p.Cs_out) *(v4i*)(p.tap_acc + o + 4 * t) = v;
+                        if (p.tap_acc && c0 + 4 * t < p.Cs_out) *(v4i*)(tap_b + o + 4 * t) = v;
                         uint32_t w = 0;
                         if (p.res) {
 #pragma unroll
@@ -349,7 +367,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                         }
                         pk[t] = w;
                     }
-                    int8_t* dst = (int8_t*)p.out + o;
+                    int8_t* dst = (int8_t*)out_b + o;
                     if (NT == 4 && c0 + 16 <= p.Cs_out) {
                         *(v4i*)dst = (v4i){(int)pk[0], (int)pk[1 % NT], (int)pk[2 % NT], (int)pk[3 % NT]};
                     } else {
@@ -362,7 +380,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                     if (p.res) {
 #pragma unroll
                         for (int t = 0; t < NT; ++t) {   // unconditional: lanes past the last channel re-read a valid group
-                            const uint32_t* xr = (const uint32_t*)((const uint16_t*)p.res + opix * p.Cs_out + min(c0 + 4 * t, p.Cs_out - 4));
+                            const uint32_t* xr = (const uint32_t*)((const uint16_t*)res_b + o_res + (uint32_t)min(c0 + 4 * t, p.Cs_out - 4));
                             xres[t][0] = xr[0];
                             xres[t][1] = xr[1];
                         }
@@ -384,7 +402,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.0f);
                         }
-                        uint32_t* d = (uint32_t*)((uint16_t*)p.out + o + 4 * t);
+                        uint32_t* d = (uint32_t*)((uint16_t*)out_b + o + 4 * t);
                         d[0] = f2bf(v[0]) | (f2bf(v[1]) << 16);
                         d[1] = f2bf(v[2]) | (f2bf(v[3]) << 16);
                     }
