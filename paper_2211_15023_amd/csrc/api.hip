@@ -301,12 +301,16 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     if (n_bands == 1) {
         const int slot = 4 * PT * 16;
         const int unit_cap = 2560;
+        // largest batch whose tile-slot use is within 3 % of the best one: more pixels per barrier pair
         double best = -1.0;
-        for (int gg = 1; gg <= 16; ++gg) {
-            if (gg > 1 && (gg * units_img > unit_cap || w_lds_max + gg * tile_stride + 32 > budget)) break;
-            const double util = (double)gg * n_pix / ((gg * n_pix + slot - 1) / slot * slot);
-            if (util > best + 0.02) { best = util; G = gg; }
+        auto util_of = [&](int gg) { return (double)gg * n_pix / ((gg * n_pix + slot - 1) / slot * slot); };
+        int gmax = 1;
+        for (int gg = 2; gg <= 64; ++gg) {
+            if (gg * units_img > unit_cap || w_lds_max + gg * tile_stride + 32 > budget) break;
+            gmax = gg;
         }
+        for (int gg = 1; gg <= gmax; ++gg) best = util_of(gg) > best ? util_of(gg) : best;
+        for (int gg = 1; gg <= gmax; ++gg) if (util_of(gg) >= best - 0.03) G = gg;
     }
     int KS = 0, PF = 16;
     if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, &KS, &PF))
@@ -1006,12 +1010,12 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
     cst.swap(B.cst);
     pol->ws_per_state = 0;
     for (const auto& b : pol->bufs) pol->ws_per_state += b.per_state;
-    // states per pass: keep one pass's intermediates near the size of the on-package cache
+    // states per pass: about 1 GiB of intermediates, so that every launch still fills the chip
     pol->chunk = 0;
     if (pol->ws_per_state > 0) {
-        int64_t ch = (160ll << 20) / pol->ws_per_state;
-        if (ch < 256) ch = 256;
-        if (ch > 8192) ch = 8192;
+        int64_t ch = (1ll << 30) / pol->ws_per_state;
+        if (ch < 1024) ch = 1024;
+        if (ch > 16384) ch = 16384;
         pol->chunk = ch;
     }
     if (const char* env = getenv("ACCERL_CHUNK")) { const long v = atol(env); if (v > 0) pol->chunk = v; }

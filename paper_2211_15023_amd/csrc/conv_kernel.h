@@ -357,7 +357,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                             // clamp(rint(y), 0, 127): the pack instruction rounds to nearest even and saturates at 0
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
-                                w = __builtin_amdgcn_cvt_pk_u8_f32(fminf((float)v[r] * ml[t][r], 127.0f), r, w);
+                                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)v[r] * ml[t][r], 0.0f, 127.0f), r, w);
                         } else {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
@@ -370,6 +370,9 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                     int8_t* dst = (int8_t*)out_b + o;
                     if (NT == 4 && c0 + 16 <= p.Cs_out) {
                         *(v4i*)dst = (v4i){(int)pk[0], (int)pk[1 % NT], (int)pk[2 % NT], (int)pk[3 % NT]};
+                    } else if (NT == 2 && c0 + 8 <= p.Cs_out) {
+                        typedef int v2i __attribute__((ext_vector_type(2)));
+                        *(v2i*)dst = (v2i){(int)pk[0], (int)pk[1 % NT]};
                     } else {
 #pragma unroll
                         for (int t = 0; t < NT; ++t)

@@ -1,6 +1,6 @@
 // Dense layers on the matrix cores: out[b, n] = sum_k W[n, k] x[b, k], int8 (int32 accumulate) or
 // bf16 (fp32 accumulate).  Output features are the MFMA rows and states the columns, so one lane ends
-// up with 4 consecutive features of one state.  A workgroup owns 64 features x 128 states and walks K
+// up with 4 consecutive features of one state.  A workgroup owns 64 features x 64 states and walks K
 // in stages of 256 bytes per row staged through LDS; the epilogue is chosen at compile time:
 // requantize to int8, bias+ReLU to bf16, policy heads (logits / value in fp32), or the LSTM cell
 // (weight rows are interleaved on the host so that the 4 accumulators of a lane are the i,f,g,o
@@ -11,7 +11,8 @@ namespace accerl {
 
 constexpr int GM_THREADS = 256;
 constexpr int GM_NT = 4;          // feature tiles (of 16) per workgroup
-constexpr int GM_ROWS = 128;      // states per workgroup
+constexpr int GM_RT = 1;          // row tiles (of 16 states) per wave
+constexpr int GM_ROWS = 64 * GM_RT;   // states per workgroup
 constexpr int GM_KS = 4;          // MFMA steps per LDS stage (64 bytes of K each)
 constexpr int GM_XPITCH = GM_KS * 64 + 16;
 
@@ -42,13 +43,13 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
     const int nts = (p.n_tiles - nt0 < GM_NT) ? (p.n_tiles - nt0) : GM_NT;
 
     // accumulators start from the bias (features n = 16*(nt0+t) + 4g + r)
-    v4i acc_i[2][GM_NT];
-    v4f acc_f[2][GM_NT];
+    v4i acc_i[GM_RT][GM_NT];
+    v4f acc_f[GM_RT][GM_NT];
 #pragma unroll
     for (int t = 0; t < GM_NT; ++t) {
         const int n0 = (nt0 + (t < nts ? t : 0)) * 16 + 4 * g;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < GM_RT; ++u) {
             if constexpr (EL == EL_I8) acc_i[u][t] = *(const v4i*)((const int*)p.bias + n0);
             else acc_f[u][t] = *(const v4f*)((const float*)p.bias + n0);
         }
@@ -121,15 +122,15 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         __syncthreads();
         if (s0 + GM_KS < p.k_steps) prefetch(s0 + GM_KS);
         for (int st = 0; st < ns; ++st) {
-            v4i bq[2];
+            v4i bq[GM_RT];
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-                bq[u] = *(const v4i*)(s_x + ((wave * 2 + u) * 16 + j) * GM_XPITCH + st * 64 + g * 16);
+            for (int u = 0; u < GM_RT; ++u)
+                bq[u] = *(const v4i*)(s_x + ((wave * GM_RT + u) * 16 + j) * GM_XPITCH + st * 64 + g * 16);
 #pragma unroll
             for (int t = 0; t < GM_NT; ++t) {
                 const v4i a = *(const v4i*)(s_w + ((t * GM_KS + st) * 64 + lane) * 16);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < GM_RT; ++u) {
                     if constexpr (EL == EL_I8) {
                         acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bq[u], acc_i[u][t], 0, 0, 0);
                     } else {
@@ -144,8 +145,8 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
 
     // ---- epilogue: lane holds features n0 .. n0+3 of state b
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int64_t b = b0 + (wave * 2 + u) * 16 + j;
+    for (int u = 0; u < GM_RT; ++u) {
+        const int64_t b = b0 + (wave * GM_RT + u) * 16 + j;
         if (b >= p.B) continue;
 #pragma unroll
         for (int t = 0; t < GM_NT; ++t) {
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
                     const int v = acc_i[u][t][r];
                     if (p.tap_acc && n0 + r < p.N) p.tap_acc[b * p.N + n0 + r] = v;
                     if (p.relu) {   // clamp(rint(y), 0, 127): the pack instruction rounds to nearest even, saturates at 0
-                        pk = __builtin_amdgcn_cvt_pk_u8_f32(fminf((float)v * ml[r], 127.0f), r, pk);
+                        pk = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)v * ml[r], 0.0f, 127.0f), r, pk);
                     } else {
                         const float y = __builtin_amdgcn_fmed3f(rintf((float)v * ml[r]), -127.0f, 127.0f);
                         pk |= ((uint32_t)(int)y & 0xffu) << (8 * r);

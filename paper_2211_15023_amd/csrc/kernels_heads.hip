@@ -5,7 +5,7 @@
 
 namespace accerl {
 
-constexpr int HD_WAVES = 4;
+constexpr int HD_WAVES = 1;          // one wavefront per workgroup: no workgroup barrier, 16 states each
 constexpr int HD_KMAX = 16;          // MFMA steps of K held in registers per lane
 constexpr int HD_PITCH = 65;         // floats per state in the logits staging area
 
@@ -22,7 +22,7 @@ template <int EL, int NT>
 __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* s_w = smem;                                               // [NT][k_steps][64 lanes][16 B]
-    float* s_l = (float*)(smem + NT * p.k_steps * 1024);            // [waves][16][HD_PITCH]
+    float* s_l = (float*)(smem + NT * p.k_steps * 1024);            // [waves][2][16][HD_PITCH]: logits, then exp terms
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int64_t row0 = ((int64_t)blockIdx.x * HD_WAVES + wave) * 16;
@@ -79,7 +79,8 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
 
     // heads -> staging area (outputs 16t + 4g + r of state j)
     const int A = p.A;
-    float* stage = s_l + wave * 16 * HD_PITCH;
+    float* stage = s_l + wave * 2 * 16 * HD_PITCH;
+    float* stage_e = stage + 16 * HD_PITCH;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         v4f ml = {1.f, 1.f, 1.f, 1.f};
@@ -108,21 +109,29 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
             p.logits[row0 * A + i] = stage[rr * HD_PITCH + a];
         }
     }
-    if (g == 0 && live && p.action) {
+    if (p.action) {
+        // every lane of a state's 4 lane groups takes the actions a = g, g+4, ... : e_a = exp(l_a - max)
         const float* lg = stage + j * HD_PITCH;
-        p.value[row] = lg[A];
         float m = lg[0];
         for (int a = 1; a < A; ++a) m = fmaxf(m, lg[a]);
-        float Z = 0.0f;
-        for (int a = 0; a < A; ++a) Z += expf(lg[a] - m);
-        const float thr = p.uniforms[row] * Z;
-        float cum = 0.0f;
-        int act = A - 1;
-        for (int a = 0; a < A; ++a) {
-            cum += expf(lg[a] - m);
-            if (cum > thr) { act = a; break; }
+        for (int a = g; a < A; a += 4) stage_e[j * HD_PITCH + a] = expf(lg[a] - m);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (g == 0 && live) {   // one lane per state: normaliser and scan in index order
+            const float* ex = stage_e + j * HD_PITCH;
+            p.value[row] = lg[A];
+            float Z = 0.0f;
+            for (int a = 0; a < A; ++a) Z += ex[a];
+            const float thr = p.uniforms[row] * Z;
+            float cum = 0.0f;
+            int act = A - 1;
+            for (int a = 0; a < A; ++a) {
+                cum += ex[a];
+                if (cum > thr) { act = a; break; }
+            }
+            p.action[row] = act;
         }
-        p.action[row] = act;
     }
 }
 
@@ -155,7 +164,7 @@ hipError_t launch_heads(const HeadsParams& p, Elem el, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
     const int nt = (p.A + 1 + 15) / 16;
     if (!heads_supported(p.k_steps, p.Kp_bytes) || nt > 4) return hipErrorInvalidValue;
-    const size_t lds = (size_t)nt * p.k_steps * 1024 + (size_t)HD_WAVES * 16 * HD_PITCH * 4;
+    const size_t lds = (size_t)nt * p.k_steps * 1024 + (size_t)HD_WAVES * 2 * 16 * HD_PITCH * 4;
     dim3 grid((unsigned)((p.B + HD_WAVES * 16 - 1) / (HD_WAVES * 16)));
     return el == EL_I8 ? heads_nt<EL_I8>(p, nt, grid, lds, s) : heads_nt<EL_BF16>(p, nt, grid, lds, s);
 }
