@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="only the headline workload")
+    ap.add_argument("--copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a known-size reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (states are independent rows; a fleet of actors "
@@ -120,6 +122,13 @@ def main():
     outs = student.alloc_outputs(B)
     torch.cuda.synchronize()
 
+    if args.copy_mb:
+        src = torch.empty(args.copy_mb << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     # ---- headline: K timed steps of the student
     sec = time_forward(student, x, u, outs, args.steps, args.warmup, **kw)
     value = B / sec
@@ -148,6 +157,8 @@ def main():
     dom = max(breakdown, key=lambda e: e["ms_per_step"])
     launches = dom["launches_per_step"]
     avg_launch_s = dom["ms_per_step"] * 1e-3 / launches
+    obs_bytes = int(np.prod(ns.obs_shape)) * (1 if ns.obs_dtype == "u8" else 4)
+    first_param = min(macs) if macs else -1
     if dom["kind"] in ("conv", "gemm", "heads"):
         m = macs[dom["layer"]]
         if dom["layer"] < len(ns.layers) and ns.layers[dom["layer"]]["kind"] == "resblock":
@@ -155,10 +166,21 @@ def main():
         is_bf16 = student.recurrent and dom["layer"] >= len(ns.layers) - 1
         ops_launch = 2.0 * m * B / launches
         peak = PEAK["bf16" if is_bf16 else "int8"]
-        roofline = dict(bound="mfma", achieved=round(ops_launch / avg_launch_s / 1e12, 3), peak=peak / 1e12,
-                        unit="TFLOP/s", frac=round(ops_launch / avg_launch_s / peak, 4), traffic=None,
-                        kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
-                        launches_per_step=launches)
+        t_mfma = ops_launch / peak
+        t_hbm = obs_bytes * B / launches / PEAK["hbm"] if dom["layer"] == first_param else 0.0
+        if t_hbm > t_mfma:
+            # the kernel that reads the observations: its algorithmic bytes (the observation, read once)
+            # take longer at HBM peak than its multiply-accumulates at MFMA peak
+            bytes_launch = obs_bytes * B / launches
+            roofline = dict(bound="hbm", achieved=round(bytes_launch / avg_launch_s / 1e9, 2), peak=PEAK["hbm"] / 1e9,
+                            unit="GB/s", frac=round(bytes_launch / avg_launch_s / PEAK["hbm"], 4), traffic=None,
+                            kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                            launches_per_step=launches, mfma_frac=round(ops_launch / avg_launch_s / peak, 4))
+        else:
+            roofline = dict(bound="mfma", achieved=round(ops_launch / avg_launch_s / 1e12, 3), peak=peak / 1e12,
+                            unit="TFLOP/s", frac=round(ops_launch / avg_launch_s / peak, 4), traffic=None,
+                            kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                            launches_per_step=launches)
     else:
         bytes_launch = io_bytes(ns) * B / launches
         roofline = dict(bound="hbm", achieved=round(bytes_launch / avg_launch_s / 1e9, 2), peak=PEAK["hbm"] / 1e9,
@@ -195,7 +217,7 @@ def main():
     if not args.no_cpu:
         import oracle
         from oracle import layers as OL
-        nsamp = {0: B, 1: B, 2: 512, 3: 256, 4: 128}.get(ci, 256)
+        nsamp = {0: B, 1: B, 2: 4096, 3: 2048, 4: 2048}.get(ci, 256)
         nsamp = min(nsamp, B)
         qp = oracle.QuantPolicy(tensors=tensors, act_scales=act_scales)
         okw = {}
@@ -207,7 +229,7 @@ def main():
         t0 = time.perf_counter()
         ref = oracle.forward_int8(ns, qp, x_host[:nsamp], u_host[:nsamp], **okw)
         dt = time.perf_counter() - t0
-        while dt * reps < 2.0 and reps < 4096:       # tiny networks: repeat to get a stable figure
+        while dt * reps < 4.0 and reps < 4096:       # small networks: repeat to get a stable figure
             reps *= 4
             t0 = time.perf_counter()
             for _ in range(reps):
