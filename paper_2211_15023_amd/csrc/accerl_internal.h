@@ -63,7 +63,10 @@ struct ConvParams {
     int in_rows;             // (TH-1)*s + k
     int pitch;               // bytes per LDS input row
     int tile_stride;         // LDS bytes per image tile (multiple of 16)
-    int lds_tiles;           // LDS bytes of all G tiles plus read slack
+    int lds_tiles;           // LDS bytes of all tiles (every wave's, if wave-private) plus read slack
+    int wave_private;        // every wavefront owns its batches of G images and its own LDS region
+    int wave_tiles;          // wave-private: LDS bytes per wavefront region
+    int wp_pt;               // wave-private: pixel tiles per iteration
     int cpr;                 // 16-byte chunks per kernel row
     int k_steps;             // MFMA steps (4 chunks each)
     int w_bytes;             // bytes of wfrag
@@ -85,6 +88,9 @@ struct ConvParams {
 hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s);
 bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, int* KS, int* PF);
 int conv_pixel_tiles(int NT);
+constexpr int CONV_LDS_CONST = 512;   // LDS bytes for bias and multipliers in the LDS-weight kernels
+bool conv_wp_available(Elem el, int NT, int RD, int PT, int units);
+constexpr int CONV_WP_NWAVES = 8;
 
 // ---------------------------------------------------------------- max pooling on NHWC
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,

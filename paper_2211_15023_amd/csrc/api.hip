@@ -271,7 +271,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     const bool whole = mode == CM_FLAT;             // tiles are whole images, staged contiguously
 
     int RD = [&] { int al = gcd_int(16, gcd_int(ss * pix, pitch)); return al < 4 ? 4 : al; }();
-    const int w_lds_max = w_bytes + k_steps * 16;
+    const int w_lds_max = w_bytes + k_steps * 16 + CONV_LDS_CONST;
     const int PT = conv_pixel_tiles(NT);
 
     // band height: units to stage per tile <= 4096 (16 per lane), LDS within budget
@@ -312,14 +312,31 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         for (int gg = 1; gg <= gmax; ++gg) best = util_of(gg) > best ? util_of(gg) : best;
         for (int gg = 1; gg <= gmax; ++gg) if (util_of(gg) >= best - 0.03) G = gg;
     }
+    // wave-private kernel for plain-copy tiles with LDS weights: 8 wavefronts, each with its own images
+    int wp_G = 0, wp_PT = 0, wp_wave_tiles = 0;
+    if (el == EL_I8 && mode == CM_FLAT && NT == 4 && n_bands == 1 && !getenv("ACCERL_NO_WAVE_PRIVATE")) {
+        double best = -1.0;
+        for (int gg = 1; gg <= 8; ++gg) {
+            const int wt = (int)up((int64_t)gg * tile_stride + 32, 16);
+            if (w_lds_max + CONV_WP_NWAVES * wt > lds_cap) break;
+            for (int pt = 4; pt >= 3; --pt) {
+                if (!conv_wp_available(el, NT, RD, pt, gg * units_img)) continue;
+                const int tiles = (gg * n_pix + 15) / 16, slots = (tiles + pt - 1) / pt * pt;
+                const double util = (double)gg * n_pix / (slots * 16.0);
+                if (util > best + 1e-9 || (util > best - 1e-9 && gg > wp_G)) { best = util; wp_G = gg; wp_PT = pt; wp_wave_tiles = wt; }
+            }
+        }
+    }
     int KS = 0, PF = 16;
-    if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, &KS, &PF))
+    if (wp_G) { G = wp_G; }
+    else if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, &KS, &PF))
         return fail(ACCERL_EUNSUPPORTED, "layer %d: no convolution kernel covers this shape", layer);
     if (!KS && RD == 8) RD = 4;                     // the generic LDS-weight kernels read chunks at 16 or 4 bytes
     c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_out;
     c.k = kk; c.s = ss; c.pad = pad; c.TH = TH; c.n_bands = n_bands;
     c.in_rows = whole ? Ht : rows_of(TH); c.pitch = pitch; c.tile_stride = tile_stride;
-    c.lds_tiles = G * tile_stride + 32;
+    c.lds_tiles = wp_G ? CONV_WP_NWAVES * wp_wave_tiles : G * tile_stride + 32;
+    c.wave_private = wp_G ? 1 : 0; c.wave_tiles = wp_wave_tiles; c.wp_pt = wp_PT;
     c.cpr = cpr; c.k_steps = k_steps; c.w_bytes = w_bytes;
     c.relu_in = relu_in; c.relu = relu; c.src_u8 = src_u8;
     c.mode = mode; c.G = G;
@@ -876,6 +893,10 @@ int run(accerl_policy* p, const Call& c) {
                         int64_t groups = 768 / cp.n_bands;
                         if (groups < 1) groups = 1;
                         if (groups > n_batch) groups = n_batch;
+                        if (cp.wave_private) {          // one workgroup of 8 wavefronts per compute unit
+                            groups = (n_batch + CONV_WP_NWAVES - 1) / CONV_WP_NWAVES;
+                            if (groups > 256) groups = 256;
+                        }
                         cp.groups = (int)groups;
                     }
                     e = launch_conv(cp, s.el, s.NT, s.KS, s.RD, s.PF, c.stream);
@@ -1062,12 +1083,12 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
         const Step& s = pol.steps[i];
         if (s.kind == ST_CONV) {
             const ConvParams& c = s.cp;
-            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16) + (long)c.lds_tiles;
+            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles;
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
-                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld vec_ok=%d\n",
+                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld vec_ok=%d wp=%d pt=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
-                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.vec_ok);
+                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.vec_ok, c.wave_private, c.wp_pt);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu);

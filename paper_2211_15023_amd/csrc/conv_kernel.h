@@ -14,6 +14,11 @@
 // the whole kernel, so LDS only feeds the pixel operand: one 16-byte read per lane serves NT MFMAs.
 // Otherwise they sit in LDS in fragment order.
 //
+// Wave-private variant (WP).  For layers whose tiles are plain copies, every wavefront of a workgroup
+// (8 of them) owns its own batch of images and its own LDS region, shares only the weights, and never
+// meets the others at a barrier after start-up: while one wavefront requantizes or stages, the other
+// one on its SIMD keeps the matrix core busy.
+//
 // Latency.  The global loads of batch i+1 are issued into registers before the MFMA work of batch i
 // and written to LDS afterwards, so HBM latency hides behind compute inside one workgroup.
 //
@@ -25,8 +30,6 @@
 
 namespace accerl {
 
-constexpr int CONV_THREADS = 256;
-constexpr int CONV_WAVES = CONV_THREADS / 64;
 
 __device__ __forceinline__ uint32_t relu_i8x4(uint32_t x) {
     const uint32_t neg = (x & 0x80808080u) >> 7;
@@ -58,8 +61,17 @@ __device__ __forceinline__ v4i read_chunk(const char* p) {
     }
 }
 
-template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT>
-__global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_wave_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// NW: wavefronts per workgroup.  WP: wave-private batches (see above); else the workgroup shares one batch.
+template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const ConvParams p) {
+    constexpr int CONV_THREADS = NW * 64;
+    constexpr int SN = WP ? 64 : CONV_THREADS;      // lanes that stage one batch together
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int ESZ = (EL == EL_I8) ? 1 : 2;
     constexpr int KSR = KS > 0 ? KS : 1;
@@ -68,7 +80,10 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
     const int pix = p.Cs_in * ESZ;                          // bytes per stored input pixel
     char* wl = smem;                                        // KS == 0: weight fragments + chunk offsets
     int* koff_lds = (int*)(smem + p.w_bytes);
-    char* tiles = (KS > 0) ? smem : smem + p.w_bytes + p.k_steps * 16;
+    char* cst_lds = smem + p.w_bytes + p.k_steps * 16;        // KS == 0: bias and multipliers, [2][NT*16] words
+    char* tiles_all = (KS > 0) ? smem : cst_lds + CONV_LDS_CONST;
+    char* tiles = tiles_all + (WP ? wave * p.wave_tiles : 0);
+    const int stid = WP ? lane : tid;               // index of this lane among those staging its batch
 
     auto chunk_off = [&](int q) -> int {
         const int ky = q / p.cpr, cx = q - ky * p.cpr;
@@ -91,22 +106,33 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
     }
     {
         const int padv = (EL == EL_I8 && p.src_u8) ? (int)0x80808080u : 0;
-        for (int i = tid; i < p.lds_tiles / 4; i += CONV_THREADS) ((int*)tiles)[i] = padv;
+        for (int i = tid; i < p.lds_tiles / 4; i += CONV_THREADS) ((int*)tiles_all)[i] = padv;
     }
 
-    // per-lane epilogue constants: channels 4*NT*g .. 4*NT*g + 4*NT - 1
-    v4i bi[NT];
-    v4f bfl[NT];
-    v4f ml[NT];
+    // per-lane epilogue constants: channels 4*NT*g .. 4*NT*g + 4*NT - 1.  Register-weight kernels keep
+    // them in registers; LDS-weight kernels (short on registers) keep them in LDS and fetch them per tile.
+    constexpr bool CREG = KS > 0;
+    v4i bi[CREG ? NT : 1];
+    v4f bfl[CREG ? NT : 1];
+    v4f ml[CREG ? NT : 1];
+    if constexpr (CREG) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        if constexpr (EL == EL_I8) {
-            bi[t] = *(const v4i*)((const int*)p.bias + 4 * NT * g + 4 * t);
-            ml[t] = *(const v4f*)(p.mult + 4 * NT * g + 4 * t);
-        } else {
-            bfl[t] = *(const v4f*)((const float*)p.bias + 4 * NT * g + 4 * t);
+        for (int t = 0; t < NT; ++t) {
+            if constexpr (EL == EL_I8) {
+                bi[t] = *(const v4i*)((const int*)p.bias + 4 * NT * g + 4 * t);
+                ml[t] = *(const v4f*)(p.mult + 4 * NT * g + 4 * t);
+            } else {
+                bfl[t] = *(const v4f*)((const float*)p.bias + 4 * NT * g + 4 * t);
+            }
+        }
+    } else {
+        for (int i = tid; i < NT * 16; i += CONV_THREADS) {
+            ((int*)cst_lds)[i] = ((const int*)p.bias)[i];
+            if constexpr (EL == EL_I8) ((float*)cst_lds)[NT * 16 + i] = p.mult[i];
         }
     }
+    const v4i* bias_l = (const v4i*)(cst_lds + (4 * NT * g) * 4);              // [t] -> bias of channels 4NTg+4t..
+    const v4f* mult_l = (const v4f*)(cst_lds + (NT * 16 + 4 * NT * g) * 4);
 
     const int band = blockIdx.x;
     const int oy0 = band * p.TH;
@@ -133,7 +159,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         const int n_units = p.G * p.units_img;
 #pragma unroll
         for (int i = 0; i < PF; ++i) {
-            const int u = min(tid + i * CONV_THREADS, n_units - 1);
+            const int u = min(stid + i * SN, n_units - 1);
             const int img = (int)fdiv((uint32_t)u, p.magic_units);
             const int w = u - img * p.units_img;
             const int rr = (int)fdiv((uint32_t)w, p.magic_rowunits);
@@ -167,14 +193,14 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
             const char* src = (const char*)p.in + b0 * (int64_t)p.img_bytes;
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                const int u = min(tid + i * CONV_THREADS, last);
+                const int u = min(stid + i * SN, last);
                 pre[i] = *(const v4i*)(src + (uint32_t)u * 16u);
             }
         } else if constexpr (MODE == CM_ROWS) {
             const char* src = (const char*)p.in + b0 * (int64_t)p.H * row_bytes_img;
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                const uint32_t so = (tid + i * CONV_THREADS <= last) ? soff[i] : 0u;   // a unit of a missing image reads image 0
+                const uint32_t so = (stid + i * SN <= last) ? soff[i] : 0u;   // a unit of a missing image reads image 0
                 if (p.vec_ok) {
                     pre[i] = *(const v4i*)(src + so + (uint32_t)ooff[i]);
                 } else {
@@ -190,7 +216,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
             const int plane = p.H * p.W;
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                const uint32_t so = (tid + i * CONV_THREADS <= last) ? soff[i] : 0u;
+                const uint32_t so = (stid + i * SN <= last) ? soff[i] : 0u;
                 v4i v;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) v[c] = *(const int*)(src + (uint32_t)(min(c, p.Cin_real - 1) * plane) + so);
@@ -204,7 +230,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         const int total = gc * p.units_img;
 #pragma unroll
         for (int i = 0; i < PF; ++i) {
-            const int u = tid + i * CONV_THREADS;
+            const int u = stid + i * SN;
             if (u >= total) break;
             v4i v = pre[i];
             if constexpr (MODE != CM_U8T) {
@@ -257,13 +283,14 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         }
     };
 
-    int64_t batch = blockIdx.y;
+    int64_t batch = WP ? (int64_t)blockIdx.y * NW + wave : blockIdx.y;
+    const int64_t bstride = WP ? (int64_t)gridDim.y * NW : gridDim.y;
     if (batch < n_batch) prefetch(batch);
     __syncthreads();   // padding fill (and LDS weights) visible before the first commit / compute
-    for (; batch < n_batch; batch += gridDim.y) {
+    for (; batch < n_batch; batch += bstride) {
         commit(batch);
-        __syncthreads();
-        if (batch + gridDim.y < n_batch) prefetch(batch + gridDim.y);
+        if constexpr (WP) conv_wave_fence(); else __syncthreads();
+        if (batch + bstride < n_batch) prefetch(batch + bstride);
 
         const int64_t b0 = batch * p.G;
         const int gc = (int)((p.B - b0 < p.G) ? (p.B - b0) : p.G);
@@ -273,7 +300,7 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
         char* out_b = (char*)p.out + base_el * ESZ;
         const char* res_b = (const char*)p.res + base_el * ESZ;
         int32_t* tap_b = p.tap_acc + base_el;
-        for (int t0 = wave * PT; t0 < n_tiles; t0 += CONV_WAVES * PT) {
+        for (int t0 = (WP ? 0 : wave * PT); t0 < n_tiles; t0 += (WP ? 1 : NW) * PT) {
             int pb[PT], pimg[PT], ppix[PT];   // tile-relative pixel offset, tile offset, pixel number
 #pragma unroll
             for (int u = 0; u < PT; ++u) {
@@ -292,14 +319,19 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
             for (int u = 0; u < PT; ++u)
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    if constexpr (EL == EL_I8) acc_i[u][t] = bi[t];   // the bias rides in the accumulator
-                    else acc_f[u][t] = bfl[t];
+                    // the bias rides in the accumulator
+                    if constexpr (EL == EL_I8) acc_i[u][t] = CREG ? bi[CREG ? t : 0] : bias_l[t];
+                    else acc_f[u][t] = CREG ? bfl[CREG ? t : 0] : __builtin_bit_cast(v4f, bias_l[t]);
                 }
-            auto step = [&](const v4i (&a)[NT], int off) {
-                v4i bq[PT];
+            auto load_b = [&](v4i (&bq)[PT], int off) {
 #pragma unroll
-                for (int u = 0; u < PT; ++u)
-                    bq[u] = read_chunk<RD>(tiles + pimg[u] + pb[u] + off);
+                for (int u = 0; u < PT; ++u) bq[u] = read_chunk<RD>(tiles + pimg[u] + pb[u] + off);
+            };
+            auto load_a = [&](v4i (&a)[NT], int st) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) a[t] = *(const v4i*)(wl + ((st * NT + t) * 64 + lane) * 16);
+            };
+            auto mfma = [&](const v4i (&a)[NT], const v4i (&bq)[PT]) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -314,13 +346,17 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
             };
             if constexpr (KS > 0) {
 #pragma unroll
-                for (int st = 0; st < KS; ++st) step(wreg[st], koffr[st]);
+                for (int st = 0; st < KS; ++st) {
+                    v4i bq[PT];
+                    load_b(bq, koffr[st]);
+                    mfma(wreg[st], bq);
+                }
             } else {
                 for (int st = 0; st < p.k_steps; ++st) {
-                    v4i a[NT];
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) a[t] = *(const v4i*)(wl + ((st * NT + t) * 64 + lane) * 16);
-                    step(a, koff_lds[st * 4 + g]);
+                    v4i a[NT], bq[PT];
+                    load_a(a, st);
+                    load_b(bq, koff_lds[st * 4 + g]);
+                    mfma(a, bq);
                 }
             }
             // ---- epilogue: this lane owns channels c0 .. c0 + 4*NT - 1 of its pixel
@@ -336,6 +372,9 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                 if constexpr (EL == EL_I8) {
                     uint32_t pk[NT];
                     uint32_t xr[NT];
+                    v4f mq[NT];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) mq[t] = CREG ? ml[CREG ? t : 0] : mult_l[t];
                     if (p.res) {
 #pragma unroll
                         for (int t = 0; t < NT; ++t)   // lanes past the last channel re-read a valid group (not stored)
@@ -350,18 +389,18 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
                                 const float tr = (float)(int)(int8_t)(xr[t] >> (8 * r)) * p.r;
-                                const float y = __builtin_amdgcn_fmed3f(rintf(fmaf((float)v[r], ml[t][r], tr)), -127.0f, 127.0f);
+                                const float y = __builtin_amdgcn_fmed3f(rintf(fmaf((float)v[r], mq[t][r], tr)), -127.0f, 127.0f);
                                 w |= ((uint32_t)(int)y & 0xffu) << (8 * r);
                             }
                         } else if (p.relu) {
                             // clamp(rint(y), 0, 127): the pack instruction rounds to nearest even and saturates at 0
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
-                                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)v[r] * ml[t][r], 0.0f, 127.0f), r, w);
+                                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)v[r] * mq[t][r], 0.0f, 127.0f), r, w);
                         } else {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                const float y = __builtin_amdgcn_fmed3f(rintf((float)v[r] * ml[t][r]), -127.0f, 127.0f);
+                                const float y = __builtin_amdgcn_fmed3f(rintf((float)v[r] * mq[t][r]), -127.0f, 127.0f);
                                 w |= ((uint32_t)(int)y & 0xffu) << (8 * r);
                             }
                         }
@@ -412,30 +451,31 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_kernel(const ConvParams 
                 }
             }
         }
-        __syncthreads();   // every wave is done reading the tiles before the next commit overwrites them
+        // every wave is done reading the tiles before the next commit overwrites them
+        if constexpr (WP) conv_wave_fence(); else __syncthreads();
     }
 }
 
 
-template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT>
+template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP>
 hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
-    auto kfn = conv_kernel<EL, NT, KS, RD, MODE, PF, PT>;
+    auto kfn = conv_kernel<EL, NT, KS, RD, MODE, PF, PT, NW, WP>;
     static size_t set_lds = 0;   // per instantiation: raise the dynamic LDS limit when needed
     if (lds > set_lds) {
         hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         set_lds = lds;
     }
-    kfn<<<grid, dim3(CONV_THREADS), lds, s>>>(p);
+    kfn<<<grid, dim3(NW * 64), lds, s>>>(p);
     return hipGetLastError();
 }
 
-// Pixel tiles per wave iteration: 4 when a layer has 4 channel tiles (each weight fragment read from
-// LDS then serves 4 MFMAs), else 2.
+// Pixel tiles per wave iteration of the shared-batch kernels: 4 when a layer has 4 channel tiles (each
+// weight fragment read from LDS then serves 4 MFMAs), else 2.
 constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
 
-// Tuned variants: (element, NT, KS, RD, staging mode, PF).  KS > 0 keeps the weights in registers and
-// unrolls that many MFMA steps; KS = 0 reads them from LDS for any number of steps.
+// Tuned shared-batch variants: (element, NT, KS, RD, staging mode, PF).  KS > 0 keeps the weights in
+// registers and unrolls that many MFMA steps; KS = 0 reads them from LDS for any number of steps.
 #define ACCERL_TUNED_I8(X)                                                                              \
     X(EL_I8, 2, 4, 16, CM_U8T, 8) X(EL_I8, 1, 4, 16, CM_U8T, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
     X(EL_I8, 4, 0, 16, CM_FLAT, 10) X(EL_I8, 2, 4, 16, CM_FLAT, 8) X(EL_I8, 1, 2, 16, CM_FLAT, 8)      \
@@ -446,15 +486,20 @@ constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
     X(EL_BF16, 2, 5, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 8) \
     X(EL_BF16, 4, 0, 16, CM_FLAT, 8)
 
+// Wave-private variants (8 wavefronts, weights in LDS, contiguous staging): (element, NT, RD, PF, PT)
+constexpr int CONV_WP_WAVES = 8;
+constexpr int CONV_WP_PF = 14;
+#define ACCERL_WP_I8(X) X(EL_I8, 4, 16, CONV_WP_PF, 3) X(EL_I8, 4, 16, CONV_WP_PF, 4)
+
 // everything else: weights in LDS, chunk reads at 16- or 4-byte alignment, 16 staging units per lane
 template <int EL, int NT>
 hipError_t conv_go_generic(const ConvParams& p, int rd, dim3 grid, size_t lds, hipStream_t s) {
     const bool a16 = rd == 16;
     constexpr int PT = conv_pt(NT);
     switch (p.mode) {
-        case CM_FLAT: return a16 ? conv_go<EL, NT, 0, 16, CM_FLAT, 16, PT>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_FLAT, 16, PT>(p, grid, lds, s);
-        case CM_ROWS: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWS, 16, PT>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWS, 16, PT>(p, grid, lds, s);
-        case CM_U8T: return a16 ? conv_go<EL, NT, 0, 16, CM_U8T, 16, PT>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_U8T, 16, PT>(p, grid, lds, s);
+        case CM_FLAT: return a16 ? conv_go<EL, NT, 0, 16, CM_FLAT, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_FLAT, 16, PT, 4, false>(p, grid, lds, s);
+        case CM_ROWS: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWS, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWS, 16, PT, 4, false>(p, grid, lds, s);
+        case CM_U8T: return a16 ? conv_go<EL, NT, 0, 16, CM_U8T, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_U8T, 16, PT, 4, false>(p, grid, lds, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -462,6 +507,7 @@ hipError_t conv_go_generic(const ConvParams& p, int rd, dim3 grid, size_t lds, h
 // one translation unit per family keeps the build parallel
 hipError_t conv_launch_tuned_i8(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
 hipError_t conv_launch_tuned_bf16(const ConvParams& p, int NT, int KS, int RD, int pf, dim3 grid, size_t lds, hipStream_t s);
+hipError_t conv_launch_wp_i8(const ConvParams& p, int NT, int RD, int PT, dim3 grid, size_t lds, hipStream_t s);
 hipError_t conv_launch_gen_i8(const ConvParams& p, int NT, int RD, dim3 grid, size_t lds, hipStream_t s);
 hipError_t conv_launch_gen_bf16(const ConvParams& p, int NT, int RD, dim3 grid, size_t lds, hipStream_t s);
 

@@ -26,11 +26,26 @@ bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, i
 
 int conv_pixel_tiles(int NT) { return conv_pt(NT); }
 
+// Wave-private variant for a contiguous-staging int8 layer: true if one exists for (NT, RD, PT) and a
+// wavefront can stage `units` 16-byte units (one batch) by itself.
+bool conv_wp_available(Elem el, int NT, int RD, int PT, int units) {
+    if (el != EL_I8 || units > 64 * CONV_WP_PF) return false;
+#define X(E, N, R, P, T) if (NT == N && RD == R && PT == T) return true;
+    ACCERL_WP_I8(X)
+#undef X
+    return false;
+}
+
 hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
-    const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16) + (size_t)p.lds_tiles;
-    if ((p.G * p.units_img + CONV_THREADS - 1) / CONV_THREADS > PF || p.groups < 1) return hipErrorInvalidValue;
+    const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16 + CONV_LDS_CONST) + (size_t)p.lds_tiles;
+    if (p.groups < 1) return hipErrorInvalidValue;
     dim3 grid((unsigned)p.n_bands, (unsigned)p.groups);
+    if (p.wave_private) {
+        if (KS != 0 || p.mode != CM_FLAT || p.n_bands != 1 || p.G * p.units_img > 64 * CONV_WP_PF) return hipErrorInvalidValue;
+        return conv_launch_wp_i8(p, NT, RD, p.wp_pt, grid, lds, s);
+    }
+    if ((p.G * p.units_img + 255) / 256 > PF) return hipErrorInvalidValue;
     hipError_t e = el == EL_I8 ? conv_launch_tuned_i8(p, NT, KS, RD, PF, grid, lds, s)
                                : conv_launch_tuned_bf16(p, NT, KS, RD, PF, grid, lds, s);
     if (e != hipErrorNotFound) return e;

@@ -121,22 +121,35 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         commit(s0);
         __syncthreads();
         if (s0 + GM_KS < p.k_steps) prefetch(s0 + GM_KS);
-        for (int st = 0; st < ns; ++st) {
-            v4i bq[GM_RT];
+        // the fragments of step st+1 are requested from LDS before the MFMAs of step st are issued
+        auto load_f = [&](v4i (&a)[GM_NT], v4i (&bq)[GM_RT], int st) {
 #pragma unroll
             for (int u = 0; u < GM_RT; ++u)
                 bq[u] = *(const v4i*)(s_x + ((wave * GM_RT + u) * 16 + j) * GM_XPITCH + st * 64 + g * 16);
 #pragma unroll
-            for (int t = 0; t < GM_NT; ++t) {
-                const v4i a = *(const v4i*)(s_w + ((t * GM_KS + st) * 64 + lane) * 16);
+            for (int t = 0; t < GM_NT; ++t) a[t] = *(const v4i*)(s_w + ((t * GM_KS + st) * 64 + lane) * 16);
+        };
+        auto mfma = [&](const v4i (&a)[GM_NT], const v4i (&bq)[GM_RT]) {
+#pragma unroll
+            for (int t = 0; t < GM_NT; ++t)
 #pragma unroll
                 for (int u = 0; u < GM_RT; ++u) {
                     if constexpr (EL == EL_I8) {
-                        acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bq[u], acc_i[u][t], 0, 0, 0);
+                        acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t], bq[u], acc_i[u][t], 0, 0, 0);
                     } else {
                         acc_f[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, bq[u]), acc_f[u][t], 0, 0, 0);
+                            __builtin_bit_cast(v8bf, a[t]), __builtin_bit_cast(v8bf, bq[u]), acc_f[u][t], 0, 0, 0);
                     }
+                }
+        };
+        {
+            v4i fa[2][GM_NT], fb[2][GM_RT];
+            load_f(fa[0], fb[0], 0);
+#pragma unroll
+            for (int st = 0; st < GM_KS; ++st) {
+                if (st < ns) {
+                    if (st + 1 < ns) load_f(fa[(st + 1) & 1], fb[(st + 1) & 1], st + 1);
+                    mfma(fa[st & 1], fb[st & 1]);
                 }
             }
         }
