@@ -57,7 +57,8 @@ struct ConvParams {
     int Cin_real;            // channels present in the source
     int Cs_in;               // stored channels per input pixel (multiple of 4)
     int Ho, Wo, Cs_out;
-    int k, s, pad;
+    int k, s, pad;           // kernel rows, vertical stride, padding
+    int sx;                  // horizontal stride in input pixels (a multiple of s when output pixels are packed)
     int TH;                  // output rows per band
     int n_bands;
     int in_rows;             // (TH-1)*s + k
@@ -78,7 +79,7 @@ struct ConvParams {
     int img_bytes;           // FLAT: contiguous bytes per image
     int units_img;           // 16-byte staging units per image tile
     int row_units;           // ROWS / U8T: units per tile row
-    int vec_ok;              // ROWS: every unit is one aligned 16-byte load or pure padding
+    int vec_ok;              // ROWS: image rows are whole 16-byte units, each staged by one aligned load
     uint32_t magic_npix, magic_wo, magic_units, magic_rowunits;   // ceil(2^32/d), 0 for d = 1
     float r;                 // residual ratio (int8 path)
     int groups;              // grid.y

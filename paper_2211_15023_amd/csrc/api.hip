@@ -249,14 +249,28 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     const int Cs_out = (int)up(Cout, 4);
     if (src_u8 && Cin > 4) return fail(ACCERL_EUNSUPPORTED, "uint8 observations with more than 4 channels");
     if (src_u8 && (W & 3)) return fail(ACCERL_EUNSUPPORTED, "uint8 observation width must be a multiple of 4");
-    const int NT = (Cout <= 16) ? 1 : (Cout <= 32) ? 2 : (Cout <= 64) ? 4 : 0;
+    const int Ho = out_hw(H, k, s, pad), Wo_img = out_hw(W, k, s, pad);
+    // Thin layers (at most 8 stored output channels): P horizontally adjacent output pixels are computed
+    // as one pixel of a layer with P times the channels, a kernel row wider by (P-1) strides (zero weights
+    // where a tap lies outside a pixel's own window) and P times the horizontal stride.  The bytes written
+    // are the same channels-last image; every MFMA row and every epilogue lane then does useful work.
+    int P = 1;
+    if (Cs_out <= 8 && !getenv("ACCERL_NO_PIXEL_PACK")) {
+        P = 16 / Cs_out;
+        while (P > 1 && (Wo_img % P)) P >>= 1;
+    }
+    const int Cs_img = Cs_out;                      // stored channels per real output pixel
+    const int CoutK = P > 1 ? P * Cs_img : Cout;    // channels of the layer the kernel sees
+    const int Cs_outK = P > 1 ? P * Cs_img : Cs_out;
+    const int Wo = Wo_img / P;
+    const int kw = k + (P - 1) * s, sx = P * s;
+    const int NT = (CoutK <= 16) ? 1 : (CoutK <= 32) ? 2 : (CoutK <= 64) ? 4 : 0;
     if (!NT) return fail(ACCERL_EUNSUPPORTED, "layer %d: more than 64 output channels", layer);
-    const int Ho = out_hw(H, k, s, pad), Wo = out_hw(W, k, s, pad);
     const int Cs_in = (int)up(Cin, 4);
     const int pix = Cs_in * esz;
     const int kk = k, ss = s;
     const int Wt = W, Ht = H;
-    const int run = kk * pix;                       // bytes of one kernel row of one pixel
+    const int run = kw * pix;                       // bytes of one kernel row of one (packed) pixel
     const int cpr = (run + 15) / 16;
     const int chunks = kk * cpr;
     const int k_steps = (chunks + 3) / 4;
@@ -269,8 +283,9 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     else if (pad == 0 && ((H * row_bytes) % 16) == 0) { mode = CM_FLAT; pitch = row_bytes; }
     else { mode = CM_ROWS; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
     const bool whole = mode == CM_FLAT;             // tiles are whole images, staged contiguously
+    const bool rows_vec = (row_bytes % 16) == 0;    // ROWS: image rows are whole 16-byte units (else gathered by dwords)
 
-    int RD = [&] { int al = gcd_int(16, gcd_int(ss * pix, pitch)); return al < 4 ? 4 : al; }();
+    int RD = [&] { int al = gcd_int(16, gcd_int(sx * pix, pitch)); return al < 4 ? 4 : al; }();
     const int w_lds_max = w_bytes + k_steps * 16 + CONV_LDS_CONST;
     const int PT = conv_pixel_tiles(NT);
 
@@ -284,7 +299,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     auto units_of = [&](int th) {
         if (whole) return tile_of(th) / 16;
         if (mode == CM_U8T) return rows_of(th) * (W / 4);
-        return rows_of(th) * (pitch / 16);
+        return rows_of(th) * (rows_vec ? row_bytes / 16 : pitch / 16);
     };
     int TH = Ho;
     if (!whole) {
@@ -332,8 +347,8 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     else if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, &KS, &PF))
         return fail(ACCERL_EUNSUPPORTED, "layer %d: no convolution kernel covers this shape", layer);
     if (!KS && RD == 8) RD = 4;                     // the generic LDS-weight kernels read chunks at 16 or 4 bytes
-    c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_out;
-    c.k = kk; c.s = ss; c.pad = pad; c.TH = TH; c.n_bands = n_bands;
+    c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_outK;
+    c.k = kk; c.s = ss; c.sx = sx; c.pad = pad; c.TH = TH; c.n_bands = n_bands;
     c.in_rows = whole ? Ht : rows_of(TH); c.pitch = pitch; c.tile_stride = tile_stride;
     c.lds_tiles = wp_G ? CONV_WP_NWAVES * wp_wave_tiles : G * tile_stride + 32;
     c.wave_private = wp_G ? 1 : 0; c.wave_tiles = wp_wave_tiles; c.wp_pt = wp_PT;
@@ -342,12 +357,12 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     c.mode = mode; c.G = G;
     c.img_bytes = H * row_bytes;
     c.units_img = units_img;
-    c.row_units = mode == CM_U8T ? W / 4 : pitch / 16;
-    c.vec_ok = ((pad * pix) % 16 == 0) && (row_bytes % 16 == 0);
+    c.row_units = mode == CM_U8T ? W / 4 : rows_vec ? row_bytes / 16 : pitch / 16;
+    c.vec_ok = rows_vec;
     c.magic_npix = magic_of(n_pix); c.magic_wo = magic_of(Wo);
     c.magic_units = magic_of(units_img); c.magic_rowunits = magic_of(c.row_units);
     st.NT = NT; st.KS = KS; st.RD = RD; st.PF = PF;
-    st.out_elems = (int64_t)Ho * Wo * Cs_out;
+    st.out_elems = (int64_t)Ho * Wo * Cs_outK;
     st.acc_elems = el == EL_I8 ? st.out_elems : 0;
 
     // ---- weight fragments: [k_step][n_tile][lane][16 bytes]; MFMA row i of tile tt is channel
@@ -361,7 +376,9 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
                 const int i = lane & 15, g = lane >> 4;
                 const int n = 4 * NT * (i >> 2) + 4 * tt + (i & 3);
                 const int q = 4 * stp + g;
-                if (n >= Cout) continue;
+                if (n >= CoutK) continue;
+                const int dx = n / Cs_img, ch = n - dx * Cs_img;   // packed pixel and its channel (dx = 0 unpacked)
+                if (ch >= Cout) continue;
                 char* dst = frag.data() + ((size_t)(stp * NT + tt) * 64 + lane) * 16;
                 for (int e = 0; e < epc; ++e) {
                     int ci, ky, kx;
@@ -371,8 +388,9 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
                         const int kbx = idx / Cs_in, rem = idx - kbx * Cs_in;
                         ky = kby; kx = kbx; ci = rem;
                     }
-                    if (ky >= k || kx >= k || ci >= Cin) continue;
-                    const int64_t src = (((int64_t)n * Cin + ci) * k + ky) * k + kx;
+                    kx -= dx * s;                               // tap inside this pixel's own window
+                    if (ky >= k || kx < 0 || kx >= k || ci >= Cin) continue;
+                    const int64_t src = (((int64_t)ch * Cin + ci) * k + ky) * k + kx;
                     if (el == EL_I8) {
                         const int8_t v = B.wq(t)[src];
                         dst[e] = (char)v;
@@ -387,18 +405,20 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     if (el == EL_I8) {
         std::vector<int32_t> bq(NT * 16, 0);
         std::vector<float> ml(NT * 16, 0.f);
-        for (int n = 0; n < Cout; ++n) {
-            int64_t b = Builder::biasq(B.bias(t)[n], s_in, B.sw(t)[n]);
+        for (int n = 0; n < CoutK; ++n) {
+            const int ch = n % Cs_img;
+            if (ch >= Cout) continue;
+            int64_t b = Builder::biasq(B.bias(t)[ch], s_in, B.sw(t)[ch]);
             if (src_u8) b += 128 * wsum[n];          // observations are staged as obs - 128
             bq[n] = (int32_t)b;
-            ml[n] = Builder::mult(s_in, B.sw(t)[n], s_out);
+            ml[n] = Builder::mult(s_in, B.sw(t)[ch], s_out);
         }
         st.o_bias = B.put(bq.data(), bq.size() * 4);
         st.o_mult = B.put(ml.data(), ml.size() * 4);
         c.r = res_buf >= 0 ? (float)((double)s_res / (double)s_out) : 0.f;
     } else {
         std::vector<float> bf(NT * 16, 0.f);
-        for (int n = 0; n < Cout; ++n) bf[n] = B.bias(t)[n];
+        for (int n = 0; n < CoutK; ++n) if (n % Cs_img < Cout) bf[n] = B.bias(t)[n % Cs_img];
         st.o_bias = B.put(bf.data(), bf.size() * 4);
         if (src_u8) {
             std::vector<uint16_t> lut(256);

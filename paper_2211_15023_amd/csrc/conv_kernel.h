@@ -168,14 +168,22 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
             const bool rin = iy >= 0 && iy < p.H;
             const int iyc = min(max(iy, 0), p.H - 1);
             if constexpr (MODE == CM_ROWS) {
-                const int o = cu * 16 - lead;
-                uint32_t m = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) m |= (rin && o + 4 * e >= 0 && o + 4 * e < row_bytes_img) ? (1u << e) : 0u;
-                smask[i] = m;
-                ooff[i] = p.vec_ok ? min(max(o, 0), row_bytes_img - 16) : o;
                 soff[i] = (uint32_t)((img * p.H + iyc) * row_bytes_img);
-                doff[i] = img * p.tile_stride + rr * p.pitch + cu * 16;
+                if (p.vec_ok) {
+                    // units are the aligned 16-byte pieces of the image rows; padding is never written
+                    smask[i] = 0xfu;
+                    ooff[i] = cu * 16;
+                    doff[i] = rin ? img * p.tile_stride + rr * p.pitch + lead + cu * 16 : -1;
+                } else {
+                    // units are the 16-byte pieces of the padded LDS rows, gathered dword by dword
+                    const int o = cu * 16 - lead;
+                    uint32_t m = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) m |= (rin && o + 4 * e >= 0 && o + 4 * e < row_bytes_img) ? (1u << e) : 0u;
+                    smask[i] = m;
+                    ooff[i] = o;
+                    doff[i] = img * p.tile_stride + rr * p.pitch + cu * 16;
+                }
             } else {
                 smask[i] = 0;
                 ooff[i] = 0;
@@ -235,16 +243,29 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
             v4i v = pre[i];
             if constexpr (MODE != CM_U8T) {
                 if constexpr (MODE == CM_ROWS) {
+                    if (doff[i] < 0) continue;                // row outside the image: stays padding
+                    if (!p.vec_ok) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = ((smask[i] >> e) & 1u) ? v[e] : 0;
+                        for (int e = 0; e < 4; ++e) v[e] = ((smask[i] >> e) & 1u) ? v[e] : 0;
+                    }
                 }
                 if (p.relu_in) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         v[e] = (int)((EL == EL_I8) ? relu_i8x4((uint32_t)v[e]) : relu_bf16x2((uint32_t)v[e]));
                 }
-                if constexpr (MODE == CM_FLAT) *(v4i*)(tiles + u * 16) = v;   // tiles of a batch are contiguous like the images
-                else *(v4i*)(tiles + doff[i]) = v;
+                if constexpr (MODE == CM_FLAT) {
+                    *(v4i*)(tiles + u * 16) = v;              // tiles of a batch are contiguous like the images
+                } else if ((lead & 15) == 0 || !p.vec_ok) {
+                    *(v4i*)(tiles + doff[i]) = v;
+                } else if ((lead & 7) == 0) {
+                    typedef int v2i __attribute__((ext_vector_type(2)));
+                    *(v2i*)(tiles + doff[i]) = (v2i){v[0], v[1]};
+                    *(v2i*)(tiles + doff[i] + 8) = (v2i){v[2], v[3]};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) *(int*)(tiles + doff[i] + 4 * e) = v[e];
+                }
             } else {
                 if (doff[i] < 0) continue;                    // row outside the image: stays padding
                 const uint32_t P0 = (uint32_t)v[0], P1 = (uint32_t)v[1], P2 = (uint32_t)v[2], P3 = (uint32_t)v[3];
@@ -310,7 +331,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
                 const int img = (int)fdiv((uint32_t)pp, p.magic_npix);
                 const int rem = pp - img * n_pix;
                 const int ty = (int)fdiv((uint32_t)rem, p.magic_wo), ox = rem - ty * p.Wo;
-                pb[u] = ty * p.s * p.pitch + ox * p.s * pix;
+                pb[u] = ty * p.s * p.pitch + ox * p.sx * pix;
                 pimg[u] = img * p.tile_stride;
             }
             v4i acc_i[PT][NT];
@@ -480,7 +501,7 @@ constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
     X(EL_I8, 2, 4, 16, CM_U8T, 8) X(EL_I8, 1, 4, 16, CM_U8T, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
     X(EL_I8, 4, 0, 16, CM_FLAT, 10) X(EL_I8, 2, 4, 16, CM_FLAT, 8) X(EL_I8, 1, 2, 16, CM_FLAT, 8)      \
     X(EL_I8, 1, 1, 8, CM_FLAT, 8) X(EL_I8, 1, 1, 4, CM_U8T, 8) X(EL_I8, 1, 2, 8, CM_ROWS, 8)           \
-    X(EL_I8, 1, 3, 16, CM_ROWS, 8)
+    X(EL_I8, 1, 3, 16, CM_ROWS, 8) X(EL_I8, 1, 2, 16, CM_ROWS, 8) X(EL_I8, 1, 1, 8, CM_U8T, 8) X(EL_I8, 1, 3, 16, CM_ROWS, 16)
 #define ACCERL_TUNED_BF16(X)                                                                            \
     X(EL_BF16, 2, 8, 16, CM_U8T, 8) X(EL_BF16, 1, 2, 8, CM_U8T, 8) X(EL_BF16, 1, 5, 16, CM_ROWS, 16)   \
     X(EL_BF16, 2, 5, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 8) \

@@ -174,9 +174,66 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const uint32_t* __restrict
     for (int d = 0; d < DW; ++d) out[i * DW + d] = m[d];
 }
 
+// 3x3 windows, pixels of 8 or 16 bytes per unit: one lane per output pixel and unit, nine unconditional
+// vector loads (a tap outside the image re-reads the nearest pixel inside, which lies in the same window,
+// so the maximum is unchanged), signed bytes compared as the high bytes of packed 16-bit lanes.
+typedef short v2s __attribute__((ext_vector_type(2)));
+template <int EL, int DW>
+__global__ __launch_bounds__(256) void maxpool3_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+                                                       int H, int W, int upp, int Ho, int Wo, int s, int pad) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= Ho * Wo * upp) return;
+    const int64_t b = blockIdx.y;
+    const int px = i / upp, u = i - px * upp;
+    const int oy = px / Wo, ox = px - oy * Wo;
+    typedef uint32_t vec __attribute__((ext_vector_type(DW)));
+    const vec* src = (const vec*)in + b * H * W * upp + u;
+    vec tap[9];
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+        const int iy = min(max(oy * s + ky - pad, 0), H - 1);
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) {
+            const int ix = min(max(ox * s + kx - pad, 0), W - 1);
+            tap[ky * 3 + kx] = src[(iy * W + ix) * upp];
+        }
+    }
+    vec r;
+#pragma unroll
+    for (int d = 0; d < DW; ++d) {
+        if constexpr (EL == EL_I8) {
+            v2s e = __builtin_bit_cast(v2s, (tap[0][d] & 0x00ff00ffu) << 8);
+            v2s o = __builtin_bit_cast(v2s, tap[0][d] & 0xff00ff00u);
+#pragma unroll
+            for (int t = 1; t < 9; ++t) {
+                e = __builtin_elementwise_max(e, __builtin_bit_cast(v2s, (tap[t][d] & 0x00ff00ffu) << 8));
+                o = __builtin_elementwise_max(o, __builtin_bit_cast(v2s, tap[t][d] & 0xff00ff00u));
+            }
+            r[d] = ((__builtin_bit_cast(uint32_t, e) >> 8) & 0x00ff00ffu) | (__builtin_bit_cast(uint32_t, o) & 0xff00ff00u);
+        } else {
+            uint32_t m = tap[0][d];
+#pragma unroll
+            for (int t = 1; t < 9; ++t) m = max_bf16x2(m, tap[t][d]);
+            r[d] = m;
+        }
+    }
+    ((vec*)out)[(b * Ho * Wo + px) * upp + u] = r;
+}
+
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,
                           int k, int s, int pad, Elem el, hipStream_t stream) {
     if (B <= 0) return hipSuccess;
+    const int pix_bytes = Cs * (el == EL_I8 ? 1 : 2);
+    if (k == 3 && pad < 3 && pix_bytes % 8 == 0 && B <= 65535) {
+        const int DW = (pix_bytes % 16 == 0) ? 4 : 2;
+        const int upp = pix_bytes / (4 * DW);
+        dim3 grid((unsigned)((Ho * Wo * upp + 255) / 256), (unsigned)B), block(256);
+#define GO(E, D) maxpool3_kernel<E, D><<<grid, block, 0, stream>>>((const uint32_t*)in, (uint32_t*)out, H, W, upp, Ho, Wo, s, pad)
+        if (el == EL_I8) { if (DW == 4) GO(EL_I8, 4); else GO(EL_I8, 2); }
+        else { if (DW == 4) GO(EL_BF16, 4); else GO(EL_BF16, 2); }
+#undef GO
+        return hipGetLastError();
+    }
     const int Cg = Cs / 4;
     const int64_t total = B * Ho * Wo * Cg;
     dim3 grid((unsigned)((total + 255) / 256)), block(256);
