@@ -42,7 +42,7 @@ hipError_t launch_mlp_i8(const MlpParams& p, hipStream_t s);
 hipError_t launch_quant_obs(const float* obs, int64_t B, int D, int Dpad, float inv_s0, int8_t* out, hipStream_t s);
 
 // ---------------------------------------------------------------- convolution (input tiles in LDS, MFMA)
-enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2 };
+enum ConvMode : int { CM_FLAT = 0, CM_ROWS = 1, CM_U8T = 2, CM_ROWSV = 3 };
 struct ConvParams {
     const void* in;          // NHWC elements, or NCHW uint8 observations (mode U8T)
     void* out;               // NHWC elements [B, Ho, Wo, Cs_out]
@@ -79,10 +79,9 @@ struct ConvParams {
     int img_bytes;           // FLAT: contiguous bytes per image
     int units_img;           // 16-byte staging units per image tile
     int row_units;           // ROWS / U8T: units per tile row
-    int vec_ok;              // ROWS: image rows are whole 16-byte units, each staged by one aligned load
     uint32_t magic_npix, magic_wo, magic_units, magic_rowunits;   // ceil(2^32/d), 0 for d = 1
+    float inv_npix, hinv_npix, inv_wo, hinv_wo;   // 1/d and 0.5/d for d = pixels per tile band, output width
     float r;                 // residual ratio (int8 path)
-    int groups;              // grid.y
 };
 // KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.
 // RD: alignment (16 / 8 / 4) of a chunk read in LDS.  PF: staging units per lane the kernel holds.

@@ -1,5 +1,6 @@
 // C-ABI entry points, the host-side plan builder (arch -> fixed list of kernel launches) and the
 // weight re-layout into MFMA fragment order.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -168,7 +169,7 @@ struct Step {
     int64_t acc_elems = 0;      // int32 accumulator elements per state (0 = none)
 };
 
-struct Buf { int64_t per_state; int64_t off; };
+struct Buf { int64_t per_state; int64_t off; int slot; };
 
 }  // namespace
 
@@ -178,6 +179,7 @@ struct accerl_policy {
     int device = 0;
     std::vector<Step> steps;
     std::vector<Buf> bufs;
+    std::vector<int64_t> slots;   // workspace slots (bytes per state); buffers whose lifetimes do not overlap share one
     int64_t ws_per_state = 0;
     char* consts = nullptr;
     char* ws = nullptr;
@@ -210,7 +212,7 @@ struct Builder {
         return o;
     }
     int new_buf(int64_t per_state) {
-        pol->bufs.push_back(Buf{up(per_state, 16), 0});
+        pol->bufs.push_back(Buf{up(per_state, 16), 0, -1});
         return (int)pol->bufs.size() - 1;
     }
     const TensorSpec& tensor(int layer, int sub) const {
@@ -281,9 +283,9 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     int mode, pitch;
     if (src_u8) { mode = CM_U8T; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
     else if (pad == 0 && ((H * row_bytes) % 16) == 0) { mode = CM_FLAT; pitch = row_bytes; }
-    else { mode = CM_ROWS; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
+    else { mode = (row_bytes % 16) == 0 ? CM_ROWSV : CM_ROWS; pitch = (int)up((int64_t)(W + 2 * pad) * pix, 16); }
     const bool whole = mode == CM_FLAT;             // tiles are whole images, staged contiguously
-    const bool rows_vec = (row_bytes % 16) == 0;    // ROWS: image rows are whole 16-byte units (else gathered by dwords)
+    const bool rows_vec = mode == CM_ROWSV;         // image rows are whole 16-byte units (else gathered by dwords)
 
     int RD = [&] { int al = gcd_int(16, gcd_int(sx * pix, pitch)); return al < 4 ? 4 : al; }();
     const int w_lds_max = w_bytes + k_steps * 16 + CONV_LDS_CONST;
@@ -301,13 +303,20 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         if (mode == CM_U8T) return rows_of(th) * (W / 4);
         return rows_of(th) * (rows_vec ? row_bytes / 16 : pitch / 16);
     };
+    // Thin layers (one channel tile, a few MFMA steps) are bound by the vector instructions around the
+    // MFMAs: they get small batches, so that the kernel needs few staging registers and four workgroups
+    // share a compute unit.
+    const bool thin = NT == 1 && k_steps <= 3 && !getenv("ACCERL_NO_THIN");
+    int thin_units = 1024;
+    if (const char* env = getenv("ACCERL_THIN_UNITS")) { const int v = atoi(env); if (v >= 256) thin_units = v; }
+    const int band_units = thin ? thin_units : 4096;
     int TH = Ho;
     if (!whole) {
-        while (TH > 1 && (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + 32 > budget)) --TH;
+        while (TH > 1 && (units_of(TH) > band_units || w_lds_max + tile_of(TH) + 32 > budget)) --TH;
         const int nb = (Ho + TH - 1) / TH;
         TH = (Ho + nb - 1) / nb;
     }
-    if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + 32 > lds_cap)
+    if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + 32 > lds_cap)   // (a whole thin image may exceed its soft cap)
         return fail(ACCERL_EUNSUPPORTED, "layer %d: one input band does not fit the staging limits", layer);
     const int n_bands = (Ho + TH - 1) / TH;
     const int tile_stride = tile_of(TH), units_img = units_of(TH), n_pix = TH * Wo;
@@ -315,7 +324,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     int G = 1;
     if (n_bands == 1) {
         const int slot = 4 * PT * 16;
-        const int unit_cap = 2560;
+        const int unit_cap = thin ? thin_units : 2560;
         // largest batch whose tile-slot use is within 3 % of the best one: more pixels per barrier pair
         double best = -1.0;
         auto util_of = [&](int gg) { return (double)gg * n_pix / ((gg * n_pix + slot - 1) / slot * slot); };
@@ -358,8 +367,11 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     c.img_bytes = H * row_bytes;
     c.units_img = units_img;
     c.row_units = mode == CM_U8T ? W / 4 : rows_vec ? row_bytes / 16 : pitch / 16;
-    c.vec_ok = rows_vec;
     c.magic_npix = magic_of(n_pix); c.magic_wo = magic_of(Wo);
+    if ((int64_t)G * n_pix >= (1 << 20) || (int64_t)Ho * Wo >= (1 << 20) || tile_stride >= (1 << 23) || (int64_t)ss * pitch >= (1 << 23))
+        return fail(ACCERL_EUNSUPPORTED, "layer %d: image too large for the pixel index arithmetic", layer);
+    c.inv_npix = 1.0f / (float)n_pix; c.hinv_npix = 0.5f / (float)n_pix;
+    c.inv_wo = 1.0f / (float)Wo; c.hinv_wo = 0.5f / (float)Wo;
     c.magic_units = magic_of(units_img); c.magic_rowunits = magic_of(c.row_units);
     st.NT = NT; st.KS = KS; st.RD = RD; st.PF = PF;
     st.out_elems = (int64_t)Ho * Wo * Cs_outK;
@@ -792,7 +804,9 @@ int ensure_workspace(accerl_policy* p, int64_t n, hipStream_t stream) {
         p->ws_states = 0;
     }
     int64_t off = 0;
-    for (auto& b : p->bufs) { b.off = off; off += up(b.per_state * n + 256, 256); }
+    std::vector<int64_t> slot_off(p->slots.size());
+    for (size_t i = 0; i < p->slots.size(); ++i) { slot_off[i] = off; off += up(p->slots[i] * n + 256, 256); }
+    for (auto& b : p->bufs) b.off = slot_off[b.slot];
     hipError_t e = hipMalloc((void**)&p->ws, (size_t)off);
     if (e != hipSuccess) { (void)hipGetLastError(); return fail(ACCERL_ENOMEM, "workspace of %lld bytes: %s", (long long)off, hipGetErrorString(e)); }
     HIP_TRY(hipMemset(p->ws, 0, (size_t)off));
@@ -908,17 +922,6 @@ int run(accerl_policy* p, const Call& c) {
                     cp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
                     cp.lut = s.o_lut >= 0 ? (const uint16_t*)(p->consts + s.o_lut) : nullptr;
                     cp.B = n;
-                    {
-                        const int64_t n_batch = (n + cp.G - 1) / cp.G;
-                        int64_t groups = 768 / cp.n_bands;
-                        if (groups < 1) groups = 1;
-                        if (groups > n_batch) groups = n_batch;
-                        if (cp.wave_private) {          // one workgroup of 8 wavefronts per compute unit
-                            groups = (n_batch + CONV_WP_NWAVES - 1) / CONV_WP_NWAVES;
-                            if (groups > 256) groups = 256;
-                        }
-                        cp.groups = (int)groups;
-                    }
                     e = launch_conv(cp, s.el, s.NT, s.KS, s.RD, s.PF, c.stream);
                     break;
                 }
@@ -1027,6 +1030,43 @@ int accerl_blob_sizes(const accerl_arch* arch, int64_t* weights_bytes, int64_t* 
 }
 
 // Host half of policy creation: parse, check, build the plan and the host image of the constants.
+// Workspace slots.  A buffer lives from the step that writes it to the last step that reads it; two
+// buffers share a slot only if one is dead before the step that first writes the other, so no kernel
+// ever reads and writes the same memory.  Buffers are taken in order of first write and placed in the
+// free slot that wastes least (a smaller free slot is grown before a new one is opened).
+static void assign_slots(accerl_policy* pol) {
+    const int nb = (int)pol->bufs.size(), ns = (int)pol->steps.size();
+    std::vector<int> first(nb, ns), last(nb, -1);
+    for (int si = 0; si < ns; ++si) {
+        const Step& st = pol->steps[si];
+        for (int b : {st.in_buf, st.res_buf, st.out_buf}) {
+            if (b < 0) continue;
+            first[b] = std::min(first[b], si);
+            last[b] = std::max(last[b], si);
+        }
+    }
+    pol->slots.clear();
+    std::vector<int> busy_until;
+    std::vector<int> order(nb);
+    for (int i = 0; i < nb; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return first[a] < first[b]; });
+    for (int b : order) {
+        const int64_t need = pol->bufs[b].per_state;
+        int pick = -1;
+        for (int sl = 0; sl < (int)pol->slots.size(); ++sl) {
+            if (busy_until[sl] >= first[b]) continue;
+            if (pick < 0) { pick = sl; continue; }
+            const bool fits = pol->slots[sl] >= need, pfits = pol->slots[pick] >= need;
+            if (fits && (!pfits || pol->slots[sl] < pol->slots[pick])) pick = sl;
+            else if (!fits && !pfits && pol->slots[sl] > pol->slots[pick]) pick = sl;
+        }
+        if (pick < 0) { pol->slots.push_back(0); busy_until.push_back(-1); pick = (int)pol->slots.size() - 1; }
+        pol->slots[pick] = std::max(pol->slots[pick], need);
+        busy_until[pick] = std::max(last[b], first[b]);
+        pol->bufs[b].slot = pick;
+    }
+}
+
 static int create_host(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
                        const float* quant_scales, int64_t n_scales, accerl_policy* pol, std::vector<char>& cst) {
     if (!weights) return fail(ACCERL_EINVAL, "weights is NULL");
@@ -1049,8 +1089,9 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
     rc = build_plan(B);
     if (rc) return rc;
     cst.swap(B.cst);
+    assign_slots(pol);
     pol->ws_per_state = 0;
-    for (const auto& b : pol->bufs) pol->ws_per_state += b.per_state;
+    for (const int64_t sz : pol->slots) pol->ws_per_state += sz;
     // states per pass: about 1 GiB of intermediates, so that every launch still fills the chip
     pol->chunk = 0;
     if (pol->ws_per_state > 0) {
@@ -1106,9 +1147,9 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
             const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles;
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
-                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld vec_ok=%d wp=%d pt=%d\n",
+                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
-                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.vec_ok, c.wave_private, c.wp_pt);
+                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu);

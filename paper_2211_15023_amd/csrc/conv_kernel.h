@@ -47,6 +47,9 @@ __device__ __forceinline__ uint32_t f2bf(float x) {
     return u >> 16;
 }
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; }
+// floor(n / d) for 0 <= n < 2^20 from inv = 1/d and hinv = 0.5/d: the true value of (n + 0.5)/d is at least
+// 0.5/d away from an integer, more than the rounding error of the two float operations.
+__device__ __forceinline__ int qdiv(int n, float inv, float hinv) { return (int)__builtin_fmaf((float)n, inv, hinv); }
 template <int RD>
 __device__ __forceinline__ v4i read_chunk(const char* p) {
     if constexpr (RD == 16) {
@@ -68,8 +71,16 @@ __device__ __forceinline__ void conv_wave_fence() {
 }
 
 // NW: wavefronts per workgroup.  WP: wave-private batches (see above); else the workgroup shares one batch.
+// Workgroups per compute unit the register budget is set for: four when weights, staging registers and
+// accumulators are few (thin layers, which need the extra wavefronts to hide their latencies), else two.
+constexpr int conv_min_blocks(int NT, int KS, int PF, int PT, int NW, int MODE) {
+    if (NW != 4) return 1;
+    const int regs = 4 * KS * NT + 4 * PF + (MODE == CM_FLAT ? 0 : MODE == CM_ROWS ? 4 * PF : 2 * PF) + 8 * PT * NT + 4 * PT + 8 * NT + 40;
+    return regs <= 120 ? 4 : 2;
+}
+
 template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP>
-__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const ConvParams p) {
+__global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE)) void conv_kernel(const ConvParams p) {
     constexpr int CONV_THREADS = NW * 64;
     constexpr int SN = WP ? 64 : CONV_THREADS;      // lanes that stage one batch together
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -142,6 +153,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
     const int row_bytes_img = p.W * pix;
     const int lead = p.pad * pix;
     const int64_t n_batch = (p.B + p.G - 1) / p.G;
+    const int row_step = p.s * p.pitch, col_step = p.sx * pix;   // LDS bytes per output row / column
+    const int band_skip = p.Ho * p.Wo - n_pix;                   // output pixels of an image outside this band
 
     // ---- staging: issue the loads of a batch into registers / write them to LDS.
     // Which bytes a lane stages, and where they land in LDS, is the same for every batch, so the source
@@ -151,10 +164,11 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
     // divergent branches would be serialised by the wait-count insertion.
     v4i pre[PF];
     constexpr int NOFF = (MODE == CM_FLAT) ? 1 : PF;
-    uint32_t soff[NOFF];      // ROWS: offset of the source row; U8T: offset of the unit in plane 0
-    int ooff[NOFF];           // ROWS: byte offset of the unit inside its image row (may lie in the padding)
+    constexpr int NGAT = (MODE == CM_ROWS) ? PF : 1;
+    uint32_t soff[NOFF];      // ROWS: offset of the source row; ROWSV: of the unit; U8T: of the unit in plane 0
     int doff[NOFF];           // LDS byte offset of the unit, -1 = never written (stays padding)
-    uint32_t smask[NOFF];     // ROWS: bit e set = dword e of the unit is real data
+    int ooff[NGAT];           // ROWS: byte offset of the unit inside its image row (may lie in the padding)
+    uint32_t smask[NGAT];     // ROWS: bit e set = dword e of the unit is real data
     if constexpr (MODE != CM_FLAT) {
         const int n_units = p.G * p.units_img;
 #pragma unroll
@@ -167,26 +181,21 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
             const int iy = iy0 + rr;
             const bool rin = iy >= 0 && iy < p.H;
             const int iyc = min(max(iy, 0), p.H - 1);
-            if constexpr (MODE == CM_ROWS) {
+            if constexpr (MODE == CM_ROWSV) {
+                // units are the aligned 16-byte pieces of the image rows; padding is never written
+                soff[i] = (uint32_t)((img * p.H + iyc) * row_bytes_img + cu * 16);
+                doff[i] = rin ? img * p.tile_stride + rr * p.pitch + lead + cu * 16 : -1;
+            } else if constexpr (MODE == CM_ROWS) {
+                // units are the 16-byte pieces of the padded LDS rows, gathered dword by dword
                 soff[i] = (uint32_t)((img * p.H + iyc) * row_bytes_img);
-                if (p.vec_ok) {
-                    // units are the aligned 16-byte pieces of the image rows; padding is never written
-                    smask[i] = 0xfu;
-                    ooff[i] = cu * 16;
-                    doff[i] = rin ? img * p.tile_stride + rr * p.pitch + lead + cu * 16 : -1;
-                } else {
-                    // units are the 16-byte pieces of the padded LDS rows, gathered dword by dword
-                    const int o = cu * 16 - lead;
-                    uint32_t m = 0;
+                const int o = cu * 16 - lead;
+                uint32_t m = 0;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) m |= (rin && o + 4 * e >= 0 && o + 4 * e < row_bytes_img) ? (1u << e) : 0u;
-                    smask[i] = m;
-                    ooff[i] = o;
-                    doff[i] = img * p.tile_stride + rr * p.pitch + cu * 16;
-                }
+                for (int e = 0; e < 4; ++e) m |= (rin && o + 4 * e >= 0 && o + 4 * e < row_bytes_img) ? (1u << e) : 0u;
+                smask[i] = m;
+                ooff[i] = o;
+                doff[i] = img * p.tile_stride + rr * p.pitch + cu * 16;
             } else {
-                smask[i] = 0;
-                ooff[i] = 0;
                 soff[i] = (uint32_t)(img * p.Cin_real * p.H * p.W + iyc * p.W + 4 * cu);
                 doff[i] = rin ? img * p.tile_stride + rr * p.pitch + lead + 4 * cu * pix : -1;
             }
@@ -204,20 +213,23 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
                 const int u = min(stid + i * SN, last);
                 pre[i] = *(const v4i*)(src + (uint32_t)u * 16u);
             }
-        } else if constexpr (MODE == CM_ROWS) {
+        } else if constexpr (MODE == CM_ROWSV) {
             const char* src = (const char*)p.in + b0 * (int64_t)p.H * row_bytes_img;
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
                 const uint32_t so = (stid + i * SN <= last) ? soff[i] : 0u;   // a unit of a missing image reads image 0
-                if (p.vec_ok) {
-                    pre[i] = *(const v4i*)(src + so + (uint32_t)ooff[i]);
-                } else {
-                    v4i v;
+                pre[i] = *(const v4i*)(src + so);
+            }
+        } else if constexpr (MODE == CM_ROWS) {
+            const char* src = (const char*)p.in + b0 * (int64_t)p.H * row_bytes_img;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        v[e] = *(const int*)(src + so + (uint32_t)min(max(ooff[i] + 4 * e, 0), row_bytes_img - 4));
-                    pre[i] = v;
-                }
+            for (int i = 0; i < PF; ++i) {
+                const uint32_t so = (stid + i * SN <= last) ? soff[i] : 0u;
+                v4i v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = *(const int*)(src + so + (uint32_t)min(max(ooff[i] + 4 * e, 0), row_bytes_img - 4));
+                pre[i] = v;
             }
         } else {   // CM_U8T: one dword (4 pixels) from each channel plane
             const uint8_t* src = (const uint8_t*)p.in + b0 * (int64_t)p.Cin_real * p.H * p.W;
@@ -242,12 +254,11 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
             if (u >= total) break;
             v4i v = pre[i];
             if constexpr (MODE != CM_U8T) {
-                if constexpr (MODE == CM_ROWS) {
+                if constexpr (MODE == CM_ROWSV) {
                     if (doff[i] < 0) continue;                // row outside the image: stays padding
-                    if (!p.vec_ok) {
+                } else if constexpr (MODE == CM_ROWS) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = ((smask[i] >> e) & 1u) ? v[e] : 0;
-                    }
+                    for (int e = 0; e < 4; ++e) v[e] = ((smask[i] >> e) & 1u) ? v[e] : 0;
                 }
                 if (p.relu_in) {
 #pragma unroll
@@ -256,7 +267,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
                 }
                 if constexpr (MODE == CM_FLAT) {
                     *(v4i*)(tiles + u * 16) = v;              // tiles of a batch are contiguous like the images
-                } else if ((lead & 15) == 0 || !p.vec_ok) {
+                } else if (MODE == CM_ROWS || (lead & 15) == 0) {
                     *(v4i*)(tiles + doff[i]) = v;
                 } else if ((lead & 7) == 0) {
                     typedef int v2i __attribute__((ext_vector_type(2)));
@@ -322,17 +333,20 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
         const char* res_b = (const char*)p.res + base_el * ESZ;
         int32_t* tap_b = p.tap_acc + base_el;
         for (int t0 = (WP ? 0 : wave * PT); t0 < n_tiles; t0 += (WP ? 1 : NW) * PT) {
-            int pb[PT], pimg[PT], ppix[PT];   // tile-relative pixel offset, tile offset, pixel number
+            int pb[PT], pimg[PT], ppix[PT], prel[PT];   // tile-relative pixel offset, tile offset, pixel number, output pixel
 #pragma unroll
             for (int u = 0; u < PT; ++u) {
                 int pp = (t0 + u) * 16 + j;
                 ppix[u] = pp;
                 if (pp >= total_pix) pp = total_pix - 1;     // clamp to a valid pixel; result not stored
-                const int img = (int)fdiv((uint32_t)pp, p.magic_npix);
-                const int rem = pp - img * n_pix;
-                const int ty = (int)fdiv((uint32_t)rem, p.magic_wo), ox = rem - ty * p.Wo;
-                pb[u] = ty * p.s * p.pitch + ox * p.sx * pix;
-                pimg[u] = img * p.tile_stride;
+                // pixel -> (image, row, column): reciprocal multiplies and 24-bit integer multiplies, which
+                // issue at full rate (32-bit integer multiplies take four times as long)
+                const int img = qdiv(pp, p.inv_npix, p.hinv_npix);
+                const int rem = pp - __mul24(img, n_pix);
+                const int ty = qdiv(rem, p.inv_wo, p.hinv_wo), ox = rem - __mul24(ty, p.Wo);
+                pb[u] = __mul24(ty, row_step) + __mul24(ox, col_step);
+                pimg[u] = __mul24(img, p.tile_stride);
+                prel[u] = ppix[u] + __mul24(img, band_skip);  // relative to the first pixel this workgroup writes for the batch
             }
             v4i acc_i[PT][NT];
             v4f acc_f[PT][NT];
@@ -384,12 +398,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
 #pragma unroll
             for (int u = 0; u < PT; ++u) {
                 if (ppix[u] >= total_pix) continue;
-                // pixel number relative to the first pixel this workgroup writes for the batch
-                const int img = (int)fdiv((uint32_t)ppix[u], p.magic_npix);
-                const int rel = ppix[u] + img * (p.Ho * p.Wo - n_pix);
                 const int c0 = 4 * NT * g;
-                const uint32_t o = (uint32_t)(rel * p.Cs_out + c0);
-                const uint32_t o_res = (uint32_t)(rel * p.Cs_out);
+                const uint32_t o_res = (uint32_t)__mul24(prel[u], p.Cs_out);
+                const uint32_t o = o_res + (uint32_t)c0;
                 if constexpr (EL == EL_I8) {
                     uint32_t pk[NT];
                     uint32_t xr[NT];
@@ -478,6 +489,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void conv_kernel(const Co
 }
 
 
+// Launch: the grid is (bands, groups).  Every workgroup stays resident (groups is at most what the chip
+// holds at this kernel's occupancy) and walks the image batches in strides of `groups`; groups is then
+// lowered to the smallest count that needs the same number of rounds, so that the rounds are even.
+int conv_num_cus();
 template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP>
 hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
     auto kfn = conv_kernel<EL, NT, KS, RD, MODE, PF, PT, NW, WP>;
@@ -487,6 +502,21 @@ hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
         if (e != hipSuccess) return e;
         set_lds = lds;
     }
+    static size_t occ_lds = ~(size_t)0;
+    static int occ = 1;
+    if (occ_lds != lds) {
+        int o = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)kfn, NW * 64, lds);
+        if (e != hipSuccess) return e;
+        occ = o < 1 ? 1 : o;
+        occ_lds = lds;
+    }
+    const int64_t n_batch = (p.B + p.G - 1) / p.G;
+    const int64_t items = WP ? (n_batch + NW - 1) / NW : n_batch;     // batches a workgroup takes per round
+    int64_t cap = (int64_t)occ * conv_num_cus() / (int64_t)grid.x;
+    if (cap < 1) cap = 1;
+    const int64_t rounds = (items + cap - 1) / cap;
+    grid.y = (unsigned)((items + rounds - 1) / rounds);
     kfn<<<grid, dim3(NW * 64), lds, s>>>(p);
     return hipGetLastError();
 }
@@ -500,11 +530,13 @@ constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
 #define ACCERL_TUNED_I8(X)                                                                              \
     X(EL_I8, 2, 4, 16, CM_U8T, 8) X(EL_I8, 1, 4, 16, CM_U8T, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
     X(EL_I8, 4, 0, 16, CM_FLAT, 10) X(EL_I8, 2, 4, 16, CM_FLAT, 8) X(EL_I8, 1, 2, 16, CM_FLAT, 8)      \
-    X(EL_I8, 1, 1, 8, CM_FLAT, 8) X(EL_I8, 1, 1, 4, CM_U8T, 8) X(EL_I8, 1, 2, 8, CM_ROWS, 8)           \
-    X(EL_I8, 1, 3, 16, CM_ROWS, 8) X(EL_I8, 1, 2, 16, CM_ROWS, 8) X(EL_I8, 1, 1, 8, CM_U8T, 8) X(EL_I8, 1, 3, 16, CM_ROWS, 16)
+    X(EL_I8, 1, 1, 8, CM_FLAT, 8) X(EL_I8, 1, 1, 4, CM_U8T, 8) X(EL_I8, 1, 1, 8, CM_U8T, 8)            \
+    X(EL_I8, 1, 1, 8, CM_U8T, 4) X(EL_I8, 1, 2, 8, CM_ROWSV, 8) X(EL_I8, 1, 2, 8, CM_ROWSV, 4)         \
+    X(EL_I8, 1, 2, 16, CM_ROWSV, 8) X(EL_I8, 1, 2, 16, CM_ROWSV, 4) X(EL_I8, 1, 2, 16, CM_ROWSV, 2)    \
+    X(EL_I8, 1, 3, 16, CM_ROWSV, 8) X(EL_I8, 1, 3, 16, CM_ROWSV, 4)
 #define ACCERL_TUNED_BF16(X)                                                                            \
-    X(EL_BF16, 2, 8, 16, CM_U8T, 8) X(EL_BF16, 1, 2, 8, CM_U8T, 8) X(EL_BF16, 1, 5, 16, CM_ROWS, 16)   \
-    X(EL_BF16, 2, 5, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 16) X(EL_BF16, 2, 9, 16, CM_ROWS, 8) \
+    X(EL_BF16, 2, 8, 16, CM_U8T, 8) X(EL_BF16, 1, 2, 8, CM_U8T, 8) X(EL_BF16, 1, 5, 16, CM_ROWSV, 16)  \
+    X(EL_BF16, 2, 5, 16, CM_ROWSV, 16) X(EL_BF16, 2, 9, 16, CM_ROWSV, 16) X(EL_BF16, 2, 9, 16, CM_ROWSV, 8) \
     X(EL_BF16, 4, 0, 16, CM_FLAT, 8)
 
 // Wave-private variants (8 wavefronts, weights in LDS, contiguous staging): (element, NT, RD, PF, PT)
@@ -520,6 +552,7 @@ hipError_t conv_go_generic(const ConvParams& p, int rd, dim3 grid, size_t lds, h
     switch (p.mode) {
         case CM_FLAT: return a16 ? conv_go<EL, NT, 0, 16, CM_FLAT, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_FLAT, 16, PT, 4, false>(p, grid, lds, s);
         case CM_ROWS: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWS, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWS, 16, PT, 4, false>(p, grid, lds, s);
+        case CM_ROWSV: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWSV, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWSV, 16, PT, 4, false>(p, grid, lds, s);
         case CM_U8T: return a16 ? conv_go<EL, NT, 0, 16, CM_U8T, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_U8T, 16, PT, 4, false>(p, grid, lds, s);
         default: return hipErrorInvalidValue;
     }

@@ -24,6 +24,16 @@ bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, i
     return true;
 }
 
+int conv_num_cus() {
+    static int n = 0;
+    if (n <= 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+        n = v;
+    }
+    return n;
+}
+
 int conv_pixel_tiles(int NT) { return conv_pt(NT); }
 
 // Wave-private variant for a contiguous-staging int8 layer: true if one exists for (NT, RD, PT) and a
@@ -39,8 +49,7 @@ bool conv_wp_available(Elem el, int NT, int RD, int PT, int units) {
 hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
     const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16 + CONV_LDS_CONST) + (size_t)p.lds_tiles;
-    if (p.groups < 1) return hipErrorInvalidValue;
-    dim3 grid((unsigned)p.n_bands, (unsigned)p.groups);
+    dim3 grid((unsigned)p.n_bands, 1);
     if (p.wave_private) {
         if (KS != 0 || p.mode != CM_FLAT || p.n_bands != 1 || p.G * p.units_img > 64 * CONV_WP_PF) return hipErrorInvalidValue;
         return conv_launch_wp_i8(p, NT, RD, p.wp_pt, grid, lds, s);

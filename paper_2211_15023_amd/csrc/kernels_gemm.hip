@@ -165,7 +165,8 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         for (int t = 0; t < GM_NT; ++t) {
             if (t >= nts) continue;
             const int n0 = (nt0 + t) * 16 + 4 * g;
-            if (n0 >= p.N) continue;
+            // stored activations: rows past N up to the row pitch are written too (zero weights and bias give zeros)
+            if (n0 >= ((EPI == EPI_REQUANT || EPI == EPI_BF16) ? p.Np : p.N)) continue;
             if constexpr (EPI == EPI_REQUANT) {
                 const v4f ml = *(const v4f*)(p.mult + n0);
                 uint32_t pk = 0;
