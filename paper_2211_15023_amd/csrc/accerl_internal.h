@@ -135,7 +135,7 @@ struct HeadsParams {
     int64_t B;
     int Kp_bytes, k_steps, A, relu_in;
 };
-bool heads_supported(int k_steps, int Kp_bytes);
+bool heads_supported(int k_steps, int Kp_bytes, int A);
 hipError_t launch_heads(const HeadsParams& p, Elem el, hipStream_t s);
 
 // fp32 dense layer (teacher MLP): out = relu?(x W^T + b); heads variant writes logits/value

@@ -782,7 +782,7 @@ int build_plan(Builder& B) {
             for (int n = 0; n < N; ++n) bf[n] = B.bias(t)[n];
             st.o_bias = B.put(bf.data(), bf.size() * 4);
         }
-        if (heads_supported(k_steps, gp.Kp_bytes)) {
+        if (heads_supported(k_steps, gp.Kp_bytes, A)) {
             st.kind = ST_HEADS;                     // one kernel: heads GEMM + sampler
             pol->steps.push_back(st);
         } else {

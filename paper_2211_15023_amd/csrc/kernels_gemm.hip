@@ -13,7 +13,7 @@ constexpr int GM_THREADS = 256;
 constexpr int GM_NT = 4;          // feature tiles (of 16) per workgroup
 constexpr int GM_RT = 1;          // row tiles (of 16 states) per wave
 constexpr int GM_ROWS = 64 * GM_RT;   // states per workgroup
-constexpr int GM_KS = 4;          // MFMA steps per LDS stage (64 bytes of K each)
+constexpr int GM_KS = 4;          // MFMA steps per LDS stage (64 bytes of K each); a multiple of 4
 constexpr int GM_XPITCH = GM_KS * 64 + 16;
 
 __device__ __forceinline__ uint32_t g_relu_i8x4(uint32_t x) {
@@ -34,8 +34,9 @@ __device__ __forceinline__ float g_sigmoid(float x) { return 1.0f / (1.0f + expf
 
 template <int EL, int EPI>
 __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p) {
-    __shared__ __attribute__((aligned(16))) char s_w[GM_NT * GM_KS * 1024];
-    __shared__ __attribute__((aligned(16))) char s_x[GM_ROWS * GM_XPITCH];
+    extern __shared__ __attribute__((aligned(16))) char gm_smem[];
+    char* s_w = gm_smem;                              // [GM_NT][GM_KS][64 lanes][16 B]
+    char* s_x = gm_smem + GM_NT * GM_KS * 1024;       // [GM_ROWS][GM_XPITCH]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int64_t b0 = (int64_t)blockIdx.x * GM_ROWS;
@@ -58,21 +59,22 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
     // Stage s0 of K: weights [GM_NT tiles][GM_KS steps] and states [GM_ROWS][GM_KS*64 bytes].  The loads of
     // the next stage are issued into registers before the MFMA work of the current one.  They are
     // unconditional (clamped addresses, zeroed afterwards) so that nothing serialises them.
-    constexpr int WPRE = GM_NT * GM_KS * 64 / GM_THREADS;       // 4 weight units per lane
-    constexpr int XPRE = GM_ROWS * GM_KS * 4 / GM_THREADS;      // 8 state units per lane
+    constexpr int WPRE = GM_NT * GM_KS * 64 / GM_THREADS;       // weight units per lane
+    constexpr int XPRE = GM_ROWS * GM_KS * 4 / GM_THREADS;      // state units per lane
+    constexpr int UPR = GM_KS * 4;                              // state units per row and stage
     v4i wpre[WPRE], xpre[XPRE];
-    const int w_st = tid >> 6;                                  // step of this lane's weight units
     auto prefetch = [&](int s0) {
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
 #pragma unroll
-        for (int r = 0; r < WPRE; ++r) {                         // unit r: tile r, step w_st
-            const int t = (r < nts) ? r : 0, st = (w_st < ns) ? w_st : 0;
+        for (int r = 0; r < WPRE; ++r) {                         // unit r: tile r % GM_NT, step wave + 4 * (r / GM_NT)
+            const int tr = r % GM_NT, sr = wave + 4 * (r / GM_NT);
+            const int t = (tr < nts) ? tr : 0, st = (sr < ns) ? sr : 0;
             wpre[r] = ((const v4i*)p.wfrag)[((int64_t)(nt0 + t) * p.k_steps + s0 + st) * 64 + lane];
         }
 #pragma unroll
         for (int r = 0; r < XPRE; ++r) {
             const int i = tid + r * GM_THREADS;
-            const int rr = i >> 4, c = i & 15;
+            const int rr = i / UPR, c = i % UPR;
             int64_t b = b0 + rr;
             if (b >= p.B) b = p.B - 1;
             int kb = s0 * 64 + c * 16;
@@ -84,14 +86,15 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
 #pragma unroll
         for (int r = 0; r < WPRE; ++r) {
+            const int tr = r % GM_NT, sr = wave + 4 * (r / GM_NT);
             v4i v = wpre[r];
-            if (!(r < nts && w_st < ns)) v = (v4i){0, 0, 0, 0};
-            ((v4i*)s_w)[tid + r * GM_THREADS] = v;
+            if (!(tr < nts && sr < ns)) v = (v4i){0, 0, 0, 0};
+            ((v4i*)s_w)[(tr * GM_KS + sr) * 64 + lane] = v;
         }
 #pragma unroll
         for (int r = 0; r < XPRE; ++r) {
             const int i = tid + r * GM_THREADS;
-            const int rr = i >> 4, c = i & 15;
+            const int rr = i / UPR, c = i % UPR;
             const int kb = s0 * 64 + c * 16;
             v4i v = xpre[r];
             // a unit that starts inside the row but runs past it re-read the row's last 16 bytes: rebuild
@@ -229,17 +232,29 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
     }
 }
 
+template <int EL, int EPI>
+static hipError_t gemm_go(const GemmParams& p, dim3 grid, hipStream_t s) {
+    constexpr size_t lds = GM_NT * GM_KS * 1024 + GM_ROWS * GM_XPITCH;
+    auto kfn = gemm_kernel<EL, EPI>;
+    static bool set = false;   // per instantiation: the stage buffers exceed the default dynamic LDS limit
+    if (!set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        set = true;
+    }
+    kfn<<<grid, dim3(GM_THREADS), lds, s>>>(p);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
     dim3 grid((unsigned)((p.B + GM_ROWS - 1) / GM_ROWS), (unsigned)((p.n_tiles + GM_NT - 1) / GM_NT));
-    dim3 block(GM_THREADS);
-    if (el == EL_I8 && epi == EPI_REQUANT) gemm_kernel<EL_I8, EPI_REQUANT><<<grid, block, 0, s>>>(p);
-    else if (el == EL_I8 && epi == EPI_HEADS_I8) gemm_kernel<EL_I8, EPI_HEADS_I8><<<grid, block, 0, s>>>(p);
-    else if (el == EL_BF16 && epi == EPI_BF16) gemm_kernel<EL_BF16, EPI_BF16><<<grid, block, 0, s>>>(p);
-    else if (el == EL_BF16 && epi == EPI_HEADS_F32ACC) gemm_kernel<EL_BF16, EPI_HEADS_F32ACC><<<grid, block, 0, s>>>(p);
-    else if (el == EL_BF16 && epi == EPI_LSTM) gemm_kernel<EL_BF16, EPI_LSTM><<<grid, block, 0, s>>>(p);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (el == EL_I8 && epi == EPI_REQUANT) return gemm_go<EL_I8, EPI_REQUANT>(p, grid, s);
+    if (el == EL_I8 && epi == EPI_HEADS_I8) return gemm_go<EL_I8, EPI_HEADS_I8>(p, grid, s);
+    if (el == EL_BF16 && epi == EPI_BF16) return gemm_go<EL_BF16, EPI_BF16>(p, grid, s);
+    if (el == EL_BF16 && epi == EPI_HEADS_F32ACC) return gemm_go<EL_BF16, EPI_HEADS_F32ACC>(p, grid, s);
+    if (el == EL_BF16 && epi == EPI_LSTM) return gemm_go<EL_BF16, EPI_LSTM>(p, grid, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace accerl

@@ -1,12 +1,11 @@
 // Policy heads fused with the sampler: logits and value of 16 states per wavefront on the matrix
-// cores (A = head weights staged once per workgroup in LDS, B = the states' feature rows, all of a
-// state's K chunks loaded up front), then log-softmax normaliser and inverse-CDF sampling per state.
+// cores (A = head weights, B = the states' feature rows, both loaded up front into registers), then log-softmax normaliser and inverse-CDF sampling per state.
 #include "accerl_internal.h"
 
 namespace accerl {
 
 constexpr int HD_WAVES = 1;          // one wavefront per workgroup: no workgroup barrier, 16 states each
-constexpr int HD_KMAX = 16;          // MFMA steps of K held in registers per lane
+constexpr int HD_KMAX = 16;          // most MFMA steps of K a kernel variant holds in registers per lane
 constexpr int HD_PITCH = 65;         // floats per state in the logits staging area
 
 __device__ __forceinline__ uint32_t h_relu_i8x4(uint32_t x) {
@@ -18,11 +17,10 @@ __device__ __forceinline__ uint32_t h_relu_bf16x2(uint32_t x) {
     return x & ~(neg * 0xffffu);
 }
 
-template <int EL, int NT>
+template <int EL, int NT, int KM>
 __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* s_w = smem;                                               // [NT][k_steps][64 lanes][16 B]
-    float* s_l = (float*)(smem + NT * p.k_steps * 1024);            // [waves][2][16][HD_PITCH]: logits, then exp terms
+    float* s_l = (float*)smem;                                      // [waves][2][16][HD_PITCH]: logits, then exp terms
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int64_t row0 = ((int64_t)blockIdx.x * HD_WAVES + wave) * 16;
@@ -31,17 +29,22 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
     if (!live) row = p.B - 1;
 
     // this lane's K chunks of its state: unconditional loads, the tail chunk rebuilt below
-    v4i xb[HD_KMAX];
+    v4i xb[KM];
     const char* xrow = (const char*)p.x + row * p.Kp_bytes;
 #pragma unroll
-    for (int st = 0; st < HD_KMAX; ++st) {
+    for (int st = 0; st < KM; ++st) {
         int kb = st * 64 + g * 16;
         if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
         xb[st] = *(const v4i*)(xrow + kb);
     }
-    for (int i = tid; i < NT * p.k_steps * 64; i += HD_WAVES * 64) ((v4i*)s_w)[i] = ((const v4i*)p.wfrag)[i];
-    __syncthreads();
 
+    // weight fragments straight into registers (every wavefront needs each of them exactly once)
+    v4i wa[NT][KM];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int st = 0; st < KM; ++st)
+            wa[t][st] = ((const v4i*)p.wfrag)[(t * p.k_steps + min(st, p.k_steps - 1)) * 64 + lane];
     v4i acc_i[NT];
     v4f acc_f[NT];
 #pragma unroll
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
         else acc_f[t] = *(const v4f*)((const float*)p.bias + 16 * t + 4 * g);
     }
 #pragma unroll
-    for (int st = 0; st < HD_KMAX; ++st) {
+    for (int st = 0; st < KM; ++st) {
         if (st < p.k_steps) {
             const int kb = st * 64 + g * 16;
             v4i v = xb[st];
@@ -70,7 +73,7 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const v4i a = *(const v4i*)(s_w + ((t * p.k_steps + st) * 64 + lane) * 16);
+                const v4i a = wa[t][st];
                 if constexpr (EL == EL_I8) acc_i[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, v, acc_i[t], 0, 0, 0);
                 else acc_f[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, v), acc_f[t], 0, 0, 0);
             }
@@ -137,34 +140,30 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
 
 template <int EL>
 static hipError_t heads_nt(const HeadsParams& p, int nt, dim3 grid, size_t lds, hipStream_t s) {
-#define GO(N)                                                                                          \
+#define GO(N, K)                                                                                       \
     do {                                                                                               \
-        auto kfn = heads_kernel<EL, N>;                                                                \
-        static size_t set_lds = 0;                                                                     \
-        if (lds > set_lds) {                                                                           \
-            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-            if (e != hipSuccess) return e;                                                             \
-            set_lds = lds;                                                                             \
-        }                                                                                              \
-        kfn<<<grid, dim3(HD_WAVES * 64), lds, s>>>(p);                                                 \
+        heads_kernel<EL, N, K><<<grid, dim3(HD_WAVES * 64), lds, s>>>(p);                              \
         return hipGetLastError();                                                                      \
     } while (0)
-    switch (nt) {
-        case 1: GO(1);
-        case 2: GO(2);
-        case 3: GO(3);
-        default: GO(4);
-    }
+    const int km = p.k_steps <= 4 ? 4 : p.k_steps <= 8 ? 8 : 16;
+    if (km == 4) { switch (nt) { case 1: GO(1, 4); case 2: GO(2, 4); case 3: GO(3, 4); default: GO(4, 4); } }
+    if (km == 8) { switch (nt) { case 1: GO(1, 8); case 2: GO(2, 8); case 3: GO(3, 8); default: GO(4, 8); } }
+    switch (nt) { case 1: GO(1, 16); default: GO(2, 16); }
 #undef GO
 }
 
-bool heads_supported(int k_steps, int Kp_bytes) { return k_steps <= HD_KMAX && Kp_bytes >= 16; }
+// a lane holds its state's K chunks and the weight fragments of nt channel tiles: at most 32 fragments
+bool heads_supported(int k_steps, int Kp_bytes, int A) {
+    const int nt = (A + 1 + 15) / 16;
+    const int km = k_steps <= 4 ? 4 : k_steps <= 8 ? 8 : 16;
+    return k_steps <= HD_KMAX && Kp_bytes >= 16 && nt <= 4 && nt * km <= 32;
+}
 
 hipError_t launch_heads(const HeadsParams& p, Elem el, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
     const int nt = (p.A + 1 + 15) / 16;
-    if (!heads_supported(p.k_steps, p.Kp_bytes) || nt > 4) return hipErrorInvalidValue;
-    const size_t lds = (size_t)nt * p.k_steps * 1024 + (size_t)HD_WAVES * 2 * 16 * HD_PITCH * 4;
+    if (!heads_supported(p.k_steps, p.Kp_bytes, p.A)) return hipErrorInvalidValue;
+    const size_t lds = (size_t)HD_WAVES * 2 * 16 * HD_PITCH * 4;
     dim3 grid((unsigned)((p.B + HD_WAVES * 16 - 1) / (HD_WAVES * 16)));
     return el == EL_I8 ? heads_nt<EL_I8>(p, nt, grid, lds, s) : heads_nt<EL_BF16>(p, nt, grid, lds, s);
 }
