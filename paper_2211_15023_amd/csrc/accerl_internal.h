@@ -80,7 +80,15 @@ struct ConvParams {
     int units_img;           // 16-byte staging units per image tile
     int row_units;           // ROWS / U8T: units per tile row
     uint32_t magic_npix, magic_wo, magic_units, magic_rowunits;   // ceil(2^32/d), 0 for d = 1
-    float inv_npix, hinv_npix, inv_wo, hinv_wo;   // 1/d and 0.5/d for d = pixels per tile band, output width
+    float inv_wo, hinv_wo;   // 1/Wo and 0.5/Wo
+    // fused 3x3 stride-2 pad-1 max-pool of the layer's output (pool = 0: plain store to out)
+    int pool;
+    void* pool_out;          // pooled image [B, PH, PW, pool_unit << pool_ush bytes]
+    int PH, PW, TPH;         // pooled size, pooled rows per band (TH then is the most conv rows a band needs)
+    int pool_W;              // conv output pixels per row as stored (before any pixel packing)
+    int pool_unit, pool_ush; // bytes per pooling unit (8 or 16), log2 of units per stored pixel
+    int lds_otile;           // LDS bytes for the conv rows of a batch
+    float inv_prow, hinv_prow;   // 1/d and 0.5/d for d = pooling units per pooled row
     float r;                 // residual ratio (int8 path)
 };
 // KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.

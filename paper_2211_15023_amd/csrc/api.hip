@@ -150,6 +150,8 @@ struct Step {
     StepKind kind;
     int layer = -1, sub = 0;
     int in_buf = -1, out_buf = -1, res_buf = -1;   // -1 = the caller's states (in) / none
+    int pool_buf = -1;          // conv: output of the max-pool fused into it (-1 = none)
+    bool fused = false;         // maxpool: normally done by the conv step before it
     ConvParams cp{};
     Elem el = EL_I8;
     int NT = 1, KS = 0, RD = 16, PF = 16;
@@ -169,7 +171,7 @@ struct Step {
     int64_t acc_elems = 0;      // int32 accumulator elements per state (0 = none)
 };
 
-struct Buf { int64_t per_state; int64_t off; int slot; };
+struct Buf { int64_t per_state; int64_t off; int slot[2]; };   // slot in the normal / the debug layout
 
 }  // namespace
 
@@ -179,7 +181,10 @@ struct accerl_policy {
     int device = 0;
     std::vector<Step> steps;
     std::vector<Buf> bufs;
-    std::vector<int64_t> slots;   // workspace slots (bytes per state); buffers whose lifetimes do not overlap share one
+    // workspace slots (bytes per state); buffers whose lifetimes do not overlap share one.  Layout 0 serves
+    // forward calls; layout 1 serves debug calls, which may run a conv and its max-pool as separate steps.
+    std::vector<int64_t> slots[2];
+    int ws_layout = 0;
     int64_t ws_per_state = 0;
     char* consts = nullptr;
     char* ws = nullptr;
@@ -212,7 +217,7 @@ struct Builder {
         return o;
     }
     int new_buf(int64_t per_state) {
-        pol->bufs.push_back(Buf{up(per_state, 16), 0, -1});
+        pol->bufs.push_back(Buf{up(per_state, 16), 0, {-1, -1}});
         return (int)pol->bufs.size() - 1;
     }
     const TensorSpec& tensor(int layer, int sub) const {
@@ -238,7 +243,7 @@ int gcd_int(int a, int b) { while (b) { const int t = a % b; a = b; b = t; } ret
 // One convolution (a conv layer or half of a resblock) -> a conv step.
 int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool src_u8,
               int Cin, int H, int W, int Cout, int k, int s, int pad, bool relu, bool relu_in,
-              int in_buf, int out_buf, int res_buf, float s_in, float s_out, float s_res) {
+              int in_buf, int out_buf, int res_buf, float s_in, float s_out, float s_res, int pool_buf = -1) {
     Step st;
     st.kind = ST_CONV;
     st.layer = layer;
@@ -248,6 +253,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     st.res_buf = res_buf;
     st.el = el;
     const int esz = el == EL_I8 ? 1 : 2;
+    bool pool = pool_buf >= 0;                       // fuse the 3x3 stride-2 pad-1 max-pool that follows
     const int Cs_out = (int)up(Cout, 4);
     if (src_u8 && Cin > 4) return fail(ACCERL_EUNSUPPORTED, "uint8 observations with more than 4 channels");
     if (src_u8 && (W & 3)) return fail(ACCERL_EUNSUPPORTED, "uint8 observation width must be a multiple of 4");
@@ -310,15 +316,38 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     int thin_units = 1024;
     if (const char* env = getenv("ACCERL_THIN_UNITS")) { const int v = atoi(env); if (v >= 256) thin_units = v; }
     const int band_units = thin ? thin_units : 4096;
-    int TH = Ho;
-    if (!whole) {
+    if (thin) {   // LDS per workgroup small enough for several workgroups per compute unit
+        int thin_lds = 32 * 1024;
+        if (const char* env = getenv("ACCERL_THIN_LDS")) { const int v = atoi(env); if (v >= 8192) thin_lds = v; }
+        if (budget > thin_lds) budget = thin_lds;
+    }
+    // fused pooling: the requantized conv rows of a band wait in LDS for the pooling pass
+    const int pool_pix = Cs_out * esz;               // bytes per stored output pixel
+    const int pool_unit = (pool_pix % 16) == 0 ? 16 : 8;
+    int pool_ush = 0;
+    while ((pool_unit << pool_ush) < pool_pix) ++pool_ush;
+    if (pool && ((pool_pix % 8) != 0 || (pool_unit << pool_ush) != pool_pix || res_buf >= 0)) pool = false;
+    const int PH = pool ? out_hw(Ho, 3, 2, 1) : 0, PW = pool ? out_hw(Wo_img, 3, 2, 1) : 0;
+    auto conv_rows = [&](int tph) { return 2 * tph + 1 < Ho ? 2 * tph + 1 : Ho; };
+    auto otile_of = [&](int th) { return pool ? th * Wo_img * pool_pix : 0; };
+    int TH = Ho, TPH = PH;
+    if (pool) {
+        if (!whole)
+            while (TPH > 1 && (units_of(conv_rows(TPH)) > band_units ||
+                               w_lds_max + tile_of(conv_rows(TPH)) + otile_of(conv_rows(TPH)) + 32 > budget)) --TPH;
+        const int nb = (PH + TPH - 1) / TPH;
+        TPH = (PH + nb - 1) / nb;
+        TH = conv_rows(TPH);
+        if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + otile_of(TH) + 32 > lds_cap) { pool = false; TH = Ho; TPH = 0; }
+    }
+    if (!pool && !whole) {
         while (TH > 1 && (units_of(TH) > band_units || w_lds_max + tile_of(TH) + 32 > budget)) --TH;
         const int nb = (Ho + TH - 1) / TH;
         TH = (Ho + nb - 1) / nb;
     }
-    if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + 32 > lds_cap)   // (a whole thin image may exceed its soft cap)
+    if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + otile_of(TH) + 32 > lds_cap)   // (a whole thin image may exceed its soft cap)
         return fail(ACCERL_EUNSUPPORTED, "layer %d: one input band does not fit the staging limits", layer);
-    const int n_bands = (Ho + TH - 1) / TH;
+    const int n_bands = pool ? (PH + TPH - 1) / TPH : (Ho + TH - 1) / TH;
     const int tile_stride = tile_of(TH), units_img = units_of(TH), n_pix = TH * Wo;
     // images per batch: best use of the pixel-tile slots (4 waves x PT tiles of 16) a workgroup fills per round
     int G = 1;
@@ -330,7 +359,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         auto util_of = [&](int gg) { return (double)gg * n_pix / ((gg * n_pix + slot - 1) / slot * slot); };
         int gmax = 1;
         for (int gg = 2; gg <= 64; ++gg) {
-            if (gg * units_img > unit_cap || w_lds_max + gg * tile_stride + 32 > budget) break;
+            if (gg * units_img > unit_cap || w_lds_max + gg * (tile_stride + otile_of(TH)) + 32 > budget) break;
             gmax = gg;
         }
         for (int gg = 1; gg <= gmax; ++gg) best = util_of(gg) > best ? util_of(gg) : best;
@@ -338,7 +367,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     }
     // wave-private kernel for plain-copy tiles with LDS weights: 8 wavefronts, each with its own images
     int wp_G = 0, wp_PT = 0, wp_wave_tiles = 0;
-    if (el == EL_I8 && mode == CM_FLAT && NT == 4 && n_bands == 1 && !getenv("ACCERL_NO_WAVE_PRIVATE")) {
+    if (el == EL_I8 && mode == CM_FLAT && NT == 4 && n_bands == 1 && !pool && !getenv("ACCERL_NO_WAVE_PRIVATE")) {
         double best = -1.0;
         for (int gg = 1; gg <= 8; ++gg) {
             const int wt = (int)up((int64_t)gg * tile_stride + 32, 16);
@@ -370,7 +399,10 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     c.magic_npix = magic_of(n_pix); c.magic_wo = magic_of(Wo);
     if ((int64_t)G * n_pix >= (1 << 20) || (int64_t)Ho * Wo >= (1 << 20) || tile_stride >= (1 << 23) || (int64_t)ss * pitch >= (1 << 23))
         return fail(ACCERL_EUNSUPPORTED, "layer %d: image too large for the pixel index arithmetic", layer);
-    c.inv_npix = 1.0f / (float)n_pix; c.hinv_npix = 0.5f / (float)n_pix;
+    c.pool = pool ? 1 : 0; c.pool_out = nullptr; c.PH = PH; c.PW = PW; c.TPH = TPH; c.pool_W = Wo_img;
+    c.pool_unit = pool_unit; c.pool_ush = pool_ush; c.lds_otile = G * otile_of(TH);
+    if (pool) { const int rowu = PW << pool_ush; c.inv_prow = 1.0f / (float)rowu; c.hinv_prow = 0.5f / (float)rowu; }
+    st.pool_buf = pool ? pool_buf : -1;
     c.inv_wo = 1.0f / (float)Wo; c.hinv_wo = 0.5f / (float)Wo;
     c.magic_units = magic_of(units_img); c.magic_rowunits = magic_of(c.row_units);
     st.NT = NT; st.KS = KS; st.RD = RD; st.PF = PF;
@@ -583,6 +615,8 @@ int build_plan(Builder& B) {
     cur.shape = image ? Shape{a->obs_c, a->obs_h, a->obs_w, false, 0} : Shape{0, 0, 0, true, a->obs_c};
     cur.el = el;
     if (q) cur.scale = act[ai++];
+    int pool_prealloc = -1;       // output buffer made for the max-pool layer while planning the conv before it
+    bool pool_fused = false;
     for (int i = 0; i < a->n_layers; ++i) {
         const accerl_layer& L = a->layers[i];
         switch (L.kind) {
@@ -590,10 +624,18 @@ int build_plan(Builder& B) {
                 const Shape o = P.shapes[i];
                 const int ob = B.new_buf((int64_t)o.h * o.w * up(o.c, 4) * esz);
                 const float s_out = q ? act[ai++] : 0.f;
+                // a 3x3 stride-2 pad-1 max-pool right after the conv is fused into its epilogue when it fits
+                pool_prealloc = -1;
+                if (i + 1 < a->n_layers && a->layers[i + 1].kind == ACCERL_MAXPOOL && a->layers[i + 1].k == 3 &&
+                    a->layers[i + 1].stride == 2 && a->layers[i + 1].pad == 1 && !getenv("ACCERL_NO_POOL_FUSE")) {
+                    const Shape po = P.shapes[i + 1];
+                    pool_prealloc = B.new_buf((int64_t)po.h * po.w * up(po.c, 4) * esz);
+                }
                 int rc = plan_conv(B, i, 0, B.tensor(i, 0), el, cur.buf < 0, cur.shape.c, cur.shape.h, cur.shape.w,
                                    L.cout, L.k, L.stride, L.pad, L.relu != 0, cur.relu_pending, cur.buf, ob, -1,
-                                   cur.scale, s_out, 0.f);
+                                   cur.scale, s_out, 0.f, pool_prealloc);
                 if (rc) return rc;
+                pool_fused = pol->steps.back().pool_buf >= 0;
                 cur.shape = o; cur.buf = ob; cur.scale = s_out; cur.relu_pending = false;
                 break;
             }
@@ -606,7 +648,9 @@ int build_plan(Builder& B) {
                 st.in_buf = cur.buf;
                 st.H = cur.shape.h; st.W = cur.shape.w; st.Cs = (int)up(cur.shape.c, 4); st.Ho = o.h; st.Wo = o.w;
                 st.k = L.k; st.s = L.stride; st.pad = L.pad;
-                st.out_buf = B.new_buf((int64_t)o.h * o.w * st.Cs * esz);
+                st.out_buf = pool_prealloc >= 0 ? pool_prealloc : B.new_buf((int64_t)o.h * o.w * st.Cs * esz);
+                st.fused = pool_prealloc >= 0 && pool_fused;
+                pool_prealloc = -1; pool_fused = false;
                 st.out_elems = (int64_t)o.h * o.w * st.Cs;
                 pol->steps.push_back(st);
                 cur.shape = o; cur.buf = st.out_buf;
@@ -794,8 +838,9 @@ int build_plan(Builder& B) {
     return ACCERL_OK;
 }
 
-int ensure_workspace(accerl_policy* p, int64_t n, hipStream_t stream) {
-    if (p->bufs.empty() || n <= p->ws_states) return ACCERL_OK;
+int ensure_workspace(accerl_policy* p, int64_t n, int layout, hipStream_t stream) {
+    if (p->bufs.empty() || (n <= p->ws_states && layout == p->ws_layout)) return ACCERL_OK;
+    if (n < p->ws_states) n = p->ws_states;
     if (p->ws) {
         HIP_TRY(hipStreamSynchronize(stream));
         HIP_TRY(hipDeviceSynchronize());
@@ -804,13 +849,15 @@ int ensure_workspace(accerl_policy* p, int64_t n, hipStream_t stream) {
         p->ws_states = 0;
     }
     int64_t off = 0;
-    std::vector<int64_t> slot_off(p->slots.size());
-    for (size_t i = 0; i < p->slots.size(); ++i) { slot_off[i] = off; off += up(p->slots[i] * n + 256, 256); }
-    for (auto& b : p->bufs) b.off = slot_off[b.slot];
+    const std::vector<int64_t>& sl = p->slots[layout];
+    std::vector<int64_t> slot_off(sl.size());
+    for (size_t i = 0; i < sl.size(); ++i) { slot_off[i] = off; off += up(sl[i] * n + 256, 256); }
+    for (auto& b : p->bufs) b.off = b.slot[layout] >= 0 ? slot_off[b.slot[layout]] : -1;
     hipError_t e = hipMalloc((void**)&p->ws, (size_t)off);
     if (e != hipSuccess) { (void)hipGetLastError(); return fail(ACCERL_ENOMEM, "workspace of %lld bytes: %s", (long long)off, hipGetErrorString(e)); }
     HIP_TRY(hipMemset(p->ws, 0, (size_t)off));
     p->ws_states = n;
+    p->ws_layout = layout;
     return ACCERL_OK;
 }
 
@@ -872,7 +919,7 @@ int run(accerl_policy* p, const Call& c) {
     }
     int64_t chunk = p->chunk > 0 ? p->chunk : c.B;
     if (chunk > c.B) chunk = c.B;
-    int rc = ensure_workspace(p, chunk, c.stream);
+    int rc = ensure_workspace(p, chunk, c.debug ? 1 : 0, c.stream);
     if (rc) return rc;
     for (int64_t c0 = 0; c0 < c.B; c0 += chunk) {
         const int64_t n = (c.B - c0 < chunk) ? (c.B - c0) : chunk;
@@ -883,6 +930,7 @@ int run(accerl_policy* p, const Call& c) {
         const float* uni = c.uniforms ? c.uniforms + c0 : nullptr;
         char* tap_out = c.debug ? (char*)c.out + c0 * tap_elems * tap_esz : nullptr;
         auto bufp = [&](int b) -> char* { return b < 0 ? const_cast<char*>(states) : p->ws + p->bufs[b].off; };
+        bool pooled = false;   // the last conv step also did the max-pool that follows it
         for (int si = 0; si <= last_step; ++si) {
             const Step& s = p->steps[si];
             const bool tap_here = c.debug && !fused && si == last_step;
@@ -922,10 +970,14 @@ int run(accerl_policy* p, const Call& c) {
                     cp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
                     cp.lut = s.o_lut >= 0 ? (const uint16_t*)(p->consts + s.o_lut) : nullptr;
                     cp.B = n;
+                    // the fused max-pool is left out when this conv's own output is the tap
+                    if (cp.pool && !tap_here) { cp.pool_out = bufp(s.pool_buf); pooled = true; }
+                    else cp.pool = 0;
                     e = launch_conv(cp, s.el, s.NT, s.KS, s.RD, s.PF, c.stream);
                     break;
                 }
                 case ST_MAXPOOL:
+                    if (s.fused && pooled) { pooled = false; break; }   // done by the conv step before
                     e = launch_maxpool(bufp(s.in_buf), bufp(s.out_buf), n, s.H, s.W, s.Cs, s.Ho, s.Wo, s.k, s.s, s.pad, s.el, c.stream);
                     break;
                 case ST_GEMM: {
@@ -1034,36 +1086,43 @@ int accerl_blob_sizes(const accerl_arch* arch, int64_t* weights_bytes, int64_t* 
 // buffers share a slot only if one is dead before the step that first writes the other, so no kernel
 // ever reads and writes the same memory.  Buffers are taken in order of first write and placed in the
 // free slot that wastes least (a smaller free slot is grown before a new one is opened).
-static void assign_slots(accerl_policy* pol) {
+static void assign_slots(accerl_policy* pol, int layout) {
     const int nb = (int)pol->bufs.size(), ns = (int)pol->steps.size();
     std::vector<int> first(nb, ns), last(nb, -1);
     for (int si = 0; si < ns; ++si) {
         const Step& st = pol->steps[si];
-        for (int b : {st.in_buf, st.res_buf, st.out_buf}) {
+        int touched[4] = {st.in_buf, st.res_buf, st.out_buf, -1};
+        if (layout == 0 && st.kind == ST_CONV && st.pool_buf >= 0) touched[2] = st.pool_buf;   // writes the pooled image only
+        if (layout == 1 && st.kind == ST_CONV) touched[3] = st.pool_buf;                       // may run either way
+        if (layout == 0 && st.kind == ST_MAXPOOL && st.fused) continue;                         // never launched
+        for (int b : touched) {
             if (b < 0) continue;
             first[b] = std::min(first[b], si);
             last[b] = std::max(last[b], si);
         }
     }
-    pol->slots.clear();
+    std::vector<int64_t>& slots = pol->slots[layout];
+    slots.clear();
     std::vector<int> busy_until;
     std::vector<int> order(nb);
     for (int i = 0; i < nb; ++i) order[i] = i;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return first[a] < first[b]; });
     for (int b : order) {
+        pol->bufs[b].slot[layout] = -1;
+        if (last[b] < 0) continue;                   // not used in this layout
         const int64_t need = pol->bufs[b].per_state;
         int pick = -1;
-        for (int sl = 0; sl < (int)pol->slots.size(); ++sl) {
+        for (int sl = 0; sl < (int)slots.size(); ++sl) {
             if (busy_until[sl] >= first[b]) continue;
             if (pick < 0) { pick = sl; continue; }
-            const bool fits = pol->slots[sl] >= need, pfits = pol->slots[pick] >= need;
-            if (fits && (!pfits || pol->slots[sl] < pol->slots[pick])) pick = sl;
-            else if (!fits && !pfits && pol->slots[sl] > pol->slots[pick]) pick = sl;
+            const bool fits = slots[sl] >= need, pfits = slots[pick] >= need;
+            if (fits && (!pfits || slots[sl] < slots[pick])) pick = sl;
+            else if (!fits && !pfits && slots[sl] > slots[pick]) pick = sl;
         }
-        if (pick < 0) { pol->slots.push_back(0); busy_until.push_back(-1); pick = (int)pol->slots.size() - 1; }
-        pol->slots[pick] = std::max(pol->slots[pick], need);
-        busy_until[pick] = std::max(last[b], first[b]);
-        pol->bufs[b].slot = pick;
+        if (pick < 0) { slots.push_back(0); busy_until.push_back(-1); pick = (int)slots.size() - 1; }
+        slots[pick] = std::max(slots[pick], need);
+        busy_until[pick] = last[b];
+        pol->bufs[b].slot[layout] = pick;
     }
 }
 
@@ -1089,9 +1148,10 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
     rc = build_plan(B);
     if (rc) return rc;
     cst.swap(B.cst);
-    assign_slots(pol);
+    assign_slots(pol, 0);
+    assign_slots(pol, 1);
     pol->ws_per_state = 0;
-    for (const int64_t sz : pol->slots) pol->ws_per_state += sz;
+    for (const int64_t sz : pol->slots[0]) pol->ws_per_state += sz;
     // states per pass: about 1 GiB of intermediates, so that every launch still fills the chip
     pol->chunk = 0;
     if (pol->ws_per_state > 0) {
@@ -1144,12 +1204,12 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
         const Step& s = pol.steps[i];
         if (s.kind == ST_CONV) {
             const ConvParams& c = s.cp;
-            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles;
+            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles + (c.pool ? c.lds_otile : 0);
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
-                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d\n",
+                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
-                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt);
+                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt, c.pool, c.TPH);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu);

@@ -64,6 +64,18 @@ __device__ __forceinline__ v4i read_chunk(const char* p) {
     }
 }
 
+// per-byte signed maximum: bytes compared as the high bytes of packed 16-bit lanes
+__device__ __forceinline__ uint32_t pmax_i8x4(uint32_t a, uint32_t b) {
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    const v2s e = __builtin_elementwise_max(__builtin_bit_cast(v2s, (a & 0x00ff00ffu) << 8), __builtin_bit_cast(v2s, (b & 0x00ff00ffu) << 8));
+    const v2s o = __builtin_elementwise_max(__builtin_bit_cast(v2s, a & 0xff00ff00u), __builtin_bit_cast(v2s, b & 0xff00ff00u));
+    return ((__builtin_bit_cast(uint32_t, e) >> 8) & 0x00ff00ffu) | (__builtin_bit_cast(uint32_t, o) & 0xff00ff00u);
+}
+__device__ __forceinline__ uint32_t pmax_bf16x2(uint32_t a, uint32_t b) {
+    const float a0 = bf2f(a & 0xffffu), a1 = bf2f(a >> 16), b0 = bf2f(b & 0xffffu), b1 = bf2f(b >> 16);
+    return ((b0 > a0) ? (b & 0xffffu) : (a & 0xffffu)) | (((b1 > a1) ? (b >> 16) : (a >> 16)) << 16);
+}
+
 __device__ __forceinline__ void conv_wave_fence() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -145,11 +157,19 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     const v4i* bias_l = (const v4i*)(cst_lds + (4 * NT * g) * 4);              // [t] -> bias of channels 4NTg+4t..
     const v4f* mult_l = (const v4f*)(cst_lds + (NT * 16 + 4 * NT * g) * 4);
 
+    // Band of output rows this workgroup computes.  With a fused 3x3 stride-2 pad-1 max-pool a band is
+    // TPH pooled rows, which need the conv rows 2*py0 - 1 .. 2*(py0 + tph) - 1 inside the image.
     const int band = blockIdx.x;
-    const int oy0 = band * p.TH;
-    const int th = (p.Ho - oy0 < p.TH) ? (p.Ho - oy0) : p.TH;
+    const int py0 = band * p.TPH;
+    const int tph = p.pool ? ((p.PH - py0 < p.TPH) ? (p.PH - py0) : p.TPH) : 0;
+    const int oy0 = p.pool ? max(2 * py0 - 1, 0) : band * p.TH;
+    const int th = p.pool ? min(2 * (py0 + tph), p.Ho) - oy0 : ((p.Ho - oy0 < p.TH) ? (p.Ho - oy0) : p.TH);
     const int iy0 = oy0 * p.s - p.pad;
     const int n_pix = th * p.Wo;
+    if (th <= 0) return;                                         // band past the image (a pooling plan launched without pooling)
+    const float inv_npix = 1.0f / (float)n_pix, hinv_npix = 0.5f / (float)n_pix;
+    char* otile = tiles_all + p.lds_tiles;                       // pooling: requantized conv rows of the batch
+    const int otile_px = p.TH * p.Wo;                            // pixels per image in otile
     const int row_bytes_img = p.W * pix;
     const int lead = p.pad * pix;
     const int64_t n_batch = (p.B + p.G - 1) / p.G;
@@ -341,12 +361,13 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                 if (pp >= total_pix) pp = total_pix - 1;     // clamp to a valid pixel; result not stored
                 // pixel -> (image, row, column): reciprocal multiplies and 24-bit integer multiplies, which
                 // issue at full rate (32-bit integer multiplies take four times as long)
-                const int img = qdiv(pp, p.inv_npix, p.hinv_npix);
+                const int img = qdiv(pp, inv_npix, hinv_npix);
                 const int rem = pp - __mul24(img, n_pix);
                 const int ty = qdiv(rem, p.inv_wo, p.hinv_wo), ox = rem - __mul24(ty, p.Wo);
                 pb[u] = __mul24(ty, row_step) + __mul24(ox, col_step);
                 pimg[u] = __mul24(img, p.tile_stride);
-                prel[u] = ppix[u] + __mul24(img, band_skip);  // relative to the first pixel this workgroup writes for the batch
+                // output pixel relative to the first one this workgroup writes for the batch (pooling: inside otile)
+                prel[u] = p.pool ? __mul24(img, otile_px) + rem : ppix[u] + __mul24(img, band_skip);
             }
             v4i acc_i[PT][NT];
             v4f acc_f[PT][NT];
@@ -438,16 +459,22 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                         }
                         pk[t] = w;
                     }
-                    int8_t* dst = (int8_t*)out_b + o;
-                    if (NT == 4 && c0 + 16 <= p.Cs_out) {
-                        *(v4i*)dst = (v4i){(int)pk[0], (int)pk[1 % NT], (int)pk[2 % NT], (int)pk[3 % NT]};
-                    } else if (NT == 2 && c0 + 8 <= p.Cs_out) {
-                        typedef int v2i __attribute__((ext_vector_type(2)));
-                        *(v2i*)dst = (v2i){(int)pk[0], (int)pk[1 % NT]};
-                    } else {
+                    if (p.pool) {
 #pragma unroll
                         for (int t = 0; t < NT; ++t)
-                            if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(dst + 4 * t) = pk[t];
+                            if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(otile + o + 4 * t) = pk[t];
+                    } else {
+                        int8_t* dst = (int8_t*)out_b + o;
+                        if (NT == 4 && c0 + 16 <= p.Cs_out) {
+                            *(v4i*)dst = (v4i){(int)pk[0], (int)pk[1 % NT], (int)pk[2 % NT], (int)pk[3 % NT]};
+                        } else if (NT == 2 && c0 + 8 <= p.Cs_out) {
+                            typedef int v2i __attribute__((ext_vector_type(2)));
+                            *(v2i*)dst = (v2i){(int)pk[0], (int)pk[1 % NT]};
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < NT; ++t)
+                                if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(dst + 4 * t) = pk[t];
+                        }
                     }
                 } else {
                     uint32_t xres[NT][2];
@@ -476,9 +503,63 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.0f);
                         }
-                        uint32_t* d = (uint32_t*)((uint16_t*)out_b + o + 4 * t);
-                        d[0] = f2bf(v[0]) | (f2bf(v[1]) << 16);
-                        d[1] = f2bf(v[2]) | (f2bf(v[3]) << 16);
+                        const uint32_t w0 = f2bf(v[0]) | (f2bf(v[1]) << 16), w1 = f2bf(v[2]) | (f2bf(v[3]) << 16);
+                        if (p.pool) {
+                            uint32_t* d = (uint32_t*)(otile + 2 * (o + 4 * t));
+                            d[0] = w0; d[1] = w1;
+                        } else {
+                            uint32_t* d = (uint32_t*)((uint16_t*)out_b + o + 4 * t);
+                            d[0] = w0; d[1] = w1;
+                        }
+                    }
+                }
+            }
+        }
+        if constexpr (!WP) {
+            if (p.pool) {
+                // max-pool the band's conv rows from LDS: one lane per pooled pixel and unit of 8 or 16 bytes.
+                // A tap outside the image re-reads the nearest pixel inside, which lies in the same window.
+                __syncthreads();
+                const int ush = p.pool_ush, U = p.pool_unit;                  // units per real pixel = 1 << ush
+                const int rowu = p.PW << ush;                                 // units per pooled row
+                const int imgu = tph * rowu;
+                const float inv_imgu = 1.0f / (float)imgu, hinv_imgu = 0.5f / (float)imgu;
+                const int total_u = gc * imgu;
+                const int Wc = p.pool_W;                                      // real (unpacked) conv pixels per row
+                const int64_t out_img = (int64_t)p.PH * rowu * U;             // pooled bytes per image
+                for (int idx = tid; idx < total_u; idx += CONV_THREADS) {
+                    const int img = qdiv(idx, inv_imgu, hinv_imgu);
+                    const int r = idx - __mul24(img, imgu);
+                    const int py = qdiv(r, p.inv_prow, p.hinv_prow);
+                    const int r2 = r - __mul24(py, rowu);
+                    const int px = r2 >> ush, uu = r2 - (px << ush);
+                    const char* src = otile + __mul24(img, otile_px) * (p.Cs_out * ESZ) + uu * U;
+                    int ro[3], co[3];
+#pragma unroll
+                    for (int kk = 0; kk < 3; ++kk) {
+                        ro[kk] = __mul24(min(max(2 * (py0 + py) - 1 + kk, 0), p.Ho - 1) - oy0, Wc);
+                        co[kk] = min(max(2 * px - 1 + kk, 0), Wc - 1);
+                    }
+                    char* dst = (char*)p.pool_out + (b0 + img) * out_img + ((int64_t)__mul24(py0 + py, rowu) + r2) * U;
+                    if (U == 16) {
+                        v4i m = *(const v4i*)(src + ((ro[0] + co[0]) << ush) * 16);
+#pragma unroll
+                        for (int t = 1; t < 9; ++t) {
+                            const v4i v = *(const v4i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 16);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) m[e] = (int)((EL == EL_I8) ? pmax_i8x4((uint32_t)m[e], (uint32_t)v[e]) : pmax_bf16x2((uint32_t)m[e], (uint32_t)v[e]));
+                        }
+                        *(v4i*)dst = m;
+                    } else {
+                        typedef int v2i __attribute__((ext_vector_type(2)));
+                        v2i m = *(const v2i*)(src + ((ro[0] + co[0]) << ush) * 8);
+#pragma unroll
+                        for (int t = 1; t < 9; ++t) {
+                            const v2i v = *(const v2i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 8);
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) m[e] = (int)((EL == EL_I8) ? pmax_i8x4((uint32_t)m[e], (uint32_t)v[e]) : pmax_bf16x2((uint32_t)m[e], (uint32_t)v[e]));
+                        }
+                        *(v2i*)dst = m;
                     }
                 }
             }
