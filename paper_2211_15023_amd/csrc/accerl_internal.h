@@ -94,7 +94,7 @@ struct ConvParams {
 // KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.
 // RD: alignment (16 / 8 / 4) of a chunk read in LDS.  PF: staging units per lane the kernel holds.
 hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s);
-bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, int* KS, int* PF);
+bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, bool extras, int* KS, int* PF);
 int conv_pixel_tiles(int NT);
 constexpr int CONV_LDS_CONST = 512;   // LDS bytes for bias and multipliers in the LDS-weight kernels
 bool conv_wp_available(Elem el, int NT, int RD, int PT, int units);

@@ -367,7 +367,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     }
     // wave-private kernel for plain-copy tiles with LDS weights: 8 wavefronts, each with its own images
     int wp_G = 0, wp_PT = 0, wp_wave_tiles = 0;
-    if (el == EL_I8 && mode == CM_FLAT && NT == 4 && n_bands == 1 && !pool && !getenv("ACCERL_NO_WAVE_PRIVATE")) {
+    if (el == EL_I8 && mode == CM_FLAT && NT == 4 && n_bands == 1 && !pool && res_buf < 0 && !getenv("ACCERL_NO_WAVE_PRIVATE")) {
         double best = -1.0;
         for (int gg = 1; gg <= 8; ++gg) {
             const int wt = (int)up((int64_t)gg * tile_stride + 32, 16);
@@ -382,7 +382,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     }
     int KS = 0, PF = 16;
     if (wp_G) { G = wp_G; }
-    else if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, &KS, &PF))
+    else if (!conv_pick_variant(el, NT, k_steps, RD, mode, (G * units_img + 255) / 256, res_buf >= 0 || pool, &KS, &PF))
         return fail(ACCERL_EUNSUPPORTED, "layer %d: no convolution kernel covers this shape", layer);
     if (!KS && RD == 8) RD = 4;                     // the generic LDS-weight kernels read chunks at 16 or 4 bytes
     c.H = H; c.W = W; c.Cin_real = Cin; c.Cs_in = Cs_in; c.Ho = Ho; c.Wo = Wo; c.Cs_out = Cs_outK;

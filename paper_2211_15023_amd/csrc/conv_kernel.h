@@ -76,6 +76,21 @@ __device__ __forceinline__ uint32_t pmax_bf16x2(uint32_t a, uint32_t b) {
     return ((b0 > a0) ? (b & 0xffffu) : (a & 0xffffu)) | (((b1 > a1) ? (b >> 16) : (a >> 16)) << 16);
 }
 
+// clamp(rint(y), -127, 127) as the bits of y + 1.5 * 2^23: the addition rounds y to the nearest integer
+// (ties to even), which then sits in the low mantissa bits; float bit patterns order like the values, so
+// the clamp is an integer median and also catches every |y| too large for the trick.  The caller keeps
+// only the low byte.
+__device__ __forceinline__ int rne_clamp127(float y) {
+    const int b = (int)__float_as_uint(y + 12582912.0f);
+    return min(max(b, 0x4B400000 - 127), 0x4B400000 + 127);
+}
+// bytes 0 of q[0..3] -> one dword
+__device__ __forceinline__ uint32_t pack_low_bytes(const int (&q)[4]) {
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)q[1], (uint32_t)q[0], 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)q[3], (uint32_t)q[2], 0x04000c0cu);
+    return lo | hi;
+}
+
 __device__ __forceinline__ void conv_wave_fence() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -91,7 +106,8 @@ constexpr int conv_min_blocks(int NT, int KS, int PF, int PT, int NW, int MODE) 
     return regs <= 120 ? 4 : 2;
 }
 
-template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP>
+// EX: residual join and fused max-pooling compiled in (kernels for layers that need neither do without their registers).
+template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP, bool EX>
 __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE)) void conv_kernel(const ConvParams p) {
     constexpr int CONV_THREADS = NW * 64;
     constexpr int SN = WP ? 64 : CONV_THREADS;      // lanes that stage one batch together
@@ -99,6 +115,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     constexpr int ESZ = (EL == EL_I8) ? 1 : 2;
     constexpr int KSR = KS > 0 ? KS : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool has_res = EX && p.res != nullptr, do_pool = EX && p.pool != 0;
     const int j = lane & 15, g = lane >> 4;
     const int pix = p.Cs_in * ESZ;                          // bytes per stored input pixel
     char* wl = smem;                                        // KS == 0: weight fragments + chunk offsets
@@ -161,9 +178,9 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     // TPH pooled rows, which need the conv rows 2*py0 - 1 .. 2*(py0 + tph) - 1 inside the image.
     const int band = blockIdx.x;
     const int py0 = band * p.TPH;
-    const int tph = p.pool ? ((p.PH - py0 < p.TPH) ? (p.PH - py0) : p.TPH) : 0;
-    const int oy0 = p.pool ? max(2 * py0 - 1, 0) : band * p.TH;
-    const int th = p.pool ? min(2 * (py0 + tph), p.Ho) - oy0 : ((p.Ho - oy0 < p.TH) ? (p.Ho - oy0) : p.TH);
+    const int tph = do_pool ? ((p.PH - py0 < p.TPH) ? (p.PH - py0) : p.TPH) : 0;
+    const int oy0 = do_pool ? max(2 * py0 - 1, 0) : band * p.TH;
+    const int th = do_pool ? min(2 * (py0 + tph), p.Ho) - oy0 : ((p.Ho - oy0 < p.TH) ? (p.Ho - oy0) : p.TH);
     const int iy0 = oy0 * p.s - p.pad;
     const int n_pix = th * p.Wo;
     if (th <= 0) return;                                         // band past the image (a pooling plan launched without pooling)
@@ -367,7 +384,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                 pb[u] = __mul24(ty, row_step) + __mul24(ox, col_step);
                 pimg[u] = __mul24(img, p.tile_stride);
                 // output pixel relative to the first one this workgroup writes for the batch (pooling: inside otile)
-                prel[u] = p.pool ? __mul24(img, otile_px) + rem : ppix[u] + __mul24(img, band_skip);
+                prel[u] = do_pool ? __mul24(img, otile_px) + rem : pp + __mul24(img, band_skip);   // (of the clamped pixel)
             }
             v4i acc_i[PT][NT];
             v4f acc_f[PT][NT];
@@ -379,6 +396,22 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                     if constexpr (EL == EL_I8) acc_i[u][t] = CREG ? bi[CREG ? t : 0] : bias_l[t];
                     else acc_f[u][t] = CREG ? bfl[CREG ? t : 0] : __builtin_bit_cast(v4f, bias_l[t]);
                 }
+            // residual stream of the tile's pixels: requested before the MFMA work so that the epilogue
+            // finds it there (pixels past the end were clamped to a valid one above; lanes past the last
+            // channel re-read a valid group)
+            uint32_t xres[PT][NT][ESZ];
+            if (has_res) {
+#pragma unroll
+                for (int u = 0; u < PT; ++u) {
+                    const int pr = prel[u];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const uint32_t* xp = (const uint32_t*)(res_b + ((uint32_t)__mul24(pr, p.Cs_out) + (uint32_t)min(4 * NT * g + 4 * t, p.Cs_out - 4)) * ESZ);
+#pragma unroll
+                        for (int e = 0; e < ESZ; ++e) xres[u][t][e] = xp[e];
+                    }
+                }
+            }
             auto load_b = [&](v4i (&bq)[PT], int off) {
 #pragma unroll
                 for (int u = 0; u < PT; ++u) bq[u] = read_chunk<RD>(tiles + pimg[u] + pb[u] + off);
@@ -424,42 +457,36 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                 const uint32_t o = o_res + (uint32_t)c0;
                 if constexpr (EL == EL_I8) {
                     uint32_t pk[NT];
-                    uint32_t xr[NT];
                     v4f mq[NT];
 #pragma unroll
                     for (int t = 0; t < NT; ++t) mq[t] = CREG ? ml[CREG ? t : 0] : mult_l[t];
-                    if (p.res) {
-#pragma unroll
-                        for (int t = 0; t < NT; ++t)   // lanes past the last channel re-read a valid group (not stored)
-                            xr[t] = *(const uint32_t*)(res_b + o_res + (uint32_t)min(c0 + 4 * t, p.Cs_out - 4));
-                    }
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         const v4i v = acc_i[u][t];
                         if (p.tap_acc && c0 + 4 * t < p.Cs_out) *(v4i*)(tap_b + o + 4 * t) = v;
                         uint32_t w = 0;
-                        if (p.res) {
+                        if (has_res) {
+                            int q[4];
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                const float tr = (float)(int)(int8_t)(xr[t] >> (8 * r)) * p.r;
-                                const float y = __builtin_amdgcn_fmed3f(rintf(fmaf((float)v[r], mq[t][r], tr)), -127.0f, 127.0f);
-                                w |= ((uint32_t)(int)y & 0xffu) << (8 * r);
+                                const float tr = (float)(int)(int8_t)(xres[u][t][0] >> (8 * r)) * p.r;
+                                q[r] = rne_clamp127(fmaf((float)v[r], mq[t][r], tr));
                             }
+                            w = pack_low_bytes(q);
                         } else if (p.relu) {
                             // clamp(rint(y), 0, 127): the pack instruction rounds to nearest even and saturates at 0
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
                                 w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)v[r] * mq[t][r], 0.0f, 127.0f), r, w);
                         } else {
+                            int q[4];
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                const float y = __builtin_amdgcn_fmed3f(rintf((float)v[r] * mq[t][r]), -127.0f, 127.0f);
-                                w |= ((uint32_t)(int)y & 0xffu) << (8 * r);
-                            }
+                            for (int r = 0; r < 4; ++r) q[r] = rne_clamp127((float)v[r] * mq[t][r]);
+                            w = pack_low_bytes(q);
                         }
                         pk[t] = w;
                     }
-                    if (p.pool) {
+                    if (do_pool) {
 #pragma unroll
                         for (int t = 0; t < NT; ++t)
                             if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(otile + o + 4 * t) = pk[t];
@@ -477,23 +504,14 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                         }
                     }
                 } else {
-                    uint32_t xres[NT][2];
-                    if (p.res) {
-#pragma unroll
-                        for (int t = 0; t < NT; ++t) {   // unconditional: lanes past the last channel re-read a valid group
-                            const uint32_t* xr = (const uint32_t*)((const uint16_t*)res_b + o_res + (uint32_t)min(c0 + 4 * t, p.Cs_out - 4));
-                            xres[t][0] = xr[0];
-                            xres[t][1] = xr[1];
-                        }
-                    }
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         if (c0 + 4 * t >= p.Cs_out) continue;
                         float v[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) v[r] = acc_f[u][t][r];
-                        if (p.res) {
-                            const uint32_t x0 = xres[t][0], x1 = xres[t][1];
+                        if (has_res) {
+                            const uint32_t x0 = xres[u][t][0], x1 = xres[u][t][ESZ - 1];
                             v[0] = bf2f(x0 & 0xffffu) + v[0];
                             v[1] = bf2f(x0 >> 16) + v[1];
                             v[2] = bf2f(x1 & 0xffffu) + v[2];
@@ -504,7 +522,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                             for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.0f);
                         }
                         const uint32_t w0 = f2bf(v[0]) | (f2bf(v[1]) << 16), w1 = f2bf(v[2]) | (f2bf(v[3]) << 16);
-                        if (p.pool) {
+                        if (do_pool) {
                             uint32_t* d = (uint32_t*)(otile + 2 * (o + 4 * t));
                             d[0] = w0; d[1] = w1;
                         } else {
@@ -516,7 +534,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
             }
         }
         if constexpr (!WP) {
-            if (p.pool) {
+            if (do_pool) {
                 // max-pool the band's conv rows from LDS: one lane per pooled pixel and unit of 8 or 16 bytes.
                 // A tap outside the image re-reads the nearest pixel inside, which lies in the same window.
                 __syncthreads();
@@ -574,9 +592,9 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
 // holds at this kernel's occupancy) and walks the image batches in strides of `groups`; groups is then
 // lowered to the smallest count that needs the same number of rounds, so that the rounds are even.
 int conv_num_cus();
-template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP>
+template <int EL, int NT, int KS, int RD, int MODE, int PF, int PT, int NW, bool WP, bool EX>
 hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
-    auto kfn = conv_kernel<EL, NT, KS, RD, MODE, PF, PT, NW, WP>;
+    auto kfn = conv_kernel<EL, NT, KS, RD, MODE, PF, PT, NW, WP, EX>;
     static size_t set_lds = 0;   // per instantiation: raise the dynamic LDS limit when needed
     if (lds > set_lds) {
         hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -608,17 +626,18 @@ constexpr int conv_pt(int NT) { return NT == 4 ? 4 : 2; }
 
 // Tuned shared-batch variants: (element, NT, KS, RD, staging mode, PF).  KS > 0 keeps the weights in
 // registers and unrolls that many MFMA steps; KS = 0 reads them from LDS for any number of steps.
-#define ACCERL_TUNED_I8(X)                                                                              \
-    X(EL_I8, 2, 4, 16, CM_U8T, 8) X(EL_I8, 1, 4, 16, CM_U8T, 8) X(EL_I8, 4, 0, 16, CM_FLAT, 8)         \
-    X(EL_I8, 4, 0, 16, CM_FLAT, 10) X(EL_I8, 2, 4, 16, CM_FLAT, 8) X(EL_I8, 1, 2, 16, CM_FLAT, 8)      \
-    X(EL_I8, 1, 1, 8, CM_FLAT, 8) X(EL_I8, 1, 1, 4, CM_U8T, 8) X(EL_I8, 1, 1, 8, CM_U8T, 8)            \
-    X(EL_I8, 1, 1, 8, CM_U8T, 4) X(EL_I8, 1, 2, 8, CM_ROWSV, 8) X(EL_I8, 1, 2, 8, CM_ROWSV, 4)         \
-    X(EL_I8, 1, 2, 16, CM_ROWSV, 8) X(EL_I8, 1, 2, 16, CM_ROWSV, 4) X(EL_I8, 1, 2, 16, CM_ROWSV, 2)    \
-    X(EL_I8, 1, 3, 16, CM_ROWSV, 8) X(EL_I8, 1, 3, 16, CM_ROWSV, 4)
-#define ACCERL_TUNED_BF16(X)                                                                            \
-    X(EL_BF16, 2, 8, 16, CM_U8T, 8) X(EL_BF16, 1, 2, 8, CM_U8T, 8) X(EL_BF16, 1, 5, 16, CM_ROWSV, 16)  \
-    X(EL_BF16, 2, 5, 16, CM_ROWSV, 16) X(EL_BF16, 2, 9, 16, CM_ROWSV, 16) X(EL_BF16, 2, 9, 16, CM_ROWSV, 8) \
-    X(EL_BF16, 4, 0, 16, CM_FLAT, 8)
+// Last entry: 1 = residual join and fused pooling compiled in.
+#define ACCERL_TUNED_I8(X)                                                                                   \
+    X(EL_I8, 2, 4, 16, CM_U8T, 8, 0) X(EL_I8, 1, 4, 16, CM_U8T, 8, 0) X(EL_I8, 4, 0, 16, CM_FLAT, 8, 0)     \
+    X(EL_I8, 4, 0, 16, CM_FLAT, 10, 0) X(EL_I8, 2, 4, 16, CM_FLAT, 8, 0) X(EL_I8, 1, 2, 16, CM_FLAT, 8, 0)  \
+    X(EL_I8, 1, 1, 8, CM_FLAT, 8, 0) X(EL_I8, 1, 1, 4, CM_U8T, 8, 1) X(EL_I8, 1, 1, 8, CM_U8T, 8, 1)        \
+    X(EL_I8, 1, 1, 8, CM_U8T, 4, 1) X(EL_I8, 1, 2, 8, CM_ROWSV, 8, 1) X(EL_I8, 1, 2, 8, CM_ROWSV, 4, 1)     \
+    X(EL_I8, 1, 2, 16, CM_ROWSV, 8, 1) X(EL_I8, 1, 2, 16, CM_ROWSV, 4, 1) X(EL_I8, 1, 2, 16, CM_ROWSV, 2, 1) \
+    X(EL_I8, 1, 3, 16, CM_ROWSV, 8, 1) X(EL_I8, 1, 3, 16, CM_ROWSV, 4, 1)
+#define ACCERL_TUNED_BF16(X)                                                                                 \
+    X(EL_BF16, 2, 8, 16, CM_U8T, 8, 0) X(EL_BF16, 1, 2, 8, CM_U8T, 8, 1) X(EL_BF16, 1, 5, 16, CM_ROWSV, 16, 1) \
+    X(EL_BF16, 2, 5, 16, CM_ROWSV, 16, 1) X(EL_BF16, 2, 9, 16, CM_ROWSV, 16, 1) X(EL_BF16, 2, 9, 16, CM_ROWSV, 8, 1) \
+    X(EL_BF16, 4, 0, 16, CM_FLAT, 8, 0)
 
 // Wave-private variants (8 wavefronts, weights in LDS, contiguous staging): (element, NT, RD, PF, PT)
 constexpr int CONV_WP_WAVES = 8;
@@ -631,10 +650,10 @@ hipError_t conv_go_generic(const ConvParams& p, int rd, dim3 grid, size_t lds, h
     const bool a16 = rd == 16;
     constexpr int PT = conv_pt(NT);
     switch (p.mode) {
-        case CM_FLAT: return a16 ? conv_go<EL, NT, 0, 16, CM_FLAT, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_FLAT, 16, PT, 4, false>(p, grid, lds, s);
-        case CM_ROWS: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWS, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWS, 16, PT, 4, false>(p, grid, lds, s);
-        case CM_ROWSV: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWSV, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWSV, 16, PT, 4, false>(p, grid, lds, s);
-        case CM_U8T: return a16 ? conv_go<EL, NT, 0, 16, CM_U8T, 16, PT, 4, false>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_U8T, 16, PT, 4, false>(p, grid, lds, s);
+        case CM_FLAT: return a16 ? conv_go<EL, NT, 0, 16, CM_FLAT, 16, PT, 4, false, true>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_FLAT, 16, PT, 4, false, true>(p, grid, lds, s);
+        case CM_ROWS: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWS, 16, PT, 4, false, true>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWS, 16, PT, 4, false, true>(p, grid, lds, s);
+        case CM_ROWSV: return a16 ? conv_go<EL, NT, 0, 16, CM_ROWSV, 16, PT, 4, false, true>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_ROWSV, 16, PT, 4, false, true>(p, grid, lds, s);
+        case CM_U8T: return a16 ? conv_go<EL, NT, 0, 16, CM_U8T, 16, PT, 4, false, true>(p, grid, lds, s) : conv_go<EL, NT, 0, 4, CM_U8T, 16, PT, 4, false, true>(p, grid, lds, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -7,10 +7,10 @@ namespace accerl {
 // if one is listed, else a tuned LDS-weight variant, else the generic family.  Returns the staging
 // depth (units per lane) of the chosen kernel in *PF, 0 in *KS for LDS weights; false if `pf` units
 // per lane cannot be staged by any kernel.
-bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, int* KS, int* PF) {
+bool conv_pick_variant(Elem el, int NT, int k_steps, int RD, int mode, int pf, bool extras, int* KS, int* PF) {
     int best_reg = 0, best_lds = 0;
-#define X(E, N, K, R, M, P)                                                                  \
-    if (el == E && NT == N && RD == R && mode == M && pf <= P) {                             \
+#define X(E, N, K, R, M, P, F)                                                               \
+    if (el == E && NT == N && RD == R && mode == M && pf <= P && (F || !extras)) {           \
         if (K == k_steps && (best_reg == 0 || P < best_reg)) best_reg = P;                   \
         if (K == 0 && (best_lds == 0 || P < best_lds)) best_lds = P;                         \
     }
@@ -51,7 +51,7 @@ hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int
     const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16 + CONV_LDS_CONST) + (size_t)p.lds_tiles + (size_t)(p.pool ? p.lds_otile : 0);
     dim3 grid((unsigned)p.n_bands, 1);
     if (p.wave_private) {
-        if (KS != 0 || p.mode != CM_FLAT || p.n_bands != 1 || p.G * p.units_img > 64 * CONV_WP_PF) return hipErrorInvalidValue;
+        if (KS != 0 || p.mode != CM_FLAT || p.res || p.pool || p.n_bands != 1 || p.G * p.units_img > 64 * CONV_WP_PF) return hipErrorInvalidValue;
         return conv_launch_wp_i8(p, NT, RD, p.wp_pt, grid, lds, s);
     }
     if ((p.G * p.units_img + 255) / 256 > PF) return hipErrorInvalidValue;
