@@ -20,8 +20,7 @@ def build(force=True):
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(_SO):
-            build()
+        build(force=False)   # also when the source is newer than the library
         _lib = ctypes.CDLL(_SO)
         _lib.orc_bf16_round_scalar.restype = ctypes.c_float
         _lib.orc_bf16_round_scalar.argtypes = [ctypes.c_float]

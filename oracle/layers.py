@@ -166,3 +166,35 @@ def lstm_step(x, h, c, done, w_ih, w_hh, bias, bf16):
     lib().orc_lstm_step(_p(x), C.c_int64(B), In, Hd, _p(done) if done is not None else None,
                         _p(w_ih), _p(w_hh), _p(bias), int(bf16), _p(h), _p(c))
     return h, c
+
+
+def kl_monitor(logits_original, logits_smaller):
+    """Monitor indicators: per-state KL(original || smaller), entropy of the smaller policy,
+    stats = [KL mean, KL max, KL variance, entropy mean] (all float64)."""
+    lo, ls = _c(logits_original, np.float32), _c(logits_smaller, np.float32)
+    B, A = lo.shape
+    assert ls.shape == (B, A) and A <= 256
+    kl = np.empty(B, np.float64)
+    ent = np.empty(B, np.float64)
+    stats = np.empty(4, np.float64)
+    lib().orc_kl_monitor(_p(lo), _p(ls), C.c_int64(B), A, _p(kl), _p(ent), _p(stats))
+    return kl, ent, stats
+
+
+def vtrace(logits_original, logits_smaller, actions, rewards, discounts, values, bootstrap,
+           rho_bar=1.0, c_bar=1.0):
+    """V-trace targets v_s, importance-weighted advantages and rho_t, time-major [T, B]."""
+    lo, ls = _c(logits_original, np.float32), _c(logits_smaller, np.float32)
+    T, B, A = lo.shape
+    assert ls.shape == (T, B, A) and A <= 256 and T <= 4096
+    a = _c(actions, np.int32)
+    r, d, v = _c(rewards, np.float32), _c(discounts, np.float32), _c(values, np.float32)
+    bs = _c(bootstrap, np.float32)
+    assert a.shape == r.shape == d.shape == v.shape == (T, B) and bs.shape == (B,)
+    assert a.min() >= 0 and a.max() < A
+    vs = np.empty((T, B), np.float64)
+    adv = np.empty((T, B), np.float64)
+    rho = np.empty((T, B), np.float64)
+    lib().orc_vtrace(_p(lo), _p(ls), _p(a), _p(r), _p(d), _p(v), _p(bs), C.c_int64(T), C.c_int64(B), A,
+                     C.c_double(rho_bar), C.c_double(c_bar), _p(vs), _p(adv), _p(rho))
+    return vs, adv, rho

@@ -323,3 +323,100 @@ void orc_lstm_step(const float* x, int64_t B, int In, int Hd, const uint8_t* don
         for (int j = 0; j < Hd; ++j) { hb[j] = hn[j]; cb[j] = cn[j]; }
     }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Monitor indicators and off-policy correction (paper Section 2.4 "Corrector", Section 2.5
+ * "Monitor").  fp64 throughout; inputs are the fp32 logits / values the actor and the
+ * learner's network produced.
+ * ------------------------------------------------------------------------------------------ */
+
+/* log-softmax of one row in double */
+static void orc_logsoftmax_row(const float* l, int A, double* logp) {
+    double m = (double)l[0];
+    for (int a = 1; a < A; ++a) if ((double)l[a] > m) m = (double)l[a];
+    double Z = 0.0;
+    for (int a = 0; a < A; ++a) Z += exp((double)l[a] - m);
+    const double lz = log(Z);
+    for (int a = 0; a < A; ++a) logp[a] = (double)l[a] - m - lz;
+}
+
+/* Monitor section, KL equation: per state, KL(pi_original || pi_smaller) =
+ * sum_a pi_original(a|x) log(pi_original(a|x) / pi_smaller(a|x)); and the policy entropy
+ * H(pi_smaller) = -sum_a pi_smaller log pi_smaller (the "entropy" indicator; also the H of
+ * Section 2.2 Eq. 1).  stats = {KL mean, KL max, KL variance, entropy mean} over the B states;
+ * the paper names the indicators without formulas: the variance is taken as the population
+ * variance mean((KL - mean)^2). */
+void orc_kl_monitor(const float* logits_original, const float* logits_smaller, int64_t B, int A,
+                    double* kl, double* entropy, double* stats) {
+    double po[256], ps[256];
+    double sum = 0.0, mx = 0.0, hsum = 0.0;
+    for (int64_t b = 0; b < B; ++b) {
+        orc_logsoftmax_row(logits_original + b * A, A, po);
+        orc_logsoftmax_row(logits_smaller + b * A, A, ps);
+        double k = 0.0, h = 0.0;
+        for (int a = 0; a < A; ++a) {
+            k += exp(po[a]) * (po[a] - ps[a]);
+            h -= exp(ps[a]) * ps[a];
+        }
+        kl[b] = k;
+        entropy[b] = h;
+        sum += k;
+        hsum += h;
+        if (b == 0 || k > mx) mx = k;
+    }
+    const double mean = B > 0 ? sum / (double)B : 0.0;
+    double var = 0.0;
+    for (int64_t b = 0; b < B; ++b) var += (kl[b] - mean) * (kl[b] - mean);
+    stats[0] = mean;
+    stats[1] = mx;
+    stats[2] = B > 0 ? var / (double)B : 0.0;
+    stats[3] = B > 0 ? hsum / (double)B : 0.0;
+}
+
+/* Corrector section, V-trace equation, written out as printed (a sum over the remaining steps
+ * of the trajectory, not a recurrence):
+ *   rho_t = min(rho_bar, pi_original(a_t|x_t) / pi_smaller(a_t|x_t)),  c_i likewise with c_bar
+ *   delta_t V = rho_t (r_t + gamma_t V(x_{t+1}) - V(x_t))
+ *   v_s = V(x_s) + sum_{t=s}^{T-1} (prod_{i=s}^{t-1} gamma_i c_i) delta_t V
+ * Tensors are time-major [T, B(, A)]; V(x_T) is the bootstrap value.  The paper's gamma^{t-s}
+ * is read as the product of per-step discounts gamma_i (gamma, or 0 where an episode ended),
+ * and its n as the steps left in the trajectory.  Also returned: rho_t and the importance-
+ * weighted advantage rho_t (r_t + gamma_t v_{t+1} - V(x_t)) of the actor-critic update
+ * (Corrector section, last equation, first line), with v_T = V(x_T). */
+void orc_vtrace(const float* logits_original, const float* logits_smaller, const int32_t* actions,
+                const float* rewards, const float* discounts, const float* values,
+                const float* bootstrap, int64_t T, int64_t B, int A, double rho_bar, double c_bar,
+                double* vs, double* pg_adv, double* rho) {
+    double lo[256], ls[256];
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) private(lo, ls)
+#endif
+    for (int64_t b = 0; b < B; ++b) {
+        /* rho_t, c_t are kept in rho[] and a local array */
+        double cc[4096];
+        for (int64_t t = 0; t < T; ++t) {
+            const int64_t i = t * B + b;
+            orc_logsoftmax_row(logits_original + i * A, A, lo);
+            orc_logsoftmax_row(logits_smaller + i * A, A, ls);
+            const double ratio = exp(lo[actions[i]] - ls[actions[i]]);
+            rho[i] = ratio < rho_bar ? ratio : rho_bar;
+            cc[t] = ratio < c_bar ? ratio : c_bar;
+        }
+        for (int64_t s = 0; s < T; ++s) {
+            double acc = 0.0, prod = 1.0;
+            for (int64_t t = s; t < T; ++t) {
+                const int64_t i = t * B + b;
+                const double vnext = (t + 1 < T) ? (double)values[(t + 1) * B + b] : (double)bootstrap[b];
+                const double delta = rho[i] * ((double)rewards[i] + (double)discounts[i] * vnext - (double)values[i]);
+                acc += prod * delta;
+                prod *= (double)discounts[i] * cc[t];
+            }
+            vs[s * B + b] = (double)values[s * B + b] + acc;
+        }
+        for (int64_t t = 0; t < T; ++t) {
+            const int64_t i = t * B + b;
+            const double vnext = (t + 1 < T) ? vs[(t + 1) * B + b] : (double)bootstrap[b];
+            pg_adv[i] = rho[i] * ((double)rewards[i] + (double)discounts[i] * vnext - (double)values[i]);
+        }
+    }
+}

@@ -12,5 +12,6 @@ from .nets import (  # noqa: F401
 )
 from .data import (  # noqa: F401
     init_params, make_obs_f32, make_frames_u8, make_uniforms, make_done, make_hc,
+    make_logits_pair, make_trajectory,
 )
 from .configs import CONFIGS, get_config  # noqa: F401

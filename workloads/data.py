@@ -63,6 +63,31 @@ def make_hc(B, H, std=0.1, seed=BASE_SEED):
     return h.astype(np.float32), c.astype(np.float32)
 
 
+def make_logits_pair(B, A, gap=0.3, scale=2.0, first=0, seed=BASE_SEED, stream=STREAM["monitor_logits"]):
+    """Two float32 [B, A] logit tables standing for the original and the compressed policy on the same
+    states: the first ~ scale * N(0, 1), the second = the first + gap * N(0, 1) (a compressed network
+    tracks its teacher up to a perturbation)."""
+    base = normal(seed, stream, 2 * first * A, B * A).reshape(B, A) * np.float32(scale)
+    pert = normal(seed, stream + 100, 2 * first * A, B * A).reshape(B, A) * np.float32(gap)
+    return base.astype(np.float32), (base + pert).astype(np.float32)
+
+
+def make_trajectory(T, B, A, gamma=0.99, p_done=0.01, seed=BASE_SEED, stream=STREAM["trajectory"]):
+    """One unroll of T steps for B environments, time-major: logits of both policies [T, B, A], the
+    actions taken (uniform over A), rewards ~ N(0, 1) mostly zero (sparse, as in Atari), discounts
+    gamma * (1 - done), values ~ N(0, 1) [T, B] and the bootstrap value [B]."""
+    lo, ls = make_logits_pair(T * B, A, seed=seed, stream=stream)
+    n = T * B
+    actions = randint(seed, stream + 1, 0, n, 0, A - 1).astype(np.int32).reshape(T, B)
+    rewards = (normal(seed, stream + 2, 0, n) * (uniform01(seed, stream + 3, 0, n) < np.float32(0.1))).astype(np.float32).reshape(T, B)
+    done = uniform01(seed, stream + 4, 0, n) < np.float32(p_done)
+    discounts = (np.float32(gamma) * (1.0 - done.astype(np.float32))).astype(np.float32).reshape(T, B)
+    values = normal(seed, stream + 5, 0, n).reshape(T, B).astype(np.float32)
+    bootstrap = normal(seed, stream + 6, 0, B).astype(np.float32)
+    return dict(logits_original=lo.reshape(T, B, A), logits_smaller=ls.reshape(T, B, A), actions=actions,
+                rewards=rewards, discounts=discounts, values=values, bootstrap=bootstrap)
+
+
 def make_frames_u8(B, C=4, H=84, W=84, stream=STREAM["states"], first=0, n_rect=6, seed=BASE_SEED):
     """uint8 [B, C, H, W]: i.i.d. bytes, then per frame-channel n_rect constant rectangles.
 

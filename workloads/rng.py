@@ -18,6 +18,8 @@ STREAM = {
     "done": 6,
     "hc": 7,
     "rectangles": 8,
+    "monitor_logits": 9,
+    "trajectory": 10,
 }
 
 _GOLD = np.uint64(0x9E3779B97F4A7C15)
