@@ -199,6 +199,43 @@ int accerl_profile_end(accerl_policy* p, int32_t cap, int32_t* n_steps, float* t
 int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t weights_bytes,
                          const float* quant_scales, int64_t n_scales, char* text, int64_t cap);
 
+/*
+ * Monitor indicators (Monitor section, KL equation): for B states on which both the original and
+ * the smaller (compressed) policy were evaluated,
+ *     KL_b = sum_a pi_original(a|x_b) log(pi_original(a|x_b) / pi_smaller(a|x_b)),
+ *     H_b  = -sum_a pi_smaller(a|x_b) log pi_smaller(a|x_b)     (the entropy indicator; Section 2.2 Eq. 1)
+ * with pi = softmax of the logits.  logits_* : DEVICE fp32 [B, A] row-major, 16-byte aligned,
+ * 1 <= A <= 64.  out_kl, out_entropy: DEVICE fp32 [B] or NULL.  out_stats: DEVICE double[4] =
+ * {KL mean, KL max, KL variance (population: mean of squares minus squared mean), entropy mean},
+ * the indicators the Monitor's strategies read.  Per-row arithmetic is fp32, the reductions are
+ * fp64 in a fixed order (results do not depend on the launch).  Asynchronous on hip_stream; the
+ * library keeps one small per-device buffer of partial sums, so calls that overlap on one device
+ * must use the same stream.  B == 0 is a no-op.  Errors: ACCERL_EINVAL for NULL / misaligned /
+ * out-of-range arguments, ACCERL_ENOMEM, ACCERL_EHIP.
+ */
+int accerl_monitor_kl(const float* logits_original, const float* logits_smaller, int64_t B, int A,
+                      float* out_kl, float* out_entropy, double* out_stats, void* hip_stream);
+
+/*
+ * V-trace corrector (Corrector section, V-trace equation) for B trajectories of T steps collected
+ * by the smaller policy and corrected towards the original one.  Time-major tensors, all DEVICE:
+ *   logits_original, logits_smaller  fp32 [T, B, A], 16-byte aligned, 1 <= A <= 64
+ *   actions int32 [T, B] (the a_t taken; clamped into 0..A-1), rewards, discounts, values fp32 [T, B]
+ *   (discounts = gamma, or 0 where the episode ended at that step; values = V(x_t)),
+ *   bootstrap fp32 [B] = V(x_T).
+ *   rho_t = min(rho_bar, pi_original(a_t|x_t) / pi_smaller(a_t|x_t)),  c_t = min(c_bar, same ratio)
+ *   delta_t = rho_t (r_t + gamma_t V(x_{t+1}) - V(x_t))
+ *   v_s = V(x_s) + sum_{t=s}^{T-1} (prod_{i=s}^{t-1} gamma_i c_i) delta_t   (evaluated as a backward scan)
+ * Outputs fp32 [T, B]: out_vs = v_s; out_rho = rho_t (also the importance weight of the Importance
+ * Sampling corrector); out_pg_adv (may be NULL) = rho_t (r_t + gamma_t v_{t+1} - V(x_t)), v_T = V(x_T),
+ * the advantage of the corrected actor-critic update.  out_rho is also used as scratch during the
+ * call.  Asynchronous on hip_stream; allocates nothing.  T == 0 or B == 0 is a no-op.
+ */
+int accerl_vtrace(const float* logits_original, const float* logits_smaller, const int32_t* actions,
+                  const float* rewards, const float* discounts, const float* values, const float* bootstrap,
+                  int64_t T, int64_t B, int A, float rho_bar, float c_bar,
+                  float* out_vs, float* out_pg_adv, float* out_rho, void* hip_stream);
+
 /* Message of the last error on this thread ("" if none). */
 const char* accerl_last_error(void);
 

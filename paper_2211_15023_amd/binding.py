@@ -55,6 +55,10 @@ def load_library():
     lib.accerl_plan_describe.restype = C.c_int
     lib.accerl_profile_begin.argtypes = [vp]
     lib.accerl_profile_end.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.accerl_monitor_kl.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
+    lib.accerl_vtrace.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, C.c_float, C.c_float, vp, vp, vp, vp]
+    lib.accerl_monitor_kl.restype = C.c_int
+    lib.accerl_vtrace.restype = C.c_int
     lib.accerl_last_error.restype = C.c_char_p
     for f in ("accerl_blob_sizes", "accerl_policy_create", "accerl_actor_forward", "accerl_actor_forward_teacher",
               "accerl_actor_forward_recurrent", "accerl_actor_forward_debug", "accerl_profile_begin",
@@ -207,6 +211,33 @@ def accerl_actor_forward_debug(handle, states, layer, tap, out, stream=None):
     B = states.shape[0]
     _check(load_library().accerl_actor_forward_debug(handle, _ptr(states), B, int(layer), int(tap), _ptr(out),
                                                      out.numel() * out.element_size(), _stream(stream)))
+
+
+def accerl_monitor_kl(logits_original, logits_smaller, out_kl, out_entropy, out_stats, stream=None):
+    """out_stats: float64 device tensor [4] = KL mean, KL max, KL variance, entropy mean."""
+    import torch
+    B, A = logits_original.shape
+    if tuple(logits_smaller.shape) != (B, A):
+        raise ValueError("logit tables differ in shape")
+    _check(load_library().accerl_monitor_kl(_ptr(logits_original, torch.float32), _ptr(logits_smaller, torch.float32), B, A,
+                                            _ptr(out_kl, torch.float32), _ptr(out_entropy, torch.float32),
+                                            _ptr(out_stats, torch.float64), _stream(stream)))
+
+
+def accerl_vtrace(logits_original, logits_smaller, actions, rewards, discounts, values, bootstrap,
+                  rho_bar, c_bar, out_vs, out_pg_adv, out_rho, stream=None):
+    import torch
+    T, B, A = logits_original.shape
+    if tuple(logits_smaller.shape) != (T, B, A):
+        raise ValueError("logit tables differ in shape")
+    for t in (actions, rewards, discounts, values, out_vs, out_rho):
+        if tuple(t.shape) != (T, B):
+            raise ValueError("per-step tensors must be [T, B]")
+    _check(load_library().accerl_vtrace(_ptr(logits_original, torch.float32), _ptr(logits_smaller, torch.float32),
+                                        _ptr(actions, torch.int32), _ptr(rewards, torch.float32), _ptr(discounts, torch.float32),
+                                        _ptr(values, torch.float32), _ptr(bootstrap, torch.float32), T, B, A,
+                                        float(rho_bar), float(c_bar), _ptr(out_vs, torch.float32),
+                                        _ptr(out_pg_adv, torch.float32), _ptr(out_rho, torch.float32), _stream(stream)))
 
 
 STEP_KINDS = ("mlp_fused", "quant_obs", "conv", "gemm", "gemm_f32", "maxpool", "lstm_pack", "sample", "heads")

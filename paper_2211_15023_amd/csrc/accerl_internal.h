@@ -13,6 +13,9 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 enum Elem : int { EL_I8 = 0, EL_BF16 = 1, EL_F32 = 2 };
 
+// records the thread's error message and returns `code`
+int set_error(int code, const char* msg);
+
 // ---------------------------------------------------------------- fused int8 MLP (wave per 16 rows)
 constexpr int MLP_MAX_LAYERS = 4;   // hidden layers; the heads come on top
 struct MlpParams {

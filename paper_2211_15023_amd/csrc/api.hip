@@ -26,6 +26,16 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
+}  // namespace
+
+// error reporting for the other translation units of the C ABI
+int accerl::set_error(int code, const char* msg) {
+    g_err = msg;
+    return code;
+}
+
+namespace {
+
 #define HIP_TRY(expr)                                                                         \
     do {                                                                                      \
         hipError_t e_ = (expr);                                                               \

@@ -1,0 +1,240 @@
+// Monitor indicators and V-trace correction: the two consumers of the actor's behaviour logits.
+// Both are row-wise passes over [rows, A] logit tables of the original and the smaller policy and are
+// bound by HBM traffic: a wavefront copies 64 consecutive rows of both tables into LDS with coalesced
+// 16-byte loads and every lane then works on its own row out of LDS.
+#include <cstdio>
+
+#include "accerl_internal.h"
+
+namespace accerl {
+
+constexpr int MON_AMAX = 64;        // most actions
+constexpr int MON_PARTS = 1024;     // most workgroups of a reduction pass
+
+// 64 rows of `tab` starting at row r0 -> LDS (row pitch A floats).  The tile starts 256*A bytes into the
+// table, so 16-byte loads are aligned whenever the table is.
+__device__ __forceinline__ void stage_rows(const float* __restrict__ tab, int64_t r0, int nrows, int A, float* sm, int lane) {
+    const float* src = tab + r0 * A;
+    const int n = nrows * A, n4 = n >> 2;
+    for (int i = lane; i < n4; i += 64) ((v4f*)sm)[i] = ((const v4f*)src)[i];
+    for (int i = (n4 << 2) + lane; i < n; i += 64) sm[i] = src[i];
+}
+
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// max and log-sum-exp normaliser of one row in LDS: logp[a] = row[a] - m - lz.  Lane l walks its row
+// starting at element `rot` = l mod A, so that the lanes of a wavefront (rows A floats apart) do not all
+// hit the same LDS bank when A is a multiple of 16.
+__device__ __forceinline__ void row_norm(const float* row, int A, int rot, float& m, float& lz) {
+    m = row[rot];
+    for (int a = 1; a < A; ++a) { int k = a + rot; k -= (k >= A) ? A : 0; m = fmaxf(m, row[k]); }
+    float Z = 0.0f;
+    for (int a = 0; a < A; ++a) { int k = a + rot; k -= (k >= A) ? A : 0; Z += expf(row[k] - m); }
+    lz = logf(Z);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_down(v, o, 64));
+    return v;
+}
+
+// ---- KL(original || smaller) and entropy of the smaller policy per state; per-workgroup partial sums
+__global__ __launch_bounds__(64) void kl_rows_kernel(const float* __restrict__ lo, const float* __restrict__ ls, int64_t B, int A,
+                                                     float* __restrict__ out_kl, float* __restrict__ out_ent, double* __restrict__ parts) {
+    extern __shared__ __attribute__((aligned(16))) float mon_sm[];
+    float* so = mon_sm;
+    float* ss = mon_sm + 64 * A;
+    const int lane = threadIdx.x;
+    double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0;
+    const int64_t n_tiles = (B + 63) >> 6;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t r0 = tile << 6;
+        const int nrows = (int)((B - r0 < 64) ? (B - r0) : 64);
+        stage_rows(lo, r0, nrows, A, so, lane);
+        stage_rows(ls, r0, nrows, A, ss, lane);
+        wave_sync_lds();
+        if (lane < nrows) {
+            const float* ro = so + lane * A;
+            const float* rs = ss + lane * A;
+            const int rot = lane % A;
+            float mo, lzo, ms, lzs;
+            row_norm(ro, A, rot, mo, lzo);
+            row_norm(rs, A, rot, ms, lzs);
+            float kl = 0.0f, h = 0.0f;
+            for (int a = 0; a < A; ++a) {
+                int k = a + rot;
+                k -= (k >= A) ? A : 0;
+                const float lpo = ro[k] - mo - lzo, lps = rs[k] - ms - lzs;
+                kl += expf(lpo) * (lpo - lps);
+                h -= expf(lps) * lps;
+            }
+            if (out_kl) out_kl[r0 + lane] = kl;
+            if (out_ent) out_ent[r0 + lane] = h;
+            s_kl += (double)kl;
+            s_sq += (double)kl * (double)kl;
+            s_mx = fmax(s_mx, (double)kl);
+            s_h += (double)h;
+        }
+        wave_sync_lds();   // rows are read before the next tile overwrites them
+    }
+    s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx);
+    if (lane == 0) {
+        double* p = parts + 4 * (int64_t)blockIdx.x;
+        p[0] = s_kl; p[1] = s_sq; p[2] = s_mx; p[3] = s_h;
+    }
+}
+
+// one wavefront folds the partials in a fixed order: stats = {mean, max, population variance, entropy mean}
+__global__ __launch_bounds__(64) void kl_stats_kernel(const double* __restrict__ parts, int n_parts, int64_t B, double* __restrict__ stats) {
+    const int lane = threadIdx.x;
+    double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0;
+    for (int i = lane; i < n_parts; i += 64) {
+        s_kl += parts[4 * i]; s_sq += parts[4 * i + 1]; s_mx = fmax(s_mx, parts[4 * i + 2]); s_h += parts[4 * i + 3];
+    }
+    s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx);
+    if (lane == 0) {
+        const double n = (double)B, mean = s_kl / n;
+        stats[0] = mean;
+        stats[1] = s_mx;
+        stats[2] = fmax(s_sq / n - mean * mean, 0.0);
+        stats[3] = s_h / n;
+    }
+}
+
+// ---- importance ratio pi_original(a|x) / pi_smaller(a|x) of the action taken, one row per (t, b)
+__global__ __launch_bounds__(64) void is_ratio_kernel(const float* __restrict__ lo, const float* __restrict__ ls, const int32_t* __restrict__ act,
+                                                      int64_t R, int A, float* __restrict__ ratio) {
+    extern __shared__ __attribute__((aligned(16))) float mon_sm[];
+    float* so = mon_sm;
+    float* ss = mon_sm + 64 * A;
+    const int lane = threadIdx.x;
+    const int64_t n_tiles = (R + 63) >> 6;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t r0 = tile << 6;
+        const int nrows = (int)((R - r0 < 64) ? (R - r0) : 64);
+        stage_rows(lo, r0, nrows, A, so, lane);
+        stage_rows(ls, r0, nrows, A, ss, lane);
+        wave_sync_lds();
+        if (lane < nrows) {
+            const float* ro = so + lane * A;
+            const float* rs = ss + lane * A;
+            const int rot = lane % A;
+            float mo, lzo, ms, lzs;
+            row_norm(ro, A, rot, mo, lzo);
+            row_norm(rs, A, rot, ms, lzs);
+            int a = act[r0 + lane];
+            a = min(max(a, 0), A - 1);
+            ratio[r0 + lane] = expf((ro[a] - mo - lzo) - (rs[a] - ms - lzs));
+        }
+        wave_sync_lds();
+    }
+}
+
+// ---- backward scan per environment: v_s - V(x_s) = delta_s + gamma_s c_s (v_{s+1} - V(x_{s+1}))
+__global__ __launch_bounds__(256) void vtrace_scan_kernel(const float* __restrict__ rewards, const float* __restrict__ discounts,
+                                                          const float* __restrict__ values, const float* __restrict__ bootstrap,
+                                                          int64_t T, int64_t B, float rho_bar, float c_bar,
+                                                          float* __restrict__ rho /* in: ratio, out: clipped */,
+                                                          float* __restrict__ vs, float* __restrict__ pg_adv) {
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    float v_next = bootstrap[b];      // V(x_{t+1})
+    float vs_next = v_next;           // v_{t+1}
+    float acc = 0.0f;                 // v_{t+1} - V(x_{t+1})
+    for (int64_t t = T - 1; t >= 0; --t) {
+        const int64_t i = t * B + b;
+        const float ratio = rho[i], r = rewards[i], g = discounts[i], v = values[i];
+        const float rh = fminf(rho_bar, ratio), c = fminf(c_bar, ratio);
+        const float delta = rh * (r + g * v_next - v);
+        acc = delta + g * c * acc;
+        const float vs_t = v + acc;
+        if (pg_adv) pg_adv[i] = rh * (r + g * vs_next - v);
+        vs[i] = vs_t;
+        rho[i] = rh;
+        v_next = v;
+        vs_next = vs_t;
+    }
+}
+
+static double* mon_parts(int dev) {
+    static double* parts[64] = {nullptr};
+    if (dev < 0 || dev >= 64) return nullptr;
+    if (!parts[dev] && hipMalloc((void**)&parts[dev], (size_t)MON_PARTS * 4 * sizeof(double)) != hipSuccess) {
+        (void)hipGetLastError();
+        parts[dev] = nullptr;
+    }
+    return parts[dev];
+}
+
+static int hip_fail(const char* what, hipError_t e) {
+    char buf[256];
+    snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+    return set_error(ACCERL_EHIP, buf);
+}
+
+static int raise_lds(const void* fn, size_t lds) {
+    if (lds <= 48 * 1024) return ACCERL_OK;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    return e == hipSuccess ? ACCERL_OK : hip_fail("hipFuncSetAttribute", e);
+}
+
+}  // namespace accerl
+
+using namespace accerl;
+
+extern "C" int accerl_monitor_kl(const float* logits_original, const float* logits_smaller, int64_t B, int A,
+                                 float* out_kl, float* out_entropy, double* out_stats, void* hip_stream) {
+    if (B < 0 || A < 1 || A > MON_AMAX) return set_error(ACCERL_EINVAL, "monitor: need B >= 0 and 1 <= A <= 64");
+    if (B == 0) return ACCERL_OK;
+    if (!logits_original || !logits_smaller || !out_stats) return set_error(ACCERL_EINVAL, "monitor: NULL logits or stats pointer");
+    if (((uintptr_t)logits_original | (uintptr_t)logits_smaller) & 15) return set_error(ACCERL_EINVAL, "monitor: logits must be 16-byte aligned");
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail("hipGetDevice", e);
+    double* parts = mon_parts(dev);
+    if (!parts) return set_error(ACCERL_ENOMEM, "monitor: partial-sum buffer");
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t n_tiles = (B + 63) / 64;
+    const int blocks = (int)(n_tiles < MON_PARTS ? n_tiles : MON_PARTS);
+    const size_t lds = (size_t)2 * 64 * A * sizeof(float);
+    if (int rc = raise_lds((const void*)kl_rows_kernel, lds)) return rc;
+    kl_rows_kernel<<<dim3(blocks), dim3(64), lds, s>>>(logits_original, logits_smaller, B, A, out_kl, out_entropy, parts);
+    if ((e = hipGetLastError()) != hipSuccess) return hip_fail("kl_rows_kernel", e);
+    kl_stats_kernel<<<dim3(1), dim3(64), 0, s>>>(parts, blocks, B, out_stats);
+    if ((e = hipGetLastError()) != hipSuccess) return hip_fail("kl_stats_kernel", e);
+    return ACCERL_OK;
+}
+
+extern "C" int accerl_vtrace(const float* logits_original, const float* logits_smaller, const int32_t* actions,
+                             const float* rewards, const float* discounts, const float* values, const float* bootstrap,
+                             int64_t T, int64_t B, int A, float rho_bar, float c_bar,
+                             float* out_vs, float* out_pg_adv, float* out_rho, void* hip_stream) {
+    if (T < 0 || B < 0 || A < 1 || A > MON_AMAX) return set_error(ACCERL_EINVAL, "vtrace: need T, B >= 0 and 1 <= A <= 64");
+    if (!(rho_bar >= 0.0f) || !(c_bar >= 0.0f)) return set_error(ACCERL_EINVAL, "vtrace: rho_bar and c_bar must be >= 0");
+    if (T == 0 || B == 0) return ACCERL_OK;
+    if (!logits_original || !logits_smaller || !actions || !rewards || !discounts || !values || !bootstrap || !out_vs || !out_rho)
+        return set_error(ACCERL_EINVAL, "vtrace: NULL argument (only out_pg_adv may be NULL)");
+    if (((uintptr_t)logits_original | (uintptr_t)logits_smaller) & 15) return set_error(ACCERL_EINVAL, "vtrace: logits must be 16-byte aligned");
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t R = T * B, n_tiles = (R + 63) / 64;
+    const int blocks = (int)(n_tiles < 256 * 16 ? n_tiles : 256 * 16);
+    const size_t lds = (size_t)2 * 64 * A * sizeof(float);
+    if (int rc = raise_lds((const void*)is_ratio_kernel, lds)) return rc;
+    is_ratio_kernel<<<dim3(blocks), dim3(64), lds, s>>>(logits_original, logits_smaller, actions, R, A, out_rho);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("is_ratio_kernel", e);
+    vtrace_scan_kernel<<<dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s>>>(rewards, discounts, values, bootstrap, T, B, rho_bar, c_bar,
+                                                                              out_rho, out_vs, out_pg_adv);
+    if ((e = hipGetLastError()) != hipSuccess) return hip_fail("vtrace_scan_kernel", e);
+    return ACCERL_OK;
+}

@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(A):
     names = set(re.findall(r"\b(accerl_[a-z_0-9]+)\s*\(", hdr))
     assert {"accerl_policy_create", "accerl_actor_forward", "accerl_actor_forward_teacher",
             "accerl_actor_forward_recurrent", "accerl_actor_forward_debug", "accerl_policy_destroy",
-            "accerl_last_error", "accerl_blob_sizes"} <= names
+            "accerl_last_error", "accerl_blob_sizes", "accerl_monitor_kl", "accerl_vtrace"} <= names
     lib = A.load_library()
     for n in names:
         assert hasattr(lib, n), n
@@ -102,3 +102,17 @@ def test_product_code_never_touches_the_oracle():
         for f in files:
             if f.endswith((".py", ".c")):
                 assert "paper_2211_15023_amd" not in open(os.path.join(dirpath, f)).read(), f
+
+
+def test_monitor_and_vtrace_reject_bad_arguments_before_any_launch(A):
+    lib = A.load_library()
+    # nothing below reaches the GPU: every call fails (or is a no-op) in the argument checks
+    assert lib.accerl_monitor_kl(None, None, 0, 18, None, None, None, None) == 0          # B = 0: no-op
+    assert lib.accerl_monitor_kl(None, None, 8, 18, None, None, None, None) == -1
+    assert "NULL" in A.accerl_last_error()
+    assert lib.accerl_monitor_kl(None, None, 8, 65, None, None, None, None) == -1
+    assert lib.accerl_monitor_kl(None, None, -1, 4, None, None, None, None) == -1
+    assert lib.accerl_vtrace(None, None, None, None, None, None, None, 0, 4, 6, 1.0, 1.0, None, None, None, None) == 0
+    assert lib.accerl_vtrace(None, None, None, None, None, None, None, 4, 4, 6, 1.0, 1.0, None, None, None, None) == -1
+    assert lib.accerl_vtrace(None, None, None, None, None, None, None, 4, 4, 0, 1.0, 1.0, None, None, None, None) == -1
+    assert lib.accerl_vtrace(None, None, None, None, None, None, None, 4, 4, 6, -1.0, 1.0, None, None, None, None) == -1
