@@ -211,6 +211,38 @@ def main():
         s160 = time_forward(student, x[:b160].contiguous(), u[:b160].contiguous(), o160, 200, 20, **kw160)
         t160 = time_forward(teacher, xt[:b160].contiguous(), u[:b160].contiguous(), teacher.alloc_outputs(b160), 100, 10, **kw160)
         extra["latency_B160_us"] = dict(student=round(s160 * 1e6, 2), teacher=round(t160 * 1e6, 2))
+        # the two consumers of the behaviour logits, on one unroll of 16 steps x B environments
+        # (Monitor section, KL equation; Corrector section, V-trace equation); both HBM-bound
+        nA = ns.n_actions
+
+        def timed(fn, n=50):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / n
+        for Tn, tag in ((16, ""), (256, "_long")):      # one unroll as configured; a long one where launch cost fades
+            tr = wl.make_trajectory(Tn, B, nA)
+            dv = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in tr.items()}
+            rows = Tn * B
+            klo = torch.empty(rows, dtype=torch.float32, device="cuda")
+            eno = torch.empty_like(klo)
+            sto = torch.zeros(4, dtype=torch.float64, device="cuda")
+            lo2, ls2 = dv["logits_original"].view(rows, nA), dv["logits_smaller"].view(rows, nA)
+            vso = torch.empty(Tn, B, dtype=torch.float32, device="cuda")
+            ado, rho = torch.empty_like(vso), torch.empty_like(vso)
+            t_kl = timed(lambda: A.accerl_monitor_kl(lo2, ls2, klo, eno, sto))
+            t_vt = timed(lambda: A.accerl_vtrace(dv["logits_original"], dv["logits_smaller"], dv["actions"], dv["rewards"],
+                                                dv["discounts"], dv["values"], dv["bootstrap"], 1.0, 1.0, vso, ado, rho))
+            kl_bytes = rows * (2 * nA * 4 + 8)                         # both logit rows in, KL and entropy out
+            vt_bytes = rows * (2 * nA * 4 + 4 + 4) + rows * (4 * 4 + 3 * 4) + B * 4   # ratio pass + scan pass
+            extra["monitor_kl" + tag] = dict(rows=rows, actions=nA, us=round(t_kl * 1e6, 2), gbps=round(kl_bytes / t_kl / 1e9, 1),
+                                             frac_hbm_peak=round(kl_bytes / t_kl / PEAK["hbm"], 4))
+            extra["vtrace" + tag] = dict(T=Tn, B=B, actions=nA, us=round(t_vt * 1e6, 2), gbps=round(vt_bytes / t_vt / 1e9, 1),
+                                         frac_hbm_peak=round(vt_bytes / t_vt / PEAK["hbm"], 4))
 
     # ---- the CPU oracle on a sample of the same states (rank 0, N = 1 only)
     cpu = None

@@ -9,7 +9,7 @@
 namespace accerl {
 
 constexpr int MON_AMAX = 64;        // most actions
-constexpr int MON_PARTS = 1024;     // most workgroups of a reduction pass
+constexpr int MON_PARTS = 2048;     // most workgroups of a reduction pass
 
 // 64 rows of `tab` starting at row r0 -> LDS (row pitch A floats).  The tile starts 256*A bytes into the
 // table, so 16-byte loads are aligned whenever the table is.
@@ -48,16 +48,19 @@ __device__ __forceinline__ double wave_max(double v) {
     return v;
 }
 
-// ---- KL(original || smaller) and entropy of the smaller policy per state; per-workgroup partial sums
-__global__ __launch_bounds__(64) void kl_rows_kernel(const float* __restrict__ lo, const float* __restrict__ ls, int64_t B, int A,
-                                                     float* __restrict__ out_kl, float* __restrict__ out_ent, double* __restrict__ parts) {
+// ---- KL(original || smaller) and entropy of the smaller policy per state; per-workgroup partial sums.
+// Four wavefronts per workgroup, each walking its own tiles with its own LDS region.
+constexpr int MON_WAVES = 4;
+__global__ __launch_bounds__(MON_WAVES * 64) void kl_rows_kernel(const float* __restrict__ lo, const float* __restrict__ ls, int64_t B, int A,
+                                                                 float* __restrict__ out_kl, float* __restrict__ out_ent, double* __restrict__ parts) {
     extern __shared__ __attribute__((aligned(16))) float mon_sm[];
-    float* so = mon_sm;
-    float* ss = mon_sm + 64 * A;
-    const int lane = threadIdx.x;
+    __shared__ double red[MON_WAVES][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float* so = mon_sm + wave * 128 * A;
+    float* ss = so + 64 * A;
     double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0;
     const int64_t n_tiles = (B + 63) >> 6;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (int64_t tile = (int64_t)blockIdx.x * MON_WAVES + wave; tile < n_tiles; tile += (int64_t)gridDim.x * MON_WAVES) {
         const int64_t r0 = tile << 6;
         const int nrows = (int)((B - r0 < 64) ? (B - r0) : 64);
         stage_rows(lo, r0, nrows, A, so, lane);
@@ -88,9 +91,13 @@ __global__ __launch_bounds__(64) void kl_rows_kernel(const float* __restrict__ l
         wave_sync_lds();   // rows are read before the next tile overwrites them
     }
     s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx);
-    if (lane == 0) {
+    if (lane == 0) { red[wave][0] = s_kl; red[wave][1] = s_sq; red[wave][2] = s_mx; red[wave][3] = s_h; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
         double* p = parts + 4 * (int64_t)blockIdx.x;
-        p[0] = s_kl; p[1] = s_sq; p[2] = s_mx; p[3] = s_h;
+        double a0 = red[0][0], a1 = red[0][1], a2 = red[0][2], a3 = red[0][3];
+        for (int w = 1; w < MON_WAVES; ++w) { a0 += red[w][0]; a1 += red[w][1]; a2 = fmax(a2, red[w][2]); a3 += red[w][3]; }
+        p[0] = a0; p[1] = a1; p[2] = a2; p[3] = a3;
     }
 }
 
@@ -112,14 +119,14 @@ __global__ __launch_bounds__(64) void kl_stats_kernel(const double* __restrict__
 }
 
 // ---- importance ratio pi_original(a|x) / pi_smaller(a|x) of the action taken, one row per (t, b)
-__global__ __launch_bounds__(64) void is_ratio_kernel(const float* __restrict__ lo, const float* __restrict__ ls, const int32_t* __restrict__ act,
-                                                      int64_t R, int A, float* __restrict__ ratio) {
+__global__ __launch_bounds__(MON_WAVES * 64) void is_ratio_kernel(const float* __restrict__ lo, const float* __restrict__ ls, const int32_t* __restrict__ act,
+                                                                  int64_t R, int A, float* __restrict__ ratio) {
     extern __shared__ __attribute__((aligned(16))) float mon_sm[];
-    float* so = mon_sm;
-    float* ss = mon_sm + 64 * A;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float* so = mon_sm + wave * 128 * A;
+    float* ss = so + 64 * A;
     const int64_t n_tiles = (R + 63) >> 6;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (int64_t tile = (int64_t)blockIdx.x * MON_WAVES + wave; tile < n_tiles; tile += (int64_t)gridDim.x * MON_WAVES) {
         const int64_t r0 = tile << 6;
         const int nrows = (int)((R - r0 < 64) ? (R - r0) : 64);
         stage_rows(lo, r0, nrows, A, so, lane);
@@ -151,18 +158,33 @@ __global__ __launch_bounds__(256) void vtrace_scan_kernel(const float* __restric
     float v_next = bootstrap[b];      // V(x_{t+1})
     float vs_next = v_next;           // v_{t+1}
     float acc = 0.0f;                 // v_{t+1} - V(x_{t+1})
-    for (int64_t t = T - 1; t >= 0; --t) {
-        const int64_t i = t * B + b;
-        const float ratio = rho[i], r = rewards[i], g = discounts[i], v = values[i];
-        const float rh = fminf(rho_bar, ratio), c = fminf(c_bar, ratio);
-        const float delta = rh * (r + g * v_next - v);
-        acc = delta + g * c * acc;
-        const float vs_t = v + acc;
-        if (pg_adv) pg_adv[i] = rh * (r + g * vs_next - v);
-        vs[i] = vs_t;
-        rho[i] = rh;
-        v_next = v;
-        vs_next = vs_t;
+    // steps are taken eight at a time, newest first: the loads of a group do not depend on the
+    // recurrence and are all in flight together
+    constexpr int CH = 8;
+    for (int64_t t1 = T; t1 > 0; t1 -= CH) {
+        float ra[CH], rw[CH], ga[CH], va[CH];
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int64_t t = t1 - 1 - k;
+            const int64_t i = (t >= 0 ? t : 0) * B + b;
+            ra[k] = rho[i]; rw[k] = rewards[i]; ga[k] = discounts[i]; va[k] = values[i];
+        }
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int64_t t = t1 - 1 - k;
+            if (t < 0) break;
+            const int64_t i = t * B + b;
+            const float ratio = ra[k], r = rw[k], g = ga[k], v = va[k];
+            const float rh = fminf(rho_bar, ratio), c = fminf(c_bar, ratio);
+            const float delta = rh * (r + g * v_next - v);
+            acc = delta + g * c * acc;
+            const float vs_t = v + acc;
+            if (pg_adv) pg_adv[i] = rh * (r + g * vs_next - v);
+            vs[i] = vs_t;
+            rho[i] = rh;
+            v_next = v;
+            vs_next = vs_t;
+        }
     }
 }
 
@@ -205,10 +227,11 @@ extern "C" int accerl_monitor_kl(const float* logits_original, const float* logi
     if (!parts) return set_error(ACCERL_ENOMEM, "monitor: partial-sum buffer");
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t n_tiles = (B + 63) / 64;
-    const int blocks = (int)(n_tiles < MON_PARTS ? n_tiles : MON_PARTS);
-    const size_t lds = (size_t)2 * 64 * A * sizeof(float);
+    const int64_t want = (n_tiles + MON_WAVES - 1) / MON_WAVES;
+    const int blocks = (int)(want < MON_PARTS ? want : MON_PARTS);
+    const size_t lds = (size_t)MON_WAVES * 2 * 64 * A * sizeof(float);
     if (int rc = raise_lds((const void*)kl_rows_kernel, lds)) return rc;
-    kl_rows_kernel<<<dim3(blocks), dim3(64), lds, s>>>(logits_original, logits_smaller, B, A, out_kl, out_entropy, parts);
+    kl_rows_kernel<<<dim3(blocks), dim3(MON_WAVES * 64), lds, s>>>(logits_original, logits_smaller, B, A, out_kl, out_entropy, parts);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail("kl_rows_kernel", e);
     kl_stats_kernel<<<dim3(1), dim3(64), 0, s>>>(parts, blocks, B, out_stats);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail("kl_stats_kernel", e);
@@ -227,10 +250,11 @@ extern "C" int accerl_vtrace(const float* logits_original, const float* logits_s
     if (((uintptr_t)logits_original | (uintptr_t)logits_smaller) & 15) return set_error(ACCERL_EINVAL, "vtrace: logits must be 16-byte aligned");
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t R = T * B, n_tiles = (R + 63) / 64;
-    const int blocks = (int)(n_tiles < 256 * 16 ? n_tiles : 256 * 16);
-    const size_t lds = (size_t)2 * 64 * A * sizeof(float);
+    const int64_t want = (n_tiles + MON_WAVES - 1) / MON_WAVES;
+    const int blocks = (int)(want < 2048 ? want : 2048);
+    const size_t lds = (size_t)MON_WAVES * 2 * 64 * A * sizeof(float);
     if (int rc = raise_lds((const void*)is_ratio_kernel, lds)) return rc;
-    is_ratio_kernel<<<dim3(blocks), dim3(64), lds, s>>>(logits_original, logits_smaller, actions, R, A, out_rho);
+    is_ratio_kernel<<<dim3(blocks), dim3(MON_WAVES * 64), lds, s>>>(logits_original, logits_smaller, actions, R, A, out_rho);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("is_ratio_kernel", e);
     vtrace_scan_kernel<<<dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s>>>(rewards, discounts, values, bootstrap, T, B, rho_bar, c_bar,
