@@ -217,6 +217,20 @@ int accerl_monitor_kl(const float* logits_original, const float* logits_smaller,
                       float* out_kl, float* out_entropy, double* out_stats, void* hip_stream);
 
 /*
+ * Knowledge-distillation loss, forward value only (Section 2.2, Eq. 1): per state
+ *     loss_b = KL(pi_original(.|s_b) || pi_smaller(.|s_b)) + (v_original(s_b) - v_smaller(s_b))^2 / 2
+ *              - beta H(pi_smaller(.|s_b)),
+ * the quantity the Compressor minimises when it transfers the original policy into the smaller
+ * network (its gradient and the optimiser are outside this library).  logits_*: DEVICE fp32 [B, A]
+ * (16-byte aligned, 1 <= A <= 64); value_*: DEVICE fp32 [B]; out_loss: DEVICE fp32 [B] or NULL;
+ * out_mean: DEVICE double[1], the batch mean (fp64 reduction in a fixed order).  Same stream and
+ * overlap rules as accerl_monitor_kl, whose per-device partial-sum buffer it shares.
+ */
+int accerl_distill_loss(const float* logits_original, const float* logits_smaller, const float* value_original,
+                        const float* value_smaller, int64_t B, int A, float beta, float* out_loss, double* out_mean,
+                        void* hip_stream);
+
+/*
  * V-trace corrector (Corrector section, V-trace equation) for B trajectories of T steps collected
  * by the smaller policy and corrected towards the original one.  Time-major tensors, all DEVICE:
  *   logits_original, logits_smaller  fp32 [T, B, A], 16-byte aligned, 1 <= A <= 64

@@ -198,3 +198,15 @@ def vtrace(logits_original, logits_smaller, actions, rewards, discounts, values,
     lib().orc_vtrace(_p(lo), _p(ls), _p(a), _p(r), _p(d), _p(v), _p(bs), C.c_int64(T), C.c_int64(B), A,
                      C.c_double(rho_bar), C.c_double(c_bar), _p(vs), _p(adv), _p(rho))
     return vs, adv, rho
+
+
+def distill_loss(logits_original, logits_smaller, v_original, v_smaller, beta):
+    """Knowledge-distillation loss per state and its batch mean (float64)."""
+    lo, ls = _c(logits_original, np.float32), _c(logits_smaller, np.float32)
+    vo, vs = _c(v_original, np.float32), _c(v_smaller, np.float32)
+    B, A = lo.shape
+    assert ls.shape == (B, A) and vo.shape == (B,) and vs.shape == (B,) and A <= 256
+    loss = np.empty(B, np.float64)
+    mean = np.empty(1, np.float64)
+    lib().orc_distill_loss(_p(lo), _p(ls), _p(vo), _p(vs), C.c_int64(B), A, C.c_double(beta), _p(loss), _p(mean))
+    return loss, float(mean[0])

@@ -373,6 +373,27 @@ void orc_kl_monitor(const float* logits_original, const float* logits_smaller, i
     stats[3] = B > 0 ? hsum / (double)B : 0.0;
 }
 
+/* Section 2.2 Eq. 1, knowledge-distillation loss of one state:
+ * KL(pi_original || pi_smaller) + (v_original - v_smaller)^2 / 2 - beta H(pi_smaller); mean over the batch. */
+void orc_distill_loss(const float* logits_original, const float* logits_smaller, const float* v_original,
+                      const float* v_smaller, int64_t B, int A, double beta, double* loss, double* mean) {
+    double po[256], ps[256];
+    double sum = 0.0;
+    for (int64_t b = 0; b < B; ++b) {
+        orc_logsoftmax_row(logits_original + b * A, A, po);
+        orc_logsoftmax_row(logits_smaller + b * A, A, ps);
+        double k = 0.0, h = 0.0;
+        for (int a = 0; a < A; ++a) {
+            k += exp(po[a]) * (po[a] - ps[a]);
+            h -= exp(ps[a]) * ps[a];
+        }
+        const double dv = (double)v_original[b] - (double)v_smaller[b];
+        loss[b] = k + 0.5 * dv * dv - beta * h;
+        sum += loss[b];
+    }
+    *mean = B > 0 ? sum / (double)B : 0.0;
+}
+
 /* Corrector section, V-trace equation, written out as printed (a sum over the remaining steps
  * of the trajectory, not a recurrence):
  *   rho_t = min(rho_bar, pi_original(a_t|x_t) / pi_smaller(a_t|x_t)),  c_i likewise with c_bar

@@ -58,6 +58,8 @@ def load_library():
     lib.accerl_monitor_kl.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
     lib.accerl_vtrace.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, C.c_float, C.c_float, vp, vp, vp, vp]
     lib.accerl_monitor_kl.restype = C.c_int
+    lib.accerl_distill_loss.argtypes = [vp, vp, vp, vp, i64, i32, C.c_float, vp, vp, vp]
+    lib.accerl_distill_loss.restype = C.c_int
     lib.accerl_vtrace.restype = C.c_int
     lib.accerl_last_error.restype = C.c_char_p
     for f in ("accerl_blob_sizes", "accerl_policy_create", "accerl_actor_forward", "accerl_actor_forward_teacher",
@@ -222,6 +224,17 @@ def accerl_monitor_kl(logits_original, logits_smaller, out_kl, out_entropy, out_
     _check(load_library().accerl_monitor_kl(_ptr(logits_original, torch.float32), _ptr(logits_smaller, torch.float32), B, A,
                                             _ptr(out_kl, torch.float32), _ptr(out_entropy, torch.float32),
                                             _ptr(out_stats, torch.float64), _stream(stream)))
+
+
+def accerl_distill_loss(logits_original, logits_smaller, value_original, value_smaller, beta, out_loss, out_mean, stream=None):
+    import torch
+    B, A = logits_original.shape
+    if tuple(logits_smaller.shape) != (B, A) or tuple(value_original.shape) != (B,) or tuple(value_smaller.shape) != (B,):
+        raise ValueError("shapes differ")
+    _check(load_library().accerl_distill_loss(_ptr(logits_original, torch.float32), _ptr(logits_smaller, torch.float32),
+                                              _ptr(value_original, torch.float32), _ptr(value_smaller, torch.float32), B, A,
+                                              float(beta), _ptr(out_loss, torch.float32), _ptr(out_mean, torch.float64),
+                                              _stream(stream)))
 
 
 def accerl_vtrace(logits_original, logits_smaller, actions, rewards, discounts, values, bootstrap,

@@ -10,6 +10,7 @@ namespace accerl {
 
 constexpr int MON_AMAX = 64;        // most actions
 constexpr int MON_PARTS = 2048;     // most workgroups of a reduction pass
+constexpr int MON_NSTAT = 5;        // partial sums per workgroup: KL, KL^2, max KL, entropy, distillation loss
 
 // 64 rows of `tab` starting at row r0 -> LDS (row pitch A floats).  The tile starts 256*A bytes into the
 // table, so 16-byte loads are aligned whenever the table is.
@@ -52,13 +53,15 @@ __device__ __forceinline__ double wave_max(double v) {
 // Four wavefronts per workgroup, each walking its own tiles with its own LDS region.
 constexpr int MON_WAVES = 4;
 __global__ __launch_bounds__(MON_WAVES * 64) void kl_rows_kernel(const float* __restrict__ lo, const float* __restrict__ ls, int64_t B, int A,
-                                                                 float* __restrict__ out_kl, float* __restrict__ out_ent, double* __restrict__ parts) {
+                                                                 float* __restrict__ out_kl, float* __restrict__ out_ent, double* __restrict__ parts,
+                                                                 const float* __restrict__ v_o, const float* __restrict__ v_s, float beta,
+                                                                 float* __restrict__ out_loss) {
     extern __shared__ __attribute__((aligned(16))) float mon_sm[];
-    __shared__ double red[MON_WAVES][4];
+    __shared__ double red[MON_WAVES][5];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float* so = mon_sm + wave * 128 * A;
     float* ss = so + 64 * A;
-    double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0;
+    double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0, s_loss = 0.0;
     const int64_t n_tiles = (B + 63) >> 6;
     for (int64_t tile = (int64_t)blockIdx.x * MON_WAVES + wave; tile < n_tiles; tile += (int64_t)gridDim.x * MON_WAVES) {
         const int64_t r0 = tile << 6;
@@ -87,34 +90,46 @@ __global__ __launch_bounds__(MON_WAVES * 64) void kl_rows_kernel(const float* __
             s_sq += (double)kl * (double)kl;
             s_mx = fmax(s_mx, (double)kl);
             s_h += (double)h;
+            if (v_o) {   // distillation loss of the state: KL + (v_original - v_smaller)^2 / 2 - beta H
+                const float dv = v_o[r0 + lane] - v_s[r0 + lane];
+                const float loss = kl + 0.5f * (dv * dv) - beta * h;
+                if (out_loss) out_loss[r0 + lane] = loss;
+                s_loss += (double)loss;
+            }
         }
         wave_sync_lds();   // rows are read before the next tile overwrites them
     }
-    s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx);
-    if (lane == 0) { red[wave][0] = s_kl; red[wave][1] = s_sq; red[wave][2] = s_mx; red[wave][3] = s_h; }
+    s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx); s_loss = wave_sum(s_loss);
+    if (lane == 0) { red[wave][0] = s_kl; red[wave][1] = s_sq; red[wave][2] = s_mx; red[wave][3] = s_h; red[wave][4] = s_loss; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double* p = parts + 4 * (int64_t)blockIdx.x;
-        double a0 = red[0][0], a1 = red[0][1], a2 = red[0][2], a3 = red[0][3];
-        for (int w = 1; w < MON_WAVES; ++w) { a0 += red[w][0]; a1 += red[w][1]; a2 = fmax(a2, red[w][2]); a3 += red[w][3]; }
-        p[0] = a0; p[1] = a1; p[2] = a2; p[3] = a3;
+        double* p = parts + MON_NSTAT * (int64_t)blockIdx.x;
+        double a0 = red[0][0], a1 = red[0][1], a2 = red[0][2], a3 = red[0][3], a4 = red[0][4];
+        for (int w = 1; w < MON_WAVES; ++w) { a0 += red[w][0]; a1 += red[w][1]; a2 = fmax(a2, red[w][2]); a3 += red[w][3]; a4 += red[w][4]; }
+        p[0] = a0; p[1] = a1; p[2] = a2; p[3] = a3; p[4] = a4;
     }
 }
 
 // one wavefront folds the partials in a fixed order: stats = {mean, max, population variance, entropy mean}
-__global__ __launch_bounds__(64) void kl_stats_kernel(const double* __restrict__ parts, int n_parts, int64_t B, double* __restrict__ stats) {
+// (monitor) or the mean distillation loss alone (loss_only)
+__global__ __launch_bounds__(64) void kl_stats_kernel(const double* __restrict__ parts, int n_parts, int64_t B, double* __restrict__ stats, int loss_only) {
     const int lane = threadIdx.x;
-    double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0;
+    double s_kl = 0.0, s_sq = 0.0, s_mx = -1.0, s_h = 0.0, s_loss = 0.0;
     for (int i = lane; i < n_parts; i += 64) {
-        s_kl += parts[4 * i]; s_sq += parts[4 * i + 1]; s_mx = fmax(s_mx, parts[4 * i + 2]); s_h += parts[4 * i + 3];
+        const double* p = parts + MON_NSTAT * i;
+        s_kl += p[0]; s_sq += p[1]; s_mx = fmax(s_mx, p[2]); s_h += p[3]; s_loss += p[4];
     }
-    s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx);
+    s_kl = wave_sum(s_kl); s_sq = wave_sum(s_sq); s_h = wave_sum(s_h); s_mx = wave_max(s_mx); s_loss = wave_sum(s_loss);
     if (lane == 0) {
         const double n = (double)B, mean = s_kl / n;
-        stats[0] = mean;
-        stats[1] = s_mx;
-        stats[2] = fmax(s_sq / n - mean * mean, 0.0);
-        stats[3] = s_h / n;
+        if (loss_only) {
+            stats[0] = s_loss / n;
+        } else {
+            stats[0] = mean;
+            stats[1] = s_mx;
+            stats[2] = fmax(s_sq / n - mean * mean, 0.0);
+            stats[3] = s_h / n;
+        }
     }
 }
 
@@ -191,7 +206,7 @@ __global__ __launch_bounds__(256) void vtrace_scan_kernel(const float* __restric
 static double* mon_parts(int dev) {
     static double* parts[64] = {nullptr};
     if (dev < 0 || dev >= 64) return nullptr;
-    if (!parts[dev] && hipMalloc((void**)&parts[dev], (size_t)MON_PARTS * 4 * sizeof(double)) != hipSuccess) {
+    if (!parts[dev] && hipMalloc((void**)&parts[dev], (size_t)MON_PARTS * MON_NSTAT * sizeof(double)) != hipSuccess) {
         (void)hipGetLastError();
         parts[dev] = nullptr;
     }
@@ -214,28 +229,45 @@ static int raise_lds(const void* fn, size_t lds) {
 
 using namespace accerl;
 
-extern "C" int accerl_monitor_kl(const float* logits_original, const float* logits_smaller, int64_t B, int A,
-                                 float* out_kl, float* out_entropy, double* out_stats, void* hip_stream) {
-    if (B < 0 || A < 1 || A > MON_AMAX) return set_error(ACCERL_EINVAL, "monitor: need B >= 0 and 1 <= A <= 64");
+static int run_kl(const char* who, const float* logits_original, const float* logits_smaller, const float* v_o, const float* v_s,
+                  float beta, int64_t B, int A, float* out_kl, float* out_entropy, float* out_loss, double* out_stats,
+                  int loss_only, void* hip_stream) {
+    char msg[160];
+    if (B < 0 || A < 1 || A > MON_AMAX) { snprintf(msg, sizeof msg, "%s: need B >= 0 and 1 <= A <= 64", who); return set_error(ACCERL_EINVAL, msg); }
     if (B == 0) return ACCERL_OK;
-    if (!logits_original || !logits_smaller || !out_stats) return set_error(ACCERL_EINVAL, "monitor: NULL logits or stats pointer");
-    if (((uintptr_t)logits_original | (uintptr_t)logits_smaller) & 15) return set_error(ACCERL_EINVAL, "monitor: logits must be 16-byte aligned");
+    if (!logits_original || !logits_smaller || !out_stats || (loss_only && (!v_o || !v_s))) {
+        snprintf(msg, sizeof msg, "%s: NULL input or result pointer", who);
+        return set_error(ACCERL_EINVAL, msg);
+    }
+    if (((uintptr_t)logits_original | (uintptr_t)logits_smaller) & 15) { snprintf(msg, sizeof msg, "%s: logits must be 16-byte aligned", who); return set_error(ACCERL_EINVAL, msg); }
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail("hipGetDevice", e);
     double* parts = mon_parts(dev);
-    if (!parts) return set_error(ACCERL_ENOMEM, "monitor: partial-sum buffer");
+    if (!parts) return set_error(ACCERL_ENOMEM, "partial-sum buffer");
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t n_tiles = (B + 63) / 64;
     const int64_t want = (n_tiles + MON_WAVES - 1) / MON_WAVES;
     const int blocks = (int)(want < MON_PARTS ? want : MON_PARTS);
     const size_t lds = (size_t)MON_WAVES * 2 * 64 * A * sizeof(float);
     if (int rc = raise_lds((const void*)kl_rows_kernel, lds)) return rc;
-    kl_rows_kernel<<<dim3(blocks), dim3(MON_WAVES * 64), lds, s>>>(logits_original, logits_smaller, B, A, out_kl, out_entropy, parts);
+    kl_rows_kernel<<<dim3(blocks), dim3(MON_WAVES * 64), lds, s>>>(logits_original, logits_smaller, B, A, out_kl, out_entropy, parts,
+                                                                  v_o, v_s, beta, out_loss);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail("kl_rows_kernel", e);
-    kl_stats_kernel<<<dim3(1), dim3(64), 0, s>>>(parts, blocks, B, out_stats);
+    kl_stats_kernel<<<dim3(1), dim3(64), 0, s>>>(parts, blocks, B, out_stats, loss_only);
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail("kl_stats_kernel", e);
     return ACCERL_OK;
+}
+
+extern "C" int accerl_monitor_kl(const float* logits_original, const float* logits_smaller, int64_t B, int A,
+                                 float* out_kl, float* out_entropy, double* out_stats, void* hip_stream) {
+    return run_kl("monitor", logits_original, logits_smaller, nullptr, nullptr, 0.0f, B, A, out_kl, out_entropy, nullptr, out_stats, 0, hip_stream);
+}
+
+extern "C" int accerl_distill_loss(const float* logits_original, const float* logits_smaller, const float* value_original,
+                                   const float* value_smaller, int64_t B, int A, float beta, float* out_loss, double* out_mean,
+                                   void* hip_stream) {
+    return run_kl("distill", logits_original, logits_smaller, value_original, value_smaller, beta, B, A, nullptr, nullptr, out_loss, out_mean, 1, hip_stream);
 }
 
 extern "C" int accerl_vtrace(const float* logits_original, const float* logits_smaller, const int32_t* actions,

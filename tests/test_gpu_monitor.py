@@ -108,3 +108,21 @@ def test_vtrace_on_policy_returns(A):
         nxt = tr["rewards"][t] + tr["discounts"][t].astype(np.float64) * nxt
         want[t] = nxt
     assert np.allclose(vs.cpu().numpy(), want, rtol=1e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("B,nA,beta", [(1, 2, 0.0), (4096 + 5, 18, 0.01), (700, 64, 1.0)])
+def test_distill_loss_matches_oracle(A, B, nA, beta):
+    lo, ls = wl.make_logits_pair(B, nA, gap=0.5)
+    vo = wl.normal(wl.BASE_SEED, 77, 0, B)
+    vs = wl.normal(wl.BASE_SEED, 78, 0, B)
+    loss_o, mean_o = L.distill_loss(lo, ls, vo, vs, beta)
+    loss = torch.empty(B, dtype=torch.float32, device="cuda")
+    mean = torch.zeros(1, dtype=torch.float64, device="cuda")
+    A.accerl_distill_loss(_dev(lo), _dev(ls), _dev(vo), _dev(vs), beta, loss, mean)
+    torch.cuda.synchronize()
+    assert np.allclose(loss.cpu().numpy(), loss_o, rtol=1e-4, atol=1e-5)
+    assert np.isclose(float(mean[0]), mean_o, rtol=1e-4, atol=1e-6)
+    mean2 = torch.zeros(1, dtype=torch.float64, device="cuda")
+    A.accerl_distill_loss(_dev(lo), _dev(ls), _dev(vo), _dev(vs), beta, None, mean2)
+    torch.cuda.synchronize()
+    assert float(mean2[0]) == float(mean[0])

@@ -155,3 +155,31 @@ def test_vtrace_episode_end_cuts_the_trace():
     vs2, _, _ = L.vtrace(**tr2)
     assert np.array_equal(vs[:5], vs2[:5])
     assert not np.allclose(vs[5:], vs2[5:])
+
+
+# ------------------------------------------------------------------ distillation loss (Section 2.2 Eq. 1)
+def test_distill_loss_terms():
+    B, A = 50, 6
+    lo, ls = wl.make_logits_pair(B, A, gap=0.6)
+    vo = wl.normal(wl.BASE_SEED, 77, 0, B)
+    vs = wl.normal(wl.BASE_SEED, 78, 0, B)
+    po, ps = _softmax64(lo), _softmax64(ls)
+    kl = sps.rel_entr(po, ps).sum(axis=1)
+    H = sst.entropy(ps, axis=1)
+    for beta in (0.0, 0.01, 1.0):
+        loss, mean = L.distill_loss(lo, ls, vo, vs, beta)
+        want = kl + 0.5 * (vo.astype(np.float64) - vs) ** 2 - beta * H
+        assert np.allclose(loss, want, rtol=1e-10, atol=1e-13)
+        assert np.isclose(mean, want.mean(), rtol=1e-12)
+    # identical networks: only the entropy bonus is left; the sign of each term is pinned by a one-term change
+    loss, _ = L.distill_loss(lo, lo, vo, vo, 0.5)
+    assert np.allclose(loss, -0.5 * sst.entropy(po, axis=1), rtol=1e-10)
+    l0, _ = L.distill_loss(lo, ls, vo, vo, 0.0)
+    l1, _ = L.distill_loss(lo, ls, vo, vo + np.float32(2.0), 0.0)
+    assert np.allclose(l1 - l0, 2.0, rtol=1e-6)              # (2)^2 / 2
+    # two actions, by hand: p = (.5,.5), q = (.8,.2), dv = 1, beta = .1
+    lo2 = np.log(np.array([[0.5, 0.5]], np.float32)); ls2 = np.log(np.array([[0.8, 0.2]], np.float32))
+    loss, _ = L.distill_loss(lo2, ls2, np.array([1.0], np.float32), np.array([0.0], np.float32), 0.1)
+    klh = 0.5 * np.log(0.5 / 0.8) + 0.5 * np.log(0.5 / 0.2)
+    hh = -(0.8 * np.log(0.8) + 0.2 * np.log(0.2))
+    assert np.isclose(loss[0], klh + 0.5 - 0.1 * hh, rtol=1e-6)
