@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="only the headline workload")
+    ap.add_argument("--paper-nets", action="store_true",
+                    help="also time the paper's own networks (network table: Original with FC 2048, Net1-Net3)")
     ap.add_argument("--copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference for HBM counters)")
     args = ap.parse_args()
@@ -243,6 +245,26 @@ def main():
                                              frac_hbm_peak=round(kl_bytes / t_kl / PEAK["hbm"], 4))
             extra["vtrace" + tag] = dict(T=Tn, B=B, actions=nA, us=round(t_vt * 1e6, 2), gbps=round(vt_bytes / t_vt / 1e9, 1),
                                          frac_hbm_peak=round(vt_bytes / t_vt / PEAK["hbm"], 4))
+
+    if args.paper_nets:
+        # the networks of the paper's table (Section 3.1), each as int8 and bf16, at the paper's batch of 160
+        # and at the benchmark batch; weights seeded, int8 scales calibrated on 64 seeded states
+        table = {}
+        nets = [("original_fc2048", wl.nature_cnn("original_fc2048", fc=2048))] + list(wl.configs.PAPER_STUDENTS.items())
+        for name, net in nets:
+            params = wl.init_params(net, wl.STREAM["weights_student"])
+            qt, qs = compressor.quantize_policy(net, params, states(net, 64, wl.STREAM["calibration"]))
+            pols = dict(int8=A.Policy(net, "int8", qt, qs), bf16=A.Policy(net, "bf16", compressor.teacher_tensors(params)))
+            row = {}
+            for bb in (160, B):
+                xb, ub = x[:bb].contiguous(), u[:bb].contiguous()
+                for prec, pol in pols.items():
+                    t = time_forward(pol, xb, ub, pol.alloc_outputs(bb), 100, 10)
+                    row[f"{prec}_B{bb}_us"] = round(t * 1e6, 2)
+            for pol in pols.values():
+                pol.close()
+            table[name] = row
+        extra["paper_nets"] = table
 
     # ---- the CPU oracle on a sample of the same states (rank 0, N = 1 only)
     cpu = None

@@ -200,6 +200,26 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
                          const float* quant_scales, int64_t n_scales, char* text, int64_t cap);
 
 /*
+ * Policy mixture (Section 3.2, "Knowledge Distillation Results"): the actor sends a state through the
+ * smaller network with probability alpha and through the original one otherwise.  The draw is the
+ * caller's (use_smaller: HOST uint8 [B], non-zero = smaller network, read during the call); the
+ * library compacts the rows of each subset, runs `smaller` on the first and `original` on the second
+ * (any two non-recurrent policies: int8, fp32 or bf16) and writes every row's results to its place in the
+ * outputs, so each row holds exactly what the chosen network alone would have produced for it.
+ * Both policies must share observation shape and number of actions and be non-recurrent.  states,
+ * uniforms and the outputs are DEVICE as in accerl_actor_forward.  Asynchronous on hip_stream; the
+ * compaction buffers belong to `smaller` and grow on demand (a stream synchronisation when they do),
+ * so calls that share `smaller` must not overlap.  Errors as accerl_actor_forward.
+ */
+int accerl_actor_forward_mixture(accerl_policy* smaller, accerl_policy* original, const void* states, int64_t B,
+                                 const float* uniforms, const uint8_t* use_smaller,
+                                 float* out_logits, float* out_value, int32_t* out_action, void* hip_stream);
+
+/* Host-only: the mixture probability as a function of the Monitor's KL-mean indicator (same passage):
+ * 1 up to kl_lo, 0 from kl_hi on, linear in between (the paper prints no constants). */
+double accerl_mixture_alpha(double kl_mean, double kl_lo, double kl_hi);
+
+/*
  * Monitor indicators (Monitor section, KL equation): for B states on which both the original and
  * the smaller (compressed) policy were evaluated,
  *     KL_b = sum_a pi_original(a|x_b) log(pi_original(a|x_b) / pi_smaller(a|x_b)),

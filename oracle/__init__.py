@@ -8,5 +8,5 @@ channel pruner that produce a student policy from fp32 weights.
 """
 from .clib import build, lib  # noqa: F401
 from . import layers  # noqa: F401
-from .forward import forward_float, forward_int8  # noqa: F401
+from .forward import forward_float, forward_int8, forward_mixture  # noqa: F401
 from .ptq import quantize_policy, prune_policy, QuantPolicy, derived_constants  # noqa: F401

@@ -153,3 +153,22 @@ def forward_int8(net, qp, states, uniforms=None, h=None, c=None, done=None, taps
         out = L.dequant(acc, hd["d"])
     logits, value, action = _heads_out(net, out, uniforms)
     return dict(logits=logits, value=value, action=action, h=h, c=c)
+
+
+def forward_mixture(net_small, qp_small, net_orig, params_orig, precision_orig, states, uniforms, use_smaller):
+    """alpha-mixture of Section 3.2 ("Knowledge Distillation Results"): row b goes through the int8 smaller
+    network where use_smaller[b] is set, else through the original network; rows are independent, so the
+    result is each network's own output on its rows."""
+    use = np.asarray(use_smaller).astype(bool)
+    B = len(use)
+    A = net_small.n_actions
+    out = dict(logits=np.zeros((B, A), np.float32), value=np.zeros(B, np.float32), action=np.zeros(B, np.int32))
+    if use.any():
+        r = forward_int8(net_small, qp_small, states[use], uniforms[use])
+        for k in out:
+            out[k][use] = r[k]
+    if (~use).any():
+        r = forward_float(net_orig, params_orig, states[~use], uniforms[~use], precision_orig)
+        for k in out:
+            out[k][~use] = r[k]
+    return out

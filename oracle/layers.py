@@ -210,3 +210,9 @@ def distill_loss(logits_original, logits_smaller, v_original, v_smaller, beta):
     mean = np.empty(1, np.float64)
     lib().orc_distill_loss(_p(lo), _p(ls), _p(vo), _p(vs), C.c_int64(B), A, C.c_double(beta), _p(loss), _p(mean))
     return loss, float(mean[0])
+
+
+def mixture_alpha(kl_mean, kl_lo, kl_hi):
+    f = lib().orc_mixture_alpha
+    f.restype = C.c_double
+    return float(f(C.c_double(kl_mean), C.c_double(kl_lo), C.c_double(kl_hi)))

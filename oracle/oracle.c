@@ -441,3 +441,13 @@ void orc_vtrace(const float* logits_original, const float* logits_smaller, const
         }
     }
 }
+
+/* Section 3.2, "Knowledge Distillation Results": the actor uses the smaller network with probability
+ * alpha and the original one with 1 - alpha, and alpha falls linearly as the KL-mean indicator
+ * grows.  The paper prints no constants: alpha = 1 at kl_mean <= kl_lo, 0 at kl_mean >= kl_hi,
+ * linear in between (kl_lo < kl_hi chosen by the user's strategy). */
+double orc_mixture_alpha(double kl_mean, double kl_lo, double kl_hi) {
+    if (kl_mean <= kl_lo) return 1.0;
+    if (kl_mean >= kl_hi) return 0.0;
+    return (kl_hi - kl_mean) / (kl_hi - kl_lo);
+}

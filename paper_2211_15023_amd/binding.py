@@ -58,6 +58,10 @@ def load_library():
     lib.accerl_monitor_kl.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
     lib.accerl_vtrace.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, C.c_float, C.c_float, vp, vp, vp, vp]
     lib.accerl_monitor_kl.restype = C.c_int
+    lib.accerl_actor_forward_mixture.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.accerl_actor_forward_mixture.restype = C.c_int
+    lib.accerl_mixture_alpha.argtypes = [C.c_double, C.c_double, C.c_double]
+    lib.accerl_mixture_alpha.restype = C.c_double
     lib.accerl_distill_loss.argtypes = [vp, vp, vp, vp, i64, i32, C.c_float, vp, vp, vp]
     lib.accerl_distill_loss.restype = C.c_int
     lib.accerl_vtrace.restype = C.c_int
@@ -213,6 +217,24 @@ def accerl_actor_forward_debug(handle, states, layer, tap, out, stream=None):
     B = states.shape[0]
     _check(load_library().accerl_actor_forward_debug(handle, _ptr(states), B, int(layer), int(tap), _ptr(out),
                                                      out.numel() * out.element_size(), _stream(stream)))
+
+
+def accerl_actor_forward_mixture(smaller, original, states, uniforms, use_smaller, out_logits, out_value, out_action, stream=None):
+    """use_smaller: host uint8 array [B] (numpy); the other tensors live on the device."""
+    import numpy as np
+    import torch
+    B = states.shape[0]
+    flags = np.ascontiguousarray(use_smaller, dtype=np.uint8)
+    if flags.shape != (B,):
+        raise ValueError("use_smaller must be a host array of B flags")
+    _check(load_library().accerl_actor_forward_mixture(smaller, original, _ptr(states), B, _ptr(uniforms, torch.float32),
+                                                       flags.ctypes.data_as(C.c_void_p), _ptr(out_logits, torch.float32),
+                                                       _ptr(out_value, torch.float32), _ptr(out_action, torch.int32),
+                                                       _stream(stream)))
+
+
+def accerl_mixture_alpha(kl_mean, kl_lo, kl_hi):
+    return float(load_library().accerl_mixture_alpha(kl_mean, kl_lo, kl_hi))
 
 
 def accerl_monitor_kl(logits_original, logits_smaller, out_kl, out_entropy, out_stats, stream=None):

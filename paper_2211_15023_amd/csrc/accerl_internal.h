@@ -107,6 +107,12 @@ constexpr int CONV_WP_NWAVES = 8;
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,
                           int k, int s, int pad, Elem el, hipStream_t stream);
 
+// ---------------------------------------------------------------- row gather / scatter (policy mixture)
+hipError_t launch_gather_rows(const void* in, const int32_t* idx, int64_t n, int64_t row_bytes, void* out, hipStream_t s);
+hipError_t launch_gather_f32(const float* in, const int32_t* idx, int64_t n, float* out, hipStream_t s);
+hipError_t launch_scatter_out(const float* logits, const float* value, const int32_t* action, const int32_t* idx, int64_t n, int A,
+                              float* out_logits, float* out_value, int32_t* out_action, hipStream_t s);
+
 // ---------------------------------------------------------------- dense layers (MFMA GEMM)
 enum GemmEpi : int { EPI_REQUANT = 0, EPI_HEADS_I8 = 1, EPI_BF16 = 2, EPI_HEADS_F32ACC = 3, EPI_LSTM = 4 };
 struct GemmParams {

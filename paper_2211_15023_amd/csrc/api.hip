@@ -203,6 +203,14 @@ struct accerl_policy {
     int64_t obs_bytes = 0;
     bool recurrent = false;
     int lstm_hidden = 0;
+    // policy mixture (owned by the smaller policy of a pair): compacted inputs and results of both subsets,
+    // and a ring of pinned host buffers for the row lists
+    char* mix_dev = nullptr;
+    int64_t mix_rows = 0;
+    int32_t* mix_pin[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t mix_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int64_t mix_pin_rows = 0;
+    int mix_slot = 0;
     // measurement aid: event pairs around every launch while profiling is on
     bool profiling = false;
     struct Ev { int step; hipEvent_t a, b; };
@@ -1237,6 +1245,11 @@ void accerl_policy_destroy(accerl_policy* p) {
     for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
     if (p->ws) (void)hipFree(p->ws);
     if (p->consts) (void)hipFree(p->consts);
+    if (p->mix_dev) (void)hipFree(p->mix_dev);
+    for (int i = 0; i < 4; ++i) {
+        if (p->mix_pin[i]) (void)hipHostFree(p->mix_pin[i]);
+        if (p->mix_ev[i]) (void)hipEventDestroy(p->mix_ev[i]);
+    }
     delete p;
 }
 
@@ -1259,6 +1272,91 @@ int accerl_actor_forward(accerl_policy* p, const void* states, int64_t B, const 
 int accerl_actor_forward_teacher(accerl_policy* p, const void* states, int64_t B, const float* uniforms,
                                  float* out_logits, float* out_value, int32_t* out_action, void* stream) {
     return forward_impl(p, false, states, B, uniforms, out_logits, out_value, out_action, stream);
+}
+
+double accerl_mixture_alpha(double kl_mean, double kl_lo, double kl_hi) {
+    if (kl_mean <= kl_lo) return 1.0;
+    if (kl_mean >= kl_hi) return 0.0;
+    return (kl_hi - kl_mean) / (kl_hi - kl_lo);
+}
+
+int accerl_actor_forward_mixture(accerl_policy* smaller, accerl_policy* original, const void* states, int64_t B,
+                                 const float* uniforms, const uint8_t* use_smaller,
+                                 float* out_logits, float* out_value, int32_t* out_action, void* stream) {
+    int rc = check_common(smaller, states, B, true, uniforms, out_logits, out_value, out_action);
+    if (rc) return rc;
+    rc = check_common(original, states, B, true, uniforms, out_logits, out_value, out_action);
+    if (rc) return rc;
+    if (smaller->recurrent || original->recurrent) return fail(ACCERL_EUNSUPPORTED, "mixture of recurrent policies");
+    const accerl_arch &as = smaller->arch, &ao = original->arch;
+    if (as.obs_dtype != ao.obs_dtype || as.obs_c != ao.obs_c || as.obs_h != ao.obs_h || as.obs_w != ao.obs_w || as.n_actions != ao.n_actions)
+        return fail(ACCERL_EINVAL, "the two policies differ in observation shape or number of actions");
+    if (B == 0) return ACCERL_OK;
+    if (!use_smaller) return fail(ACCERL_EINVAL, "use_smaller is NULL");
+    if (B > 0x7fffffff) return fail(ACCERL_EINVAL, "batch too large for 32-bit row lists");
+    hipStream_t st = (hipStream_t)stream;
+    int64_t ns = 0;
+    for (int64_t b = 0; b < B; ++b) ns += use_smaller[b] ? 1 : 0;
+    const int64_t no = B - ns;
+    if (no == 0 || ns == 0) {     // one network takes every row: no compaction needed
+        Call c{states, B, uniforms, nullptr, nullptr, nullptr, out_logits, out_value, out_action, st};
+        return run(ns ? smaller : original, c);
+    }
+    accerl_policy* m = smaller;
+    const int A = as.n_actions;
+    const int64_t obs = smaller->obs_bytes;
+    if (obs % 16) return fail(ACCERL_EUNSUPPORTED, "mixture needs observation rows that are a multiple of 16 bytes");
+    // ---- row lists through a pinned slot (the copy is asynchronous; a slot is reused only after its copy has finished)
+    if (m->mix_pin_rows < B) {
+        HIP_TRY(hipStreamSynchronize(st));
+        for (int i = 0; i < 4; ++i) {
+            if (m->mix_pin[i]) { HIP_TRY(hipHostFree(m->mix_pin[i])); m->mix_pin[i] = nullptr; }
+            HIP_TRY(hipHostMalloc((void**)&m->mix_pin[i], (size_t)B * sizeof(int32_t), hipHostMallocDefault));
+            if (!m->mix_ev[i]) HIP_TRY(hipEventCreateWithFlags(&m->mix_ev[i], hipEventDisableTiming));
+        }
+        m->mix_pin_rows = B;
+    }
+    auto rup = [](int64_t v) { return (v + 255) / 256 * 256; };
+    const int64_t per_row = obs + 4 + 4 * (int64_t)A + 4 + 4;
+    if (m->mix_rows < B) {
+        HIP_TRY(hipStreamSynchronize(st));
+        if (m->mix_dev) { HIP_TRY(hipFree(m->mix_dev)); m->mix_dev = nullptr; m->mix_rows = 0; }
+        hipError_t e = hipMalloc((void**)&m->mix_dev, (size_t)(rup((B + 4) * 4) + rup((B + 4) * obs) + 4 * rup((B + 4) * 4 * (int64_t)(A > 1 ? A : 1)) + 4096));
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(ACCERL_ENOMEM, "mixture workspace of %lld rows x %lld bytes", (long long)B, (long long)per_row); }
+        m->mix_rows = B;
+    }
+    const int slot = m->mix_slot;
+    m->mix_slot = (slot + 1) & 3;
+    HIP_TRY(hipEventSynchronize(m->mix_ev[slot]));
+    int32_t* pin = m->mix_pin[slot];
+    {   // rows of the smaller policy first, then the original's, each in increasing order
+        int64_t is = 0, io = ns;
+        for (int64_t b = 0; b < B; ++b) { if (use_smaller[b]) pin[is++] = (int32_t)b; else pin[io++] = (int32_t)b; }
+    }
+    const int64_t cap = m->mix_rows + 4;         // the second subset starts at a row count rounded up to 4
+    char* d = m->mix_dev;
+    int32_t* d_idx = (int32_t*)d;               d += rup(cap * 4);
+    char* d_states = d;                          d += rup(cap * obs);
+    float* d_uni = (float*)d;                    d += rup(cap * 4);
+    float* d_logits = (float*)d;                 d += rup(cap * 4 * (int64_t)A);
+    float* d_value = (float*)d;                  d += rup(cap * 4);
+    int32_t* d_action = (int32_t*)d;
+    const int64_t o2 = (ns + 3) & ~(int64_t)3;   // keeps every buffer of the second subset 16-byte aligned
+    HIP_TRY(hipMemcpyAsync(d_idx, pin, (size_t)B * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(m->mix_ev[slot], st));
+    HIP_TRY(launch_gather_rows(states, d_idx, ns, obs, d_states, st));
+    HIP_TRY(launch_gather_rows(states, d_idx + ns, no, obs, d_states + o2 * obs, st));
+    HIP_TRY(launch_gather_f32(uniforms, d_idx, ns, d_uni, st));
+    HIP_TRY(launch_gather_f32(uniforms, d_idx + ns, no, d_uni + o2, st));
+    Call cs{d_states, ns, d_uni, nullptr, nullptr, nullptr, d_logits, d_value, d_action, st};
+    rc = run(smaller, cs);
+    if (rc) return rc;
+    Call co{d_states + o2 * obs, no, d_uni + o2, nullptr, nullptr, nullptr, d_logits + o2 * A, d_value + o2, d_action + o2, st};
+    rc = run(original, co);
+    if (rc) return rc;
+    HIP_TRY(launch_scatter_out(d_logits, d_value, d_action, d_idx, ns, A, out_logits, out_value, out_action, st));
+    HIP_TRY(launch_scatter_out(d_logits + o2 * A, d_value + o2, d_action + o2, d_idx + ns, no, A, out_logits, out_value, out_action, st));
+    return ACCERL_OK;
 }
 
 int accerl_actor_forward_recurrent(accerl_policy* p, const void* states, int64_t B, const float* uniforms,

@@ -293,6 +293,52 @@ hipError_t launch_lstm_pack(const LstmPackParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ row gather / scatter (policy mixture)
+// out row i = in row idx[i]; rows are row_bytes long (a multiple of 16), one workgroup per row
+__global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ in, const int32_t* __restrict__ idx,
+                                                          int row_units, char* __restrict__ out) {
+    const int64_t i = blockIdx.x;
+    const v4i* src = (const v4i*)(in + (int64_t)idx[i] * row_units * 16);
+    v4i* dst = (v4i*)(out + i * row_units * 16);
+    for (int u = threadIdx.x; u < row_units; u += 256) dst[u] = src[u];
+}
+
+// uniforms of the chosen rows (in: [B], out: [n])
+__global__ __launch_bounds__(256) void gather_f32_kernel(const float* __restrict__ in, const int32_t* __restrict__ idx, int64_t n, float* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = in[idx[i]];
+}
+
+// results of a compacted forward back to their rows
+__global__ __launch_bounds__(256) void scatter_out_kernel(const float* __restrict__ logits, const float* __restrict__ value, const int32_t* __restrict__ action,
+                                                          const int32_t* __restrict__ idx, int64_t n, int A,
+                                                          float* __restrict__ out_logits, float* __restrict__ out_value, int32_t* __restrict__ out_action) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int64_t r = idx[i];
+    if (out_logits) for (int a = 0; a < A; ++a) out_logits[r * A + a] = logits[i * A + a];
+    if (out_value) out_value[r] = value[i];
+    if (out_action) out_action[r] = action[i];
+}
+
+hipError_t launch_gather_rows(const void* in, const int32_t* idx, int64_t n, int64_t row_bytes, void* out, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    if (row_bytes % 16) return hipErrorInvalidValue;
+    gather_rows_kernel<<<dim3((unsigned)n), dim3(256), 0, s>>>((const char*)in, idx, (int)(row_bytes / 16), (char*)out);
+    return hipGetLastError();
+}
+hipError_t launch_gather_f32(const float* in, const int32_t* idx, int64_t n, float* out, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    gather_f32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(in, idx, n, out);
+    return hipGetLastError();
+}
+hipError_t launch_scatter_out(const float* logits, const float* value, const int32_t* action, const int32_t* idx, int64_t n, int A,
+                              float* out_logits, float* out_value, int32_t* out_action, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    scatter_out_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(logits, value, action, idx, n, A, out_logits, out_value, out_action);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ debug conversion
 __global__ __launch_bounds__(256) void bf16_to_f32_kernel(const uint16_t* __restrict__ in, float* __restrict__ out, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

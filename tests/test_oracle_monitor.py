@@ -183,3 +183,13 @@ def test_distill_loss_terms():
     klh = 0.5 * np.log(0.5 / 0.8) + 0.5 * np.log(0.5 / 0.2)
     hh = -(0.8 * np.log(0.8) + 0.2 * np.log(0.2))
     assert np.isclose(loss[0], klh + 0.5 - 0.1 * hh, rtol=1e-6)
+
+
+# ------------------------------------------------------------------ alpha mixture (Section 3.2)
+def test_mixture_alpha_schedule():
+    assert L.mixture_alpha(0.0, 0.1, 0.5) == 1.0 and L.mixture_alpha(0.1, 0.1, 0.5) == 1.0
+    assert L.mixture_alpha(0.5, 0.1, 0.5) == 0.0 and L.mixture_alpha(9.0, 0.1, 0.5) == 0.0
+    assert np.isclose(L.mixture_alpha(0.3, 0.1, 0.5), 0.5)
+    ks = np.linspace(0.1, 0.5, 9)
+    al = np.array([L.mixture_alpha(k, 0.1, 0.5) for k in ks])
+    assert np.all(np.diff(al) < 0) and np.allclose(np.diff(al), np.diff(al)[0])    # decreasing, linear
