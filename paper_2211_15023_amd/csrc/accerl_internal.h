@@ -103,6 +103,10 @@ constexpr int CONV_LDS_CONST = 512;   // LDS bytes for bias and multipliers in t
 bool conv_wp_available(Elem el, int NT, int RD, int PT, int units);
 constexpr int CONV_WP_NWAVES = 8;
 
+// first two int8 convolutions of an image policy in one kernel (the first layer's output stays in LDS)
+bool conv_fused_supported(const ConvParams& a, int NTA, int KSA, int RDA, const ConvParams& b, int NTB, int KSB, int RDB);
+hipError_t launch_conv_fused(const ConvParams& a, int NTA, const ConvParams& b, hipStream_t s);
+
 // ---------------------------------------------------------------- max pooling on NHWC
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,
                           int k, int s, int pad, Elem el, hipStream_t stream);

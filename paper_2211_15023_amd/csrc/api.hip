@@ -162,6 +162,8 @@ struct Step {
     int in_buf = -1, out_buf = -1, res_buf = -1;   // -1 = the caller's states (in) / none
     int pool_buf = -1;          // conv: output of the max-pool fused into it (-1 = none)
     bool fused = false;         // maxpool: normally done by the conv step before it
+    bool fuse_next = false;     // conv: normally runs together with the conv step after it (its output stays on chip)
+    bool fused_prev = false;    // conv: normally done by the conv step before it
     ConvParams cp{};
     Elem el = EL_I8;
     int NT = 1, KS = 0, RD = 16, PF = 16;
@@ -949,6 +951,7 @@ int run(accerl_policy* p, const Call& c) {
         char* tap_out = c.debug ? (char*)c.out + c0 * tap_elems * tap_esz : nullptr;
         auto bufp = [&](int b) -> char* { return b < 0 ? const_cast<char*>(states) : p->ws + p->bufs[b].off; };
         bool pooled = false;   // the last conv step also did the max-pool that follows it
+        bool conv_pair_done = false;   // the last conv step also did the conv that follows it
         for (int si = 0; si <= last_step; ++si) {
             const Step& s = p->steps[si];
             const bool tap_here = c.debug && !fused && si == last_step;
@@ -979,6 +982,20 @@ int run(accerl_policy* p, const Call& c) {
                     e = launch_quant_obs((const float*)states, n, s.D, s.Dpad, s.inv_s0, (int8_t*)bufp(s.out_buf), c.stream);
                     break;
                 case ST_CONV: {
+                    if (s.fused_prev && conv_pair_done) { conv_pair_done = false; break; }   // done by the step before
+                    if (s.fuse_next && !c.debug) {
+                        const Step& nx = p->steps[si + 1];
+                        ConvParams ca = s.cp, cb = nx.cp;
+                        ca.in = bufp(s.in_buf); ca.out = nullptr; ca.res = nullptr; ca.tap_acc = nullptr;
+                        ca.wfrag = p->consts + s.o_w; ca.bias = p->consts + s.o_bias; ca.mult = (const float*)(p->consts + s.o_mult);
+                        ca.B = n;
+                        cb.in = nullptr; cb.out = bufp(nx.out_buf); cb.res = nullptr; cb.tap_acc = nullptr;
+                        cb.wfrag = p->consts + nx.o_w; cb.bias = p->consts + nx.o_bias; cb.mult = (const float*)(p->consts + nx.o_mult);
+                        cb.B = n;
+                        e = launch_conv_fused(ca, s.NT, cb, c.stream);
+                        conv_pair_done = true;
+                        break;
+                    }
                     ConvParams cp = s.cp;
                     cp.in = bufp(s.in_buf); cp.out = bufp(s.out_buf);
                     cp.res = s.res_buf >= 0 ? bufp(s.res_buf) : nullptr;
@@ -1113,6 +1130,8 @@ static void assign_slots(accerl_policy* pol, int layout) {
         if (layout == 0 && st.kind == ST_CONV && st.pool_buf >= 0) touched[2] = st.pool_buf;   // writes the pooled image only
         if (layout == 1 && st.kind == ST_CONV) touched[3] = st.pool_buf;                       // may run either way
         if (layout == 0 && st.kind == ST_MAXPOOL && st.fused) continue;                         // never launched
+        if (layout == 0 && st.kind == ST_CONV && st.fused_prev) continue;                       // done by the step before
+        if (layout == 0 && st.kind == ST_CONV && st.fuse_next) touched[2] = pol->steps[si + 1].out_buf;
         for (int b : touched) {
             if (b < 0) continue;
             first[b] = std::min(first[b], si);
@@ -1166,6 +1185,19 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
     rc = build_plan(B);
     if (rc) return rc;
     cst.swap(B.cst);
+    if (!getenv("ACCERL_NO_CONV_FUSE")) {
+        for (size_t si = 0; si + 1 < pol->steps.size(); ++si) {
+            Step& sa = pol->steps[si];
+            Step& sb = pol->steps[si + 1];
+            if (sa.kind != ST_CONV || sb.kind != ST_CONV || sa.el != EL_I8 || sb.el != EL_I8) continue;
+            if (sa.fused_prev || sa.res_buf >= 0 || sb.res_buf >= 0 || sb.in_buf != sa.out_buf) continue;
+            bool read_elsewhere = false;             // the first layer's output must have no other reader
+            for (size_t sj = si + 2; sj < pol->steps.size(); ++sj)
+                if (pol->steps[sj].in_buf == sa.out_buf || pol->steps[sj].res_buf == sa.out_buf) read_elsewhere = true;
+            if (read_elsewhere) continue;
+            if (conv_fused_supported(sa.cp, sa.NT, sa.KS, sa.RD, sb.cp, sb.NT, sb.KS, sb.RD)) { sa.fuse_next = true; sb.fused_prev = true; }
+        }
+    }
     assign_slots(pol, 0);
     assign_slots(pol, 1);
     pol->ws_per_state = 0;
@@ -1225,9 +1257,9 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
             const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles + (c.pool ? c.lds_otile : 0);
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
-                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d\n",
+                     "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d fuse_next=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
-                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt, c.pool, c.TPH);
+                     s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt, c.pool, c.TPH, (int)s.fuse_next);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu);
