@@ -144,27 +144,31 @@ def main():
     macs = layer_macs(ns, None)
     n_launch_step = sum(p["launches"] for p in prof) / args.steps
     breakdown = []
+    def step_macs(p):
+        m = macs.get(p["layer"], 0) if p["kind"] in ("conv", "gemm", "heads") else 0
+        if p["layer"] < len(ns.layers) and ns.layers[p["layer"]]["kind"] == "resblock":
+            m //= 2
+        return m
     for p in prof:
         if not p["launches"]:
+            # a conv or max-pool done inside the kernel of the step before it: its work counts there
+            if breakdown and p["kind"] in ("conv", "maxpool"):
+                breakdown[-1]["layers"].append(p["layer"])
+                breakdown[-1]["macs"] += step_macs(p)
             continue
         per_step_ms = p["total_ms"] / args.steps
-        ent = dict(step=p["step"], kind=p["kind"], layer=p["layer"], ms_per_step=round(per_step_ms, 5),
-                   launches_per_step=p["launches"] / args.steps)
-        if p["kind"] in ("conv", "gemm", "heads"):
-            m = macs.get(p["layer"], 0)
-            if ns.layers[p["layer"]]["kind"] == "resblock" if p["layer"] < len(ns.layers) else False:
-                m //= 2
-            ent["tops"] = round(2 * m * B / (per_step_ms * 1e-3) / 1e12, 2)
-        breakdown.append(ent)
+        breakdown.append(dict(step=p["step"], kind=p["kind"], layer=p["layer"], layers=[p["layer"]], macs=step_macs(p),
+                              ms_per_step=round(per_step_ms, 5), launches_per_step=p["launches"] / args.steps))
+    for ent in breakdown:
+        if ent["macs"]:
+            ent["tops"] = round(2 * ent["macs"] * B / (ent["ms_per_step"] * 1e-3) / 1e12, 2)
     dom = max(breakdown, key=lambda e: e["ms_per_step"])
     launches = dom["launches_per_step"]
     avg_launch_s = dom["ms_per_step"] * 1e-3 / launches
     obs_bytes = int(np.prod(ns.obs_shape)) * (1 if ns.obs_dtype == "u8" else 4)
     first_param = min(macs) if macs else -1
     if dom["kind"] in ("conv", "gemm", "heads"):
-        m = macs[dom["layer"]]
-        if dom["layer"] < len(ns.layers) and ns.layers[dom["layer"]]["kind"] == "resblock":
-            m //= 2
+        m = dom["macs"]
         is_bf16 = student.recurrent and dom["layer"] >= len(ns.layers) - 1
         ops_launch = 2.0 * m * B / launches
         peak = PEAK["bf16" if is_bf16 else "int8"]
@@ -176,18 +180,18 @@ def main():
             bytes_launch = obs_bytes * B / launches
             roofline = dict(bound="hbm", achieved=round(bytes_launch / avg_launch_s / 1e9, 2), peak=PEAK["hbm"] / 1e9,
                             unit="GB/s", frac=round(bytes_launch / avg_launch_s / PEAK["hbm"], 4), traffic=None,
-                            kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                            kernel=f"{dom['kind']} layers {dom['layers']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
                             launches_per_step=launches, mfma_frac=round(ops_launch / avg_launch_s / peak, 4))
         else:
             roofline = dict(bound="mfma", achieved=round(ops_launch / avg_launch_s / 1e12, 3), peak=peak / 1e12,
                             unit="TFLOP/s", frac=round(ops_launch / avg_launch_s / peak, 4), traffic=None,
-                            kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                            kernel=f"{dom['kind']} layers {dom['layers']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
                             launches_per_step=launches)
     else:
         bytes_launch = io_bytes(ns) * B / launches
         roofline = dict(bound="hbm", achieved=round(bytes_launch / avg_launch_s / 1e9, 2), peak=PEAK["hbm"] / 1e9,
                         unit="GB/s", frac=round(bytes_launch / avg_launch_s / PEAK["hbm"], 4), traffic=None,
-                        kernel=f"{dom['kind']} layer {dom['layer']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
+                        kernel=f"{dom['kind']} layers {dom['layers']}", avg_launch_us=round(avg_launch_s * 1e6, 2),
                         launches_per_step=launches)
     tfile = os.path.join(ROOT, "profiles", f"traffic_cfg{ci}_B{B}.txt")
     if os.path.exists(tfile):

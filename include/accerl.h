@@ -179,10 +179,12 @@ int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, 
 
 /*
  * Measurement aid (not part of the method).  Between accerl_profile_begin and accerl_profile_end
- * every forward call on the policy records a pair of HIP events around each kernel launch of its
- * plan, on the stream of that call.  accerl_profile_end waits for those events and returns, per
- * plan step, the summed elapsed time in ms, the number of launches, the arch layer the step
- * belongs to (n_layers = heads / sampler) and the step kind (0 fused MLP, 1 observation quantizer,
+ * every forward call on the policy records one HIP event after each kernel launch of its plan (and
+ * one before the first), on the stream of that call; a step's time is the span between the event
+ * before it and the event after it.  A step whose work was done by the step before it (a conv or a
+ * max-pool fused into the preceding conv kernel) records nothing and reports zero launches.
+ * accerl_profile_end waits for the events and returns, per plan step, the summed elapsed time in
+ * ms, the number of launches, the arch layer the step belongs to (n_layers = heads / sampler) and the step kind (0 fused MLP, 1 observation quantizer,
  * 2 convolution, 3 MFMA dense, 4 fp32 dense, 5 max pooling, 6 LSTM packing, 7 sampler, 8 heads + sampler).  All arrays
  * are HOST, `cap` entries each; *n_steps receives the number of plan steps (also on ACCERL_EINVAL
  * when cap is too small).

@@ -213,10 +213,12 @@ struct accerl_policy {
     hipEvent_t mix_ev[4] = {nullptr, nullptr, nullptr, nullptr};
     int64_t mix_pin_rows = 0;
     int mix_slot = 0;
-    // measurement aid: event pairs around every launch while profiling is on
+    // measurement aid while profiling is on: one event after every launch (and one before the first of a
+    // pass); a step's time is the span between the event before it and the event after it
     bool profiling = false;
     struct Ev { int step; hipEvent_t a, b; };
     std::vector<Ev> events;
+    std::vector<hipEvent_t> ev_starts;
 };
 
 namespace {
@@ -952,15 +954,16 @@ int run(accerl_policy* p, const Call& c) {
         auto bufp = [&](int b) -> char* { return b < 0 ? const_cast<char*>(states) : p->ws + p->bufs[b].off; };
         bool pooled = false;   // the last conv step also did the max-pool that follows it
         bool conv_pair_done = false;   // the last conv step also did the conv that follows it
+        hipEvent_t prof_prev = nullptr;
         for (int si = 0; si <= last_step; ++si) {
             const Step& s = p->steps[si];
             const bool tap_here = c.debug && !fused && si == last_step;
             hipError_t e = hipSuccess;
-            accerl_policy::Ev ev{si, nullptr, nullptr};
-            if (p->profiling) {
-                HIP_TRY(hipEventCreate(&ev.a));
-                HIP_TRY(hipEventCreate(&ev.b));
-                HIP_TRY(hipEventRecord(ev.a, c.stream));
+            bool launched = true;          // false for a step whose work the step before it has done
+            if (p->profiling && !prof_prev) {
+                HIP_TRY(hipEventCreate(&prof_prev));
+                HIP_TRY(hipEventRecord(prof_prev, c.stream));
+                p->ev_starts.push_back(prof_prev);
             }
             switch (s.kind) {
                 case ST_MLP: {
@@ -982,7 +985,7 @@ int run(accerl_policy* p, const Call& c) {
                     e = launch_quant_obs((const float*)states, n, s.D, s.Dpad, s.inv_s0, (int8_t*)bufp(s.out_buf), c.stream);
                     break;
                 case ST_CONV: {
-                    if (s.fused_prev && conv_pair_done) { conv_pair_done = false; break; }   // done by the step before
+                    if (s.fused_prev && conv_pair_done) { conv_pair_done = false; launched = false; break; }   // done by the step before
                     if (s.fuse_next && !c.debug) {
                         const Step& nx = p->steps[si + 1];
                         ConvParams ca = s.cp, cb = nx.cp;
@@ -1012,7 +1015,7 @@ int run(accerl_policy* p, const Call& c) {
                     break;
                 }
                 case ST_MAXPOOL:
-                    if (s.fused && pooled) { pooled = false; break; }   // done by the conv step before
+                    if (s.fused && pooled) { pooled = false; launched = false; break; }   // done by the conv step before
                     e = launch_maxpool(bufp(s.in_buf), bufp(s.out_buf), n, s.H, s.W, s.Cs, s.Ho, s.Wo, s.k, s.s, s.pad, s.el, c.stream);
                     break;
                 case ST_GEMM: {
@@ -1067,9 +1070,12 @@ int run(accerl_policy* p, const Call& c) {
                 }
             }
             if (e != hipSuccess) return fail(ACCERL_EHIP, "step %d (kind %d, layer %d): %s", si, (int)s.kind, s.layer, hipGetErrorString(e));
-            if (p->profiling) {
+            if (p->profiling && launched) {
+                accerl_policy::Ev ev{si, prof_prev, nullptr};
+                HIP_TRY(hipEventCreate(&ev.b));
                 HIP_TRY(hipEventRecord(ev.b, c.stream));
                 p->events.push_back(ev);
+                prof_prev = ev.b;
             }
             if (tap_here && !tap_acc) {
                 const char* src = bufp(s.out_buf);
@@ -1274,7 +1280,8 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
 
 void accerl_policy_destroy(accerl_policy* p) {
     if (!p) return;
-    for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+    for (auto& ev : p->events) (void)hipEventDestroy(ev.b);
+    for (auto& ev : p->ev_starts) (void)hipEventDestroy(ev);
     if (p->ws) (void)hipFree(p->ws);
     if (p->consts) (void)hipFree(p->consts);
     if (p->mix_dev) (void)hipFree(p->mix_dev);
@@ -1422,8 +1429,10 @@ int accerl_actor_forward_debug(accerl_policy* p, const void* states, int64_t B, 
 
 int accerl_profile_begin(accerl_policy* p) {
     if (!p) return fail(ACCERL_EINVAL, "policy is NULL");
-    for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+    for (auto& ev : p->events) (void)hipEventDestroy(ev.b);
+    for (auto& ev : p->ev_starts) (void)hipEventDestroy(ev);
     p->events.clear();
+    p->ev_starts.clear();
     p->profiling = true;
     return ACCERL_OK;
 }
@@ -1447,8 +1456,10 @@ int accerl_profile_end(accerl_policy* p, int32_t cap, int32_t* n_steps, float* t
             launches[ev.step] += 1;
         }
     }
-    for (auto& ev : p->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+    for (auto& ev : p->events) (void)hipEventDestroy(ev.b);
+    for (auto& ev : p->ev_starts) (void)hipEventDestroy(ev);
     p->events.clear();
+    p->ev_starts.clear();
     return rc;
 }
 
