@@ -6,9 +6,9 @@
 //   phase A  uint8 planes -> channels-last tile in LDS (byte permutes), conv A on the matrix cores with
 //            its weights in registers, requantized (ReLU) output written to a second LDS tile, which is
 //            exactly the channels-last image conv B reads;
-//   phase B  conv B from that tile with its weights in LDS; work items are (16-pixel tile, half of the
-//            64 output channels), dealt round-robin to the four wavefronts so that the six tiles of a
-//            9x9 output keep all of them busy; requantized output goes to memory.
+//   phase B  conv B from that tile with its weights in LDS; work items are (three 16-pixel tiles, half of
+//            the 64 output channels), dealt round-robin to the four wavefronts: the six tiles of a 9x9
+//            output are exactly one item each; requantized output goes to memory.
 // Both phases use the arithmetic of conv_kernel.h (same fragments, same epilogue), so accumulators and
 // activations are bit-identical to the unfused path; debug taps run the unfused kernels.
 #include "conv_kernel.h"
@@ -152,9 +152,9 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
             for (int u = 0; u < 2; ++u) {
                 if (pp[u] >= npixA) continue;
                 char* dst = tileB + __mul24(pp[u], a.Cs_out) + 4 * NTA * g;
+                uint32_t wq[NTA];
 #pragma unroll
                 for (int t = 0; t < NTA; ++t) {
-                    if (4 * NTA * g + 4 * t >= a.Cs_out) continue;
                     uint32_t w = 0;
                     if (a.relu) {
 #pragma unroll
@@ -166,46 +166,71 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
                         for (int r = 0; r < 4; ++r) q[r] = rne_clamp127((float)acc[u][t][r] * mlA[t][r]);
                         w = pack_low_bytes(q);
                     }
-                    *(uint32_t*)(dst + 4 * t) = w;
+                    wq[t] = w;
+                }
+                if (NTA == 2 && 8 * g + 8 <= a.Cs_out) {
+                    typedef int v2i __attribute__((ext_vector_type(2)));
+                    *(v2i*)dst = (v2i){(int)wq[0], (int)wq[NTA - 1]};
+                } else {
+#pragma unroll
+                    for (int t = 0; t < NTA; ++t)
+                        if (4 * NTA * g + 4 * t < a.Cs_out) *(uint32_t*)(dst + 4 * t) = wq[t];
                 }
             }
         }
         __syncthreads();     // tile B complete
 
-        // ---- phase B: conv B from tile B; item = (pixel tile, channel half)
+        // ---- phase B: conv B from tile B; item = (three pixel tiles, channel half): five fragment reads feed
+        // six MFMAs per step, and a 9x9 output (six tiles) is exactly one item per wavefront
         char* outB = (char*)b.out + img * (int64_t)npixB * b.Cs_out;
-        for (int it = wave; it < 2 * tilesB; it += 4) {
-            const int tile = it >> 1, h = it & 1;
-            const int pp = tile * 16 + j;
-            const int pc = min(pp, npixB - 1);
-            const int ty = qdiv(pc, b.inv_wo, b.hinv_wo), ox = pc - __mul24(ty, b.Wo);
-            const char* base = tileB + __mul24(ty, rowB) + __mul24(ox, colB);
-            v4i acc0 = biasB[2 * h], acc1 = biasB[2 * h + 1];
+        const int itemsB = 2 * ((tilesB + 2) / 3);
+        for (int it = wave; it < itemsB; it += 4) {
+            const int h = it & 1, tile0 = (it >> 1) * 3;
+            int pp[3];
+            const char* base[3];
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                pp[u] = (tile0 + u) * 16 + j;
+                const int pc = min(pp[u], npixB - 1);
+                const int ty = qdiv(pc, b.inv_wo, b.hinv_wo), ox = pc - __mul24(ty, b.Wo);
+                base[u] = tileB + __mul24(ty, rowB) + __mul24(ox, colB);
+            }
+            v4i acc[3][2];
+#pragma unroll
+            for (int u = 0; u < 3; ++u) { acc[u][0] = biasB[2 * h]; acc[u][1] = biasB[2 * h + 1]; }
             for (int st = 0; st < b.k_steps; ++st) {
                 const v4i a0 = *(const v4i*)(wl + ((st * 4 + 2 * h) * 64 + lane) * 16);
                 const v4i a1 = *(const v4i*)(wl + ((st * 4 + 2 * h + 1) * 64 + lane) * 16);
-                const v4i bq = *(const v4i*)(base + koffB[st * 4 + g]);
-                acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bq, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bq, acc1, 0, 0, 0);
+                const int ko = koffB[st * 4 + g];
+                v4i bq[3];
+#pragma unroll
+                for (int u = 0; u < 3; ++u) bq[u] = *(const v4i*)(base[u] + ko);
+#pragma unroll
+                for (int u = 0; u < 3; ++u) {
+                    acc[u][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bq[u], acc[u][0], 0, 0, 0);
+                    acc[u][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bq[u], acc[u][1], 0, 0, 0);
+                }
             }
-            if (pp < npixB) {
-                const v4f m0 = multB[2 * h], m1 = multB[2 * h + 1];
+            const v4f m0 = multB[2 * h], m1 = multB[2 * h + 1];
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                if (pp[u] >= npixB) continue;
                 uint32_t w0 = 0, w1 = 0;
                 if (b.relu) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        w0 = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc0[r] * m0[r], 0.0f, 127.0f), r, w0);
-                        w1 = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc1[r] * m1[r], 0.0f, 127.0f), r, w1);
+                        w0 = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc[u][0][r] * m0[r], 0.0f, 127.0f), r, w0);
+                        w1 = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc[u][1][r] * m1[r], 0.0f, 127.0f), r, w1);
                     }
                 } else {
                     int q0[4], q1[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) { q0[r] = rne_clamp127((float)acc0[r] * m0[r]); q1[r] = rne_clamp127((float)acc1[r] * m1[r]); }
+                    for (int r = 0; r < 4; ++r) { q0[r] = rne_clamp127((float)acc[u][0][r] * m0[r]); q1[r] = rne_clamp127((float)acc[u][1][r] * m1[r]); }
                     w0 = pack_low_bytes(q0);
                     w1 = pack_low_bytes(q1);
                 }
                 typedef int v2i __attribute__((ext_vector_type(2)));
-                *(v2i*)(outB + __mul24(pp, b.Cs_out) + 16 * g + 8 * h) = (v2i){(int)w0, (int)w1};
+                *(v2i*)(outB + __mul24(pp[u], b.Cs_out) + 16 * g + 8 * h) = (v2i){(int)w0, (int)w1};
             }
         }
     }
