@@ -1,7 +1,8 @@
 // Dense layers on the matrix cores: out[b, n] = sum_k W[n, k] x[b, k], int8 (int32 accumulate) or
 // bf16 (fp32 accumulate).  Output features are the MFMA rows and states the columns, so one lane ends
 // up with 4 consecutive features of one state.  A workgroup owns 64 features x 64 states and walks K
-// in stages of 256 bytes per row staged through LDS; the epilogue is chosen at compile time:
+// in stages of 256 bytes per row: weights through LDS, every wavefront's 16 states straight from memory
+// into its B fragments; the epilogue is chosen at compile time:
 // requantize to int8, bias+ReLU to bf16, policy heads (logits / value in fp32), or the LSTM cell
 // (weight rows are interleaved on the host so that the 4 accumulators of a lane are the i,f,g,o
 // pre-activations of one hidden unit).
@@ -14,7 +15,6 @@ constexpr int GM_NT = 4;          // feature tiles (of 16) per workgroup
 constexpr int GM_RT = 1;          // row tiles (of 16 states) per wave
 constexpr int GM_ROWS = 64 * GM_RT;   // states per workgroup
 constexpr int GM_KS = 4;          // MFMA steps per LDS stage (64 bytes of K each); a multiple of 4
-constexpr int GM_XPITCH = GM_KS * 64 + 16;
 
 __device__ __forceinline__ uint32_t g_relu_i8x4(uint32_t x) {
     const uint32_t neg = (x & 0x80808080u) >> 7;
@@ -36,7 +36,6 @@ template <int EL, int EPI>
 __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char gm_smem[];
     char* s_w = gm_smem;                              // [GM_NT][GM_KS][64 lanes][16 B]
-    char* s_x = gm_smem + GM_NT * GM_KS * 1024;       // [GM_ROWS][GM_XPITCH]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int64_t b0 = (int64_t)blockIdx.x * GM_ROWS;
@@ -56,13 +55,22 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         }
     }
 
-    // Stage s0 of K: weights [GM_NT tiles][GM_KS steps] and states [GM_ROWS][GM_KS*64 bytes].  The loads of
-    // the next stage are issued into registers before the MFMA work of the current one.  They are
-    // unconditional (clamped addresses, zeroed afterwards) so that nothing serialises them.
+    // Stage s0 of K: the weight fragments [GM_NT tiles][GM_KS steps] go through LDS (all four wavefronts
+    // read them); a wavefront's own 16 states need no sharing: lane (j, g) loads state j's 16 bytes of K
+    // block g straight from memory, which is exactly its MFMA B fragment.  The loads of the next stage are
+    // issued into registers before the MFMA work of the current one.  They are unconditional (clamped
+    // addresses, fixed up afterwards) so that nothing serialises them.
     constexpr int WPRE = GM_NT * GM_KS * 64 / GM_THREADS;       // weight units per lane
-    constexpr int XPRE = GM_ROWS * GM_KS * 4 / GM_THREADS;      // state units per lane
-    constexpr int UPR = GM_KS * 4;                              // state units per row and stage
-    v4i wpre[WPRE], xpre[XPRE];
+    v4i wpre[WPRE], xpre[GM_RT][GM_KS], xcur[GM_RT][GM_KS];
+    bool row_live[GM_RT];
+    const char* xptr[GM_RT];
+#pragma unroll
+    for (int u = 0; u < GM_RT; ++u) {
+        int64_t xrow = b0 + (wave * GM_RT + u) * 16 + j;
+        row_live[u] = xrow < p.B;
+        if (!row_live[u]) xrow = p.B - 1;
+        xptr[u] = (const char*)p.x + xrow * p.Kp_bytes;
+    }
     auto prefetch = [&](int s0) {
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
 #pragma unroll
@@ -72,14 +80,11 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
             wpre[r] = ((const v4i*)p.wfrag)[((int64_t)(nt0 + t) * p.k_steps + s0 + st) * 64 + lane];
         }
 #pragma unroll
-        for (int r = 0; r < XPRE; ++r) {
-            const int i = tid + r * GM_THREADS;
-            const int rr = i / UPR, c = i % UPR;
-            int64_t b = b0 + rr;
-            if (b >= p.B) b = p.B - 1;
-            int kb = s0 * 64 + c * 16;
+        for (int st = 0; st < GM_KS; ++st) {
+            int kb = (s0 + st) * 64 + g * 16;
             if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
-            xpre[r] = *(const v4i*)((const char*)p.x + b * p.Kp_bytes + kb);
+#pragma unroll
+            for (int u = 0; u < GM_RT; ++u) xpre[u][st] = *(const v4i*)(xptr[u] + kb);
         }
     };
     auto commit = [&](int s0) {
@@ -92,14 +97,14 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
             ((v4i*)s_w)[(tr * GM_KS + sr) * 64 + lane] = v;
         }
 #pragma unroll
-        for (int r = 0; r < XPRE; ++r) {
-            const int i = tid + r * GM_THREADS;
-            const int rr = i / UPR, c = i % UPR;
-            const int kb = s0 * 64 + c * 16;
-            v4i v = xpre[r];
-            // a unit that starts inside the row but runs past it re-read the row's last 16 bytes: rebuild
+        for (int st = 0; st < GM_KS; ++st)
+#pragma unroll
+        for (int u = 0; u < GM_RT; ++u) {
+            const int kb = (s0 + st) * 64 + g * 16;
+            v4i v = xpre[u][st];
+            // a chunk that starts inside the row but runs past it re-read the row's last 16 bytes: rebuild
             // it from the bytes that belong to it (rows are padded with zero weights, not zero data)
-            if (b0 + rr >= p.B || kb >= p.Kp_bytes) {
+            if (!row_live[u] || kb >= p.Kp_bytes) {
                 v = (v4i){0, 0, 0, 0};
             } else if (kb > p.Kp_bytes - 16) {
                 const int have = p.Kp_bytes - kb;              // 4, 8 or 12 valid bytes, at the end of v
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
                 for (int e = 0; e < 4; ++e)
                     v[e] = (int)((EL == EL_I8) ? g_relu_i8x4((uint32_t)v[e]) : g_relu_bf16x2((uint32_t)v[e]));
             }
-            *(v4i*)(s_x + rr * GM_XPITCH + c * 16) = v;
+            xcur[u][st] = v;
         }
     };
 
@@ -124,35 +129,32 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         commit(s0);
         __syncthreads();
         if (s0 + GM_KS < p.k_steps) prefetch(s0 + GM_KS);
-        // the fragments of step st+1 are requested from LDS before the MFMAs of step st are issued
-        auto load_f = [&](v4i (&a)[GM_NT], v4i (&bq)[GM_RT], int st) {
-#pragma unroll
-            for (int u = 0; u < GM_RT; ++u)
-                bq[u] = *(const v4i*)(s_x + ((wave * GM_RT + u) * 16 + j) * GM_XPITCH + st * 64 + g * 16);
+        // the weight fragments of step st+1 are requested from LDS before the MFMAs of step st are issued
+        auto load_a = [&](v4i (&a)[GM_NT], int st) {
 #pragma unroll
             for (int t = 0; t < GM_NT; ++t) a[t] = *(const v4i*)(s_w + ((t * GM_KS + st) * 64 + lane) * 16);
         };
-        auto mfma = [&](const v4i (&a)[GM_NT], const v4i (&bq)[GM_RT]) {
+        auto mfma = [&](const v4i (&a)[GM_NT], int st) {
 #pragma unroll
             for (int t = 0; t < GM_NT; ++t)
 #pragma unroll
                 for (int u = 0; u < GM_RT; ++u) {
                     if constexpr (EL == EL_I8) {
-                        acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t], bq[u], acc_i[u][t], 0, 0, 0);
+                        acc_i[u][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t], xcur[u][st], acc_i[u][t], 0, 0, 0);
                     } else {
                         acc_f[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(v8bf, a[t]), __builtin_bit_cast(v8bf, bq[u]), acc_f[u][t], 0, 0, 0);
+                            __builtin_bit_cast(v8bf, a[t]), __builtin_bit_cast(v8bf, xcur[u][st]), acc_f[u][t], 0, 0, 0);
                     }
                 }
         };
         {
-            v4i fa[2][GM_NT], fb[2][GM_RT];
-            load_f(fa[0], fb[0], 0);
+            v4i fa[2][GM_NT];
+            load_a(fa[0], 0);
 #pragma unroll
             for (int st = 0; st < GM_KS; ++st) {
                 if (st < ns) {
-                    if (st + 1 < ns) load_f(fa[(st + 1) & 1], fb[(st + 1) & 1], st + 1);
-                    mfma(fa[st & 1], fb[st & 1]);
+                    if (st + 1 < ns) load_a(fa[(st + 1) & 1], st + 1);
+                    mfma(fa[st & 1], st);
                 }
             }
         }
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
 
 template <int EL, int EPI>
 static hipError_t gemm_go(const GemmParams& p, dim3 grid, hipStream_t s) {
-    constexpr size_t lds = GM_NT * GM_KS * 1024 + GM_ROWS * GM_XPITCH;
+    constexpr size_t lds = GM_NT * GM_KS * 1024;
     auto kfn = gemm_kernel<EL, EPI>;
     static bool set = false;   // per instantiation: the stage buffers exceed the default dynamic LDS limit
     if (!set) {
