@@ -82,7 +82,7 @@ struct ConvParams {
     int img_bytes;           // FLAT: contiguous bytes per image
     int units_img;           // 16-byte staging units per image tile
     int row_units;           // ROWS / U8T: units per tile row
-    uint32_t magic_npix, magic_wo, magic_units, magic_rowunits;   // ceil(2^32/d), 0 for d = 1
+    uint32_t magic_units, magic_rowunits;   // ceil(2^32/d) for d = units per image tile, units per tile row (0 for d = 1)
     float inv_wo, hinv_wo;   // 1/Wo and 0.5/Wo
     // fused 3x3 stride-2 pad-1 max-pool of the layer's output (pool = 0: plain store to out)
     int pool;

@@ -418,7 +418,6 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     c.img_bytes = H * row_bytes;
     c.units_img = units_img;
     c.row_units = mode == CM_U8T ? W / 4 : rows_vec ? row_bytes / 16 : pitch / 16;
-    c.magic_npix = magic_of(n_pix); c.magic_wo = magic_of(Wo);
     if ((int64_t)G * n_pix >= (1 << 20) || (int64_t)Ho * Wo >= (1 << 20) || tile_stride >= (1 << 23) || (int64_t)ss * pitch >= (1 << 23))
         return fail(ACCERL_EUNSUPPORTED, "layer %d: image too large for the pixel index arithmetic", layer);
     c.pool = pool ? 1 : 0; c.pool_out = nullptr; c.PH = PH; c.PW = PW; c.TPH = TPH; c.pool_W = Wo_img;

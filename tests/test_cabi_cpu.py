@@ -116,3 +116,46 @@ def test_monitor_and_vtrace_reject_bad_arguments_before_any_launch(A):
     assert lib.accerl_vtrace(None, None, None, None, None, None, None, 4, 4, 6, 1.0, 1.0, None, None, None, None) == -1
     assert lib.accerl_vtrace(None, None, None, None, None, None, None, 4, 4, 0, 1.0, 1.0, None, None, None, None) == -1
     assert lib.accerl_vtrace(None, None, None, None, None, None, None, 4, 4, 6, -1.0, 1.0, None, None, None, None) == -1
+
+
+def _plan(A, net, prec, tensors, scales=None):
+    blob = A.pack_weights(tensors)
+    sc = A.pack_scales(scales, tensors) if scales is not None else None
+    return A.accerl_plan_describe(A.make_arch(net, prec), blob, sc)
+
+
+def _fields(line):
+    return dict(tok.split("=", 1) for tok in line.split() if "=" in tok)
+
+
+def test_planner_decisions_on_the_benchmark_networks(A):
+    """Host-only view of the launch plans: the fusions and layouts the kernels rely on are chosen where expected."""
+    from helpers import policies
+    # config 2 student: first two convs share a kernel; conv3 runs wave-private
+    nt, pt, ns, ps, qp = policies(2, 8)
+    steps = [l for l in _plan(A, ns, "int8", qp.tensors, qp.act_scales).splitlines() if l.startswith("step")]
+    convs = [_fields(l) for l in steps if " conv " in l]
+    assert [c["fuse_next"] for c in convs] == ["1", "0", "0"]
+    assert convs[0]["mode"] == "2" and convs[0]["KS"] == "4" and convs[2]["wp"] == "1"
+    # config 3 student: thin layers are pixel-packed (8 stored channels -> 16-row tiles at half the width),
+    # the three stack convs carry their max-pool, residual convs do not
+    nt, pt, ns, ps, qp = policies(3, 8)
+    steps = [l for l in _plan(A, ns, "int8", qp.tensors, qp.act_scales).splitlines() if l.startswith("step")]
+    convs = [_fields(l) for l in steps if " conv " in l]
+    assert convs[0]["out"] == "84x42x16" and convs[1]["out"] == "42x21x16"
+    assert [c["pool"] for c in convs].count("1") == 3 and convs[0]["pool"] == "1"
+    assert all(int(c["PF"]) <= 4 for c in convs)                   # small batches: four workgroups per compute unit
+    assert sum(1 for l in steps if " maxpool " in l) == 3          # kept in the plan for debug taps
+    # the teacher's wider layers are not packed
+    tsteps = [l for l in _plan(A, nt, "bf16", [dict(w=w, b=b) for _, w, b in pt]).splitlines() if l.startswith("step")]
+    assert _fields([l for l in tsteps if " conv " in l][0])["out"] == "84x84x16"
+
+
+def test_workspace_slots_are_shared(A):
+    from helpers import policies
+    nt, pt, ns, ps, qp = policies(3, 8)
+    head = _plan(A, ns, "int8", qp.tensors, qp.act_scales).splitlines()[0]
+    per_state = int(_fields(head)["ws_bytes_per_state"])
+    shapes = wl.trace_shapes(ns)
+    naive = sum(int(np.prod(s)) for s in shapes if len(s) == 3)    # one buffer per image-shaped layer output
+    assert per_state < naive / 3
