@@ -601,22 +601,36 @@ hipError_t conv_go(const ConvParams& p, dim3 grid, size_t lds, hipStream_t s) {
         if (e != hipSuccess) return e;
         set_lds = lds;
     }
-    static size_t occ_lds = ~(size_t)0;
-    static int occ = 1;
-    if (occ_lds != lds) {
+    // occupancy of this instantiation at this LDS size: a few sizes occur per policy, remembered in a small table
+    static size_t occ_lds[4] = {~(size_t)0, ~(size_t)0, ~(size_t)0, ~(size_t)0};
+    static int occ_val[4] = {1, 1, 1, 1};
+    static int occ_next = 0;
+    int occ = 0;
+    for (int i = 0; i < 4; ++i) if (occ_lds[i] == lds) occ = occ_val[i];
+    if (!occ) {
         int o = 0;
         hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)kfn, NW * 64, lds);
         if (e != hipSuccess) return e;
         occ = o < 1 ? 1 : o;
-        occ_lds = lds;
+        occ_val[occ_next] = occ;
+        occ_lds[occ_next] = lds;
+        occ_next = (occ_next + 1) & 3;
     }
-    const int64_t n_batch = (p.B + p.G - 1) / p.G;
-    const int64_t items = WP ? (n_batch + NW - 1) / NW : n_batch;     // batches a workgroup takes per round
     int64_t cap = (int64_t)occ * conv_num_cus() / (int64_t)grid.x;
     if (cap < 1) cap = 1;
+    // a small call does not fill the chip with batches of G images: take fewer images per batch (the LDS
+    // layout allows any count up to G), so that more workgroups share the work and each has a shorter chain
+    ConvParams q = p;
+    const int64_t slots = cap * (WP ? NW : 1);                       // batches in flight when every slot is used
+    if ((q.B + q.G - 1) / q.G < slots) {
+        const int64_t g = (q.B + slots - 1) / slots;
+        q.G = (int)(g < 1 ? 1 : g < q.G ? g : q.G);
+    }
+    const int64_t n_batch = (q.B + q.G - 1) / q.G;
+    const int64_t items = WP ? (n_batch + NW - 1) / NW : n_batch;     // batches a workgroup takes per round
     const int64_t rounds = (items + cap - 1) / cap;
     grid.y = (unsigned)((items + rounds - 1) / rounds);
-    kfn<<<grid, dim3(NW * 64), lds, s>>>(p);
+    kfn<<<grid, dim3(NW * 64), lds, s>>>(q);
     return hipGetLastError();
 }
 
