@@ -234,6 +234,100 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
     }
 }
 
+// ---- small batches (int8, requantizing epilogue): too few 64-state workgroups to fill the chip, and each
+// would walk all of K alone.  Here a workgroup owns 16 states x 64 features and its four wavefronts split
+// K: wavefront w takes the MFMA steps w, w+4, ...; weights and states both come straight from memory
+// (nothing is shared between the wavefronts), two steps are kept in flight, and the four partial
+// accumulators meet in LDS, where wavefront t finishes feature tile t.  Integer sums: the result does
+// not depend on the split.
+constexpr int GS_NT = 4;
+__global__ __launch_bounds__(256) void gemm_small_i8_kernel(const GemmParams p) {
+    __shared__ __attribute__((aligned(16))) int s_part[4][GS_NT][64][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int64_t b0 = (int64_t)blockIdx.x * 16;
+    const int nt0 = blockIdx.y * GS_NT;
+    const int nts = (p.n_tiles - nt0 < GS_NT) ? (p.n_tiles - nt0) : GS_NT;
+    int64_t xrow = b0 + j;
+    const bool row_live = xrow < p.B;
+    if (!row_live) xrow = p.B - 1;
+    const char* xptr = (const char*)p.x + xrow * p.Kp_bytes;
+
+    v4i acc[GS_NT];
+#pragma unroll
+    for (int t = 0; t < GS_NT; ++t) acc[t] = (v4i){0, 0, 0, 0};
+    auto load = [&](int st, v4i (&a)[GS_NT], v4i& x) {
+        const int sc = st < p.k_steps ? st : p.k_steps - 1;          // past the end: a valid step, not used
+#pragma unroll
+        for (int t = 0; t < GS_NT; ++t)
+            a[t] = ((const v4i*)p.wfrag)[((int64_t)(nt0 + (t < nts ? t : 0)) * p.k_steps + sc) * 64 + lane];
+        int kb = sc * 64 + g * 16;
+        if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
+        x = *(const v4i*)(xptr + kb);
+    };
+    auto fix_x = [&](int st, v4i v) -> v4i {
+        const int kb = st * 64 + g * 16;
+        if (!row_live || kb >= p.Kp_bytes) {
+            v = (v4i){0, 0, 0, 0};
+        } else if (kb > p.Kp_bytes - 16) {                           // the row's last, partial chunk (see gemm_kernel)
+            const int sh = (16 - (p.Kp_bytes - kb)) >> 2;
+            v4i w = {0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (e + sh < 4) w[e] = v[(e + sh) & 3];
+            v = w;
+        }
+        if (p.relu_in) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (int)g_relu_i8x4((uint32_t)v[e]);
+        }
+        return v;
+    };
+    v4i a0[GS_NT], a1[GS_NT], x0, x1;
+    load(wave, a0, x0);
+    for (int st = wave; st < p.k_steps; st += 8) {
+        load(st + 4, a1, x1);
+        {
+            const v4i x = fix_x(st, x0);
+#pragma unroll
+            for (int t = 0; t < GS_NT; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0[t], x, acc[t], 0, 0, 0);
+        }
+        load(st + 8, a0, x0);
+        if (st + 4 < p.k_steps) {
+            const v4i x = fix_x(st + 4, x1);
+#pragma unroll
+            for (int t = 0; t < GS_NT; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1[t], x, acc[t], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < GS_NT; ++t) *(v4i*)s_part[wave][t][lane] = acc[t];
+    __syncthreads();
+    // wavefront t finishes feature tile t: features n0 .. n0+3 of state b in lane (j, g)
+    const int t = wave;
+    const int64_t b = b0 + j;
+    const int n0 = (nt0 + t) * 16 + 4 * g;
+    if (t >= nts || b >= p.B || n0 >= p.Np) return;
+    v4i sum = *(const v4i*)((const int*)p.bias + n0);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const v4i v = *(const v4i*)s_part[w][t][lane];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum[r] += v[r];
+    }
+    const v4f ml = *(const v4f*)(p.mult + n0);
+    uint32_t pk = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if (p.tap_acc && n0 + r < p.N) p.tap_acc[b * p.N + n0 + r] = sum[r];
+        if (p.relu) {
+            pk = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)sum[r] * ml[r], 0.0f, 127.0f), r, pk);
+        } else {
+            const float y = __builtin_amdgcn_fmed3f(rintf((float)sum[r] * ml[r]), -127.0f, 127.0f);
+            pk |= ((uint32_t)(int)y & 0xffu) << (8 * r);
+        }
+    }
+    *(uint32_t*)((int8_t*)p.out + b * p.Np + n0) = pk;
+}
+
 template <int EL, int EPI>
 static hipError_t gemm_go(const GemmParams& p, dim3 grid, hipStream_t s) {
     constexpr size_t lds = GM_NT * GM_KS * 1024;
@@ -251,6 +345,12 @@ static hipError_t gemm_go(const GemmParams& p, dim3 grid, hipStream_t s) {
 hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
     dim3 grid((unsigned)((p.B + GM_ROWS - 1) / GM_ROWS), (unsigned)((p.n_tiles + GM_NT - 1) / GM_NT));
+    if (el == EL_I8 && epi == EPI_REQUANT && (int64_t)grid.x * grid.y < 128 && p.k_steps >= 8) {
+        // fewer than 128 workgroups of the large kernel: split K over the wavefronts instead
+        dim3 gs((unsigned)((p.B + 15) / 16), (unsigned)((p.n_tiles + GS_NT - 1) / GS_NT));
+        gemm_small_i8_kernel<<<gs, dim3(256), 0, s>>>(p);
+        return hipGetLastError();
+    }
     if (el == EL_I8 && epi == EPI_REQUANT) return gemm_go<EL_I8, EPI_REQUANT>(p, grid, s);
     if (el == EL_I8 && epi == EPI_HEADS_I8) return gemm_go<EL_I8, EPI_HEADS_I8>(p, grid, s);
     if (el == EL_BF16 && epi == EPI_BF16) return gemm_go<EL_BF16, EPI_BF16>(p, grid, s);
