@@ -398,7 +398,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
                 if (!conv_wp_available(el, NT, RD, pt, gg * units_img)) continue;
                 const int tiles = (gg * n_pix + 15) / 16, slots = (tiles + pt - 1) / pt * pt;
                 const double util = (double)gg * n_pix / (slots * 16.0);
-                if (util > best + 1e-9 || (util > best - 1e-9 && gg > wp_G)) { best = util; wp_G = gg; wp_PT = pt; wp_wave_tiles = wt; }
+                if (util > best + 1e-9) { best = util; wp_G = gg; wp_PT = pt; wp_wave_tiles = wt; }
             }
         }
     }

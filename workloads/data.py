@@ -117,6 +117,7 @@ def make_frames_u8(B, C=4, H=84, W=84, stream=STREAM["states"], first=0, n_rect=
             idx = (np.arange(p0, p0 + npl, dtype=np.int64) * n_rect + r) * 5
             rw = (_gather(seed, rstream, idx) % np.uint64(37)).astype(np.int64) + 4
             rh = (_gather(seed, rstream, idx + 1) % np.uint64(37)).astype(np.int64) + 4
+            rw, rh = np.minimum(rw, W), np.minimum(rh, H)      # frames smaller than a rectangle: cut it to the frame
             x0 = (_gather(seed, rstream, idx + 2) % (W - rw + 1).astype(np.uint64)).astype(np.int64)
             y0 = (_gather(seed, rstream, idx + 3) % (H - rh + 1).astype(np.uint64)).astype(np.int64)
             val = (_gather(seed, rstream, idx + 4) >> np.uint64(56)).astype(np.uint8)
