@@ -91,6 +91,21 @@ __device__ __forceinline__ uint32_t pack_low_bytes(const int (&q)[4]) {
     return lo | hi;
 }
 
+// Copy n16 16-byte units from memory to LDS with `nthr` lanes: eight loads per lane are in flight before
+// the first LDS store (a plain copy loop would wait for every load in turn).
+__device__ __forceinline__ void lds_copy16(char* dst, const void* src, int n16, int tid, int nthr) {
+    for (int base = 0; base < n16; base += 8 * nthr) {
+        v4i r[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r[k] = ((const v4i*)src)[min(base + k * nthr + tid, n16 - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = base + k * nthr + tid;
+            if (i < n16) ((v4i*)dst)[i] = r[k];
+        }
+    }
+}
+
 __device__ __forceinline__ void conv_wave_fence() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -140,14 +155,21 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
 #pragma unroll
             for (int t = 0; t < NT; ++t) wreg[st][t] = ((const v4i*)p.wfrag)[(st * NT + t) * 64 + lane];
         }
-    } else {
-        for (int i = tid; i < p.w_bytes / 16; i += CONV_THREADS) ((v4i*)wl)[i] = ((const v4i*)p.wfrag)[i];
-        for (int i = tid; i < p.k_steps * 4; i += CONV_THREADS) koff_lds[i] = chunk_off(i);
     }
-    {
+    // LDS set-up (weights, chunk offsets, constants, padding fill): run after the first batch's loads have
+    // been issued, so that their latency and the weights' overlap
+    auto setup_lds = [&]() {
+        if constexpr (KS == 0) {
+            lds_copy16(wl, p.wfrag, p.w_bytes / 16, tid, CONV_THREADS);
+            for (int i = tid; i < p.k_steps * 4; i += CONV_THREADS) koff_lds[i] = chunk_off(i);
+            for (int i = tid; i < NT * 16; i += CONV_THREADS) {
+                ((int*)cst_lds)[i] = ((const int*)p.bias)[i];
+                if constexpr (EL == EL_I8) ((float*)cst_lds)[NT * 16 + i] = p.mult[i];
+            }
+        }
         const int padv = (EL == EL_I8 && p.src_u8) ? (int)0x80808080u : 0;
         for (int i = tid; i < p.lds_tiles / 4; i += CONV_THREADS) ((int*)tiles_all)[i] = padv;
-    }
+    };
 
     // per-lane epilogue constants: channels 4*NT*g .. 4*NT*g + 4*NT - 1.  Register-weight kernels keep
     // them in registers; LDS-weight kernels (short on registers) keep them in LDS and fetch them per tile.
@@ -164,11 +186,6 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
             } else {
                 bfl[t] = *(const v4f*)((const float*)p.bias + 4 * NT * g + 4 * t);
             }
-        }
-    } else {
-        for (int i = tid; i < NT * 16; i += CONV_THREADS) {
-            ((int*)cst_lds)[i] = ((const int*)p.bias)[i];
-            if constexpr (EL == EL_I8) ((float*)cst_lds)[NT * 16 + i] = p.mult[i];
         }
     }
     const v4i* bias_l = (const v4i*)(cst_lds + (4 * NT * g) * 4);              // [t] -> bias of channels 4NTg+4t..
@@ -355,6 +372,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     int64_t batch = WP ? (int64_t)blockIdx.y * NW + wave : blockIdx.y;
     const int64_t bstride = WP ? (int64_t)gridDim.y * NW : gridDim.y;
     if (batch < n_batch) prefetch(batch);
+    setup_lds();
     __syncthreads();   // padding fill (and LDS weights) visible before the first commit / compute
     for (; batch < n_batch; batch += bstride) {
         commit(batch);

@@ -40,17 +40,20 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
 #pragma unroll
         for (int t = 0; t < NTA; ++t) wregA[st][t] = ((const v4i*)a.wfrag)[(st * NTA + t) * 64 + lane];
     }
-    for (int i = tid; i < b.w_bytes / 16; i += 256) ((v4i*)wl)[i] = ((const v4i*)b.wfrag)[i];
-    for (int i = tid; i < b.k_steps * 4; i += 256) {
-        const int ky = i / b.cpr, cx = i - ky * b.cpr;
-        koffB[i] = (ky < b.k) ? ky * b.pitch + cx * 16 : 0;
-    }
-    for (int i = tid; i < 64; i += 256) {
-        ((int*)cstB)[i] = ((const int*)b.bias)[i];
-        ((float*)cstB)[64 + i] = b.mult[i];
-    }
-    for (int i = tid; i < (a.tile_stride + 32) / 4; i += 256) ((int*)tileA)[i] = (int)0x80808080u;   // obs - 128 of a zero
-    for (int i = tid; i < 8; i += 256) ((int*)(tileB + tileB_bytes))[i] = 0;                          // read slack
+    // LDS set-up, run after the first observation's loads have been issued (their latencies overlap)
+    auto setup_lds = [&]() {
+        lds_copy16(wl, b.wfrag, b.w_bytes / 16, tid, 256);
+        for (int i = tid; i < b.k_steps * 4; i += 256) {
+            const int ky = i / b.cpr, cx = i - ky * b.cpr;
+            koffB[i] = (ky < b.k) ? ky * b.pitch + cx * 16 : 0;
+        }
+        for (int i = tid; i < 64; i += 256) {
+            ((int*)cstB)[i] = ((const int*)b.bias)[i];
+            ((float*)cstB)[64 + i] = b.mult[i];
+        }
+        for (int i = tid; i < (a.tile_stride + 32) / 4; i += 256) ((int*)tileA)[i] = (int)0x80808080u;   // obs - 128 of a zero
+        for (int i = tid; i < 8; i += 256) ((int*)(tileB + tileB_bytes))[i] = 0;                          // read slack
+    };
     v4i biA[NTA];
     v4f mlA[NTA];
 #pragma unroll
@@ -117,6 +120,7 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
 
     int64_t img = blockIdx.x;
     if (img < a.B) prefetch(img);
+    setup_lds();
     __syncthreads();
     for (; img < a.B; img += gridDim.x) {
         commit();
