@@ -13,7 +13,8 @@ namespace accerl {
 constexpr int GM_THREADS = 256;
 constexpr int GM_NT = 4;          // feature tiles (of 16) per workgroup
 constexpr int GM_RT = 1;          // row tiles (of 16 states) per wave
-constexpr int GM_ROWS = 64 * GM_RT;   // states per workgroup
+constexpr int GM_WAVES = GM_THREADS / 64;
+constexpr int GM_ROWS = 16 * GM_WAVES * GM_RT;   // states per workgroup
 constexpr int GM_KS = 4;          // MFMA steps per LDS stage (64 bytes of K each); a multiple of 4
 
 __device__ __forceinline__ uint32_t g_relu_i8x4(uint32_t x) {
@@ -33,7 +34,7 @@ __device__ __forceinline__ uint32_t g_f2bf(float x) {
 __device__ __forceinline__ float g_sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
 
 template <int EL, int EPI>
-__global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p) {
+__global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char gm_smem[];
     char* s_w = gm_smem;                              // [GM_NT][GM_KS][64 lanes][16 B]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -74,8 +75,8 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
     auto prefetch = [&](int s0) {
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
 #pragma unroll
-        for (int r = 0; r < WPRE; ++r) {                         // unit r: tile r % GM_NT, step wave + 4 * (r / GM_NT)
-            const int tr = r % GM_NT, sr = wave + 4 * (r / GM_NT);
+        for (int r = 0; r < WPRE; ++r) {                         // unit r of a lane: (tile, step) pair number wave + GM_WAVES * r
+            const int tr = (wave + GM_WAVES * r) % GM_NT, sr = (wave + GM_WAVES * r) / GM_NT;
             const int t = (tr < nts) ? tr : 0, st = (sr < ns) ? sr : 0;
             wpre[r] = ((const v4i*)p.wfrag)[((int64_t)(nt0 + t) * p.k_steps + s0 + st) * 64 + lane];
         }
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(GM_THREADS, 2) void gemm_kernel(const GemmParams p)
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
 #pragma unroll
         for (int r = 0; r < WPRE; ++r) {
-            const int tr = r % GM_NT, sr = wave + 4 * (r / GM_NT);
+            const int tr = (wave + GM_WAVES * r) % GM_NT, sr = (wave + GM_WAVES * r) / GM_NT;
             v4i v = wpre[r];
             if (!(tr < nts && sr < ns)) v = (v4i){0, 0, 0, 0};
             ((v4i*)s_w)[(tr * GM_KS + sr) * 64 + lane] = v;
