@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="only the headline workload")
     ap.add_argument("--paper-nets", action="store_true",
                     help="also time the paper's own networks (network table: Original with FC 2048, Net1-Net3)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also measure what this machine sustains: register-resident MFMA loops and a streaming copy")
     ap.add_argument("--copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference for HBM counters)")
     args = ap.parse_args()
@@ -249,6 +251,28 @@ def main():
                                              frac_hbm_peak=round(kl_bytes / t_kl / PEAK["hbm"], 4))
             extra["vtrace" + tag] = dict(T=Tn, B=B, actions=nA, us=round(t_vt * 1e6, 2), gbps=round(vt_bytes / t_vt / 1e9, 1),
                                          frac_hbm_peak=round(vt_bytes / t_vt / PEAK["hbm"], 4))
+
+    if args.ceilings:
+        def span(fn, n=10):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / n
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        iters = 4000
+        waves = 2048 * 4
+        t_i8 = span(lambda: A.accerl_probe_mfma(0, iters, sink))
+        t_bf = span(lambda: A.accerl_probe_mfma(1, iters, sink))
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        t_cp = span(lambda: A.accerl_probe_copy(src, dst))
+        extra["ceilings"] = dict(int8_mfma_tops=round(waves * iters * 8 * 2 * 16 * 16 * 64 / t_i8 / 1e12, 1),
+                                 bf16_mfma_tflops=round(waves * iters * 8 * 2 * 16 * 16 * 32 / t_bf / 1e12, 1),
+                                 copy_1gib_read_plus_write_gbps=round(2 * (1 << 30) / t_cp / 1e9, 1))
+        del src, dst
 
     if args.paper_nets:
         # the networks of the paper's table (Section 3.1), each as int8 and bf16, at the paper's batch of 160

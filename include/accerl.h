@@ -272,6 +272,16 @@ int accerl_vtrace(const float* logits_original, const float* logits_smaller, con
                   int64_t T, int64_t B, int A, float rho_bar, float c_bar,
                   float* out_vs, float* out_pg_adv, float* out_rho, void* hip_stream);
 
+/*
+ * Measurement aids (not part of the method): the ceilings the kernels are compared with, as this machine
+ * sustains them.  accerl_probe_mfma runs 2048 workgroups x 4 wavefronts, each issuing iters x 8 independent
+ * 16x16 MFMAs on registers (int8 16x16x64, or bf16 16x16x32 if bf16 != 0): ops = 2048 * 4 * iters * 8 *
+ * 2 * 16*16*K.  accerl_probe_copy streams `bytes` (a multiple of 16) from src to dst with 16-byte
+ * loads and stores.  Both asynchronous on hip_stream; the caller times them.  sink: DEVICE int32[1].
+ */
+int accerl_probe_mfma(int32_t bf16, int32_t iters, int32_t* sink, void* hip_stream);
+int accerl_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
+
 /* Message of the last error on this thread ("" if none). */
 const char* accerl_last_error(void);
 

@@ -58,6 +58,10 @@ def load_library():
     lib.accerl_monitor_kl.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
     lib.accerl_vtrace.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, C.c_float, C.c_float, vp, vp, vp, vp]
     lib.accerl_monitor_kl.restype = C.c_int
+    lib.accerl_probe_mfma.argtypes = [i32, i32, vp, vp]
+    lib.accerl_probe_mfma.restype = C.c_int
+    lib.accerl_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.accerl_probe_copy.restype = C.c_int
     lib.accerl_actor_forward_mixture.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.accerl_actor_forward_mixture.restype = C.c_int
     lib.accerl_mixture_alpha.argtypes = [C.c_double, C.c_double, C.c_double]
@@ -235,6 +239,16 @@ def accerl_actor_forward_mixture(smaller, original, states, uniforms, use_smalle
 
 def accerl_mixture_alpha(kl_mean, kl_lo, kl_hi):
     return float(load_library().accerl_mixture_alpha(kl_mean, kl_lo, kl_hi))
+
+
+def accerl_probe_mfma(bf16, iters, sink, stream=None):
+    import torch
+    _check(load_library().accerl_probe_mfma(int(bool(bf16)), int(iters), _ptr(sink, torch.int32), _stream(stream)))
+
+
+def accerl_probe_copy(src, dst, stream=None):
+    n = src.numel() * src.element_size()
+    _check(load_library().accerl_probe_copy(_ptr(src), _ptr(dst), n, _stream(stream)))
 
 
 def accerl_monitor_kl(logits_original, logits_smaller, out_kl, out_entropy, out_stats, stream=None):
