@@ -37,7 +37,8 @@ template <int EL, int EPI>
 __global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char gm_smem[];
     char* s_w = gm_smem;                              // [GM_NT][GM_KS][64 lanes][16 B]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: what depends on it stays scalar
     const int j = lane & 15, g = lane >> 4;
     const int64_t b0 = (int64_t)blockIdx.x * GM_ROWS;
     const int nt0 = blockIdx.y * GM_NT;
@@ -63,13 +64,11 @@ __global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_ke
     // addresses, fixed up afterwards) so that nothing serialises them.
     constexpr int WPRE = GM_NT * GM_KS * 64 / GM_THREADS;       // weight units per lane
     v4i wpre[WPRE], xpre[GM_RT][GM_KS], xcur[GM_RT][GM_KS];
-    bool row_live[GM_RT];
     const char* xptr[GM_RT];
 #pragma unroll
     for (int u = 0; u < GM_RT; ++u) {
         int64_t xrow = b0 + (wave * GM_RT + u) * 16 + j;
-        row_live[u] = xrow < p.B;
-        if (!row_live[u]) xrow = p.B - 1;
+        if (xrow >= p.B) xrow = p.B - 1;        // a state past the batch re-reads the last one; its results are not stored
         xptr[u] = (const char*)p.x + xrow * p.Kp_bytes;
     }
     auto prefetch = [&](int s0) {
@@ -97,6 +96,15 @@ __global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_ke
             if (!(tr < nts && sr < ns)) v = (v4i){0, 0, 0, 0};
             ((v4i*)s_w)[(tr * GM_KS + sr) * 64 + lane] = v;
         }
+        // only the stage that reaches the end of the rows needs the chunk fix-ups (states past the batch
+        // need none: their results are never stored)
+        if ((s0 + GM_KS) * 64 <= p.Kp_bytes && !p.relu_in) {
+#pragma unroll
+            for (int st = 0; st < GM_KS; ++st)
+#pragma unroll
+                for (int u = 0; u < GM_RT; ++u) xcur[u][st] = xpre[u][st];
+            return;
+        }
 #pragma unroll
         for (int st = 0; st < GM_KS; ++st)
 #pragma unroll
@@ -105,7 +113,7 @@ __global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_ke
             v4i v = xpre[u][st];
             // a chunk that starts inside the row but runs past it re-read the row's last 16 bytes: rebuild
             // it from the bytes that belong to it (rows are padded with zero weights, not zero data)
-            if (!row_live[u] || kb >= p.Kp_bytes) {
+            if (kb >= p.Kp_bytes) {
                 v = (v4i){0, 0, 0, 0};
             } else if (kb > p.Kp_bytes - 16) {
                 const int have = p.Kp_bytes - kb;              // 4, 8 or 12 valid bytes, at the end of v
