@@ -129,7 +129,8 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int ESZ = (EL == EL_I8) ? 1 : 2;
     constexpr int KSR = KS > 0 ? KS : 1;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: what depends on it stays scalar
     const bool has_res = EX && p.res != nullptr, do_pool = EX && p.pool != 0;
     const int j = lane & 15, g = lane >> 4;
     const int pix = p.Cs_in * ESZ;                          // bytes per stored input pixel

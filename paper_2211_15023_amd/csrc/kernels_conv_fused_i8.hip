@@ -20,7 +20,8 @@ constexpr int FUSED_PF = 8;     // staging units per lane (256 lanes): observati
 template <int NTA, int KSA>
 __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, const ConvParams b) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: what depends on it stays scalar
     const int j = lane & 15, g = lane >> 4;
     char* wl = smem;                                             // conv B weight fragments
     int* koffB = (int*)(smem + b.w_bytes);                       // conv B chunk offsets
