@@ -16,6 +16,8 @@
 namespace accerl {
 
 constexpr int FUSED_PF = 8;     // staging units per lane (256 lanes): observations up to 2048 units
+constexpr int FUSED_ITA = 4;    // phase A rounds per observation: first-layer outputs up to 4 * 8 * 16 = 512 pixels
+constexpr int FUSED_ITB = 2;    // phase B items per wavefront: second-layer outputs up to 2 * 2 * 48 = 192 pixels
 
 template <int NTA, int KSA>
 __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, const ConvParams b) {
@@ -119,6 +121,28 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
     const int rowA = a.s * a.pitch, colA = a.sx * pixA;
     const int rowB = b.s * b.pitch, colB = b.sx * b.Cs_in;
 
+    // Which pixels a lane works on, and where they sit in the LDS tiles, is the same for every observation:
+    // worked out once (phase A: up to FUSED_ITA rounds of two tiles per wavefront; phase B: up to FUSED_ITB
+    // items of three tiles).
+    int pbA[FUSED_ITA][2];
+#pragma unroll
+    for (int r = 0; r < FUSED_ITA; ++r)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int pc = min((wave * 2 + 8 * r + u) * 16 + j, npixA - 1);
+            const int ty = qdiv(pc, a.inv_wo, a.hinv_wo), ox = pc - __mul24(ty, a.Wo);
+            pbA[r][u] = __mul24(ty, rowA) + __mul24(ox, colA);
+        }
+    int pbB[FUSED_ITB][3];
+#pragma unroll
+    for (int r = 0; r < FUSED_ITB; ++r)
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const int pc = min((((wave + 4 * r) >> 1) * 3 + u) * 16 + j, npixB - 1);
+            const int ty = qdiv(pc, b.inv_wo, b.hinv_wo), ox = pc - __mul24(ty, b.Wo);
+            pbB[r][u] = __mul24(ty, rowB) + __mul24(ox, colB);
+        }
+
     int64_t img = blockIdx.x;
     if (img < a.B) prefetch(img);
     setup_lds();
@@ -129,14 +153,15 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
         if (img + gridDim.x < a.B) prefetch(img + gridDim.x);
 
         // ---- phase A: conv A -> tile B (two pixel tiles per wavefront and step)
-        for (int t0 = wave * 2; t0 < tilesA; t0 += 8) {
+#pragma unroll
+        for (int r = 0; r < FUSED_ITA; ++r) {
+            const int t0 = wave * 2 + 8 * r;
+            if (t0 >= tilesA) break;
             int pb[2], pp[2];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 pp[u] = (t0 + u) * 16 + j;
-                const int pc = min(pp[u], npixA - 1);
-                const int ty = qdiv(pc, a.inv_wo, a.hinv_wo), ox = pc - __mul24(ty, a.Wo);
-                pb[u] = __mul24(ty, rowA) + __mul24(ox, colA);
+                pb[u] = pbA[r][u];
             }
             v4i acc[2][NTA];
 #pragma unroll
@@ -189,16 +214,17 @@ __global__ __launch_bounds__(256, 2) void conv_fused_kernel(const ConvParams a, 
         // six MFMAs per step, and a 9x9 output (six tiles) is exactly one item per wavefront
         char* outB = (char*)b.out + img * (int64_t)npixB * b.Cs_out;
         const int itemsB = 2 * ((tilesB + 2) / 3);
-        for (int it = wave; it < itemsB; it += 4) {
+#pragma unroll
+        for (int r = 0; r < FUSED_ITB; ++r) {
+            const int it = wave + 4 * r;
+            if (it >= itemsB) break;
             const int h = it & 1, tile0 = (it >> 1) * 3;
             int pp[3];
             const char* base[3];
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 pp[u] = (tile0 + u) * 16 + j;
-                const int pc = min(pp[u], npixB - 1);
-                const int ty = qdiv(pc, b.inv_wo, b.hinv_wo), ox = pc - __mul24(ty, b.Wo);
-                base[u] = tileB + __mul24(ty, rowB) + __mul24(ox, colB);
+                base[u] = tileB + pbB[r][u];
             }
             v4i acc[3][2];
 #pragma unroll
@@ -250,6 +276,7 @@ bool conv_fused_supported(const ConvParams& a, int NTA, int KSA, int RDA, const 
     if (!a.src_u8 || a.mode != CM_U8T || a.n_bands != 1 || a.pool || a.wave_private || KSA != 4 || a.k_steps != 4 || RDA != 16) return false;
     if (NTA != 1 && NTA != 2) return false;
     if (a.units_img > 256 * FUSED_PF || (a.Cs_out & 3)) return false;
+    if (a.Ho * a.Wo > FUSED_ITA * 8 * 16 || b.Ho * b.Wo > FUSED_ITB * 2 * 48) return false;
     if (b.mode != CM_FLAT || b.n_bands != 1 || b.pool || b.relu_in || b.src_u8 || NTB != 4 || KSB != 0 || RDB != 16) return false;
     if (b.Cs_out != 64 || b.Cs_in != a.Cs_out || b.H != a.Ho || b.W * b.Cs_in != a.Wo * a.Cs_out) return false;
     if (a.Ho * a.Wo * a.Cs_out >= (1 << 23) || b.Ho * b.Wo * b.Cs_out >= (1 << 23)) return false;
