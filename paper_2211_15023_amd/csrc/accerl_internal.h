@@ -91,6 +91,7 @@ struct ConvParams {
     int pool_W;              // conv output pixels per row as stored (before any pixel packing)
     int pool_unit, pool_ush; // bytes per pooling unit (8 or 16), log2 of units per stored pixel
     int lds_otile;           // LDS bytes for the conv rows of a batch
+    int lds_tab;             // LDS bytes of the pixel table of a thin layer (0 = none)
     float inv_prow, hinv_prow;   // 1/d and 0.5/d for d = pooling units per pooled row
     float r;                 // residual ratio (int8 path)
 };

@@ -351,7 +351,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     if (pool && ((pool_pix % 8) != 0 || (pool_unit << pool_ush) != pool_pix || res_buf >= 0)) pool = false;
     const int PH = pool ? out_hw(Ho, 3, 2, 1) : 0, PW = pool ? out_hw(Wo_img, 3, 2, 1) : 0;
     auto conv_rows = [&](int tph) { return 2 * tph + 1 < Ho ? 2 * tph + 1 : Ho; };
-    auto otile_of = [&](int th) { return pool ? th * Wo_img * pool_pix : 0; };
+    auto otile_of = [&](int th) { return (pool ? th * Wo_img * pool_pix : 0) + (NT == 1 ? 8 * th * Wo + 16 : 0); };   // + a thin layer's pixel table
     int TH = Ho, TPH = PH;
     if (pool) {
         if (!whole)
@@ -363,7 +363,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         if (units_of(TH) > 4096 || w_lds_max + tile_of(TH) + otile_of(TH) + 32 > lds_cap) { pool = false; TH = Ho; TPH = 0; }
     }
     if (!pool && !whole) {
-        while (TH > 1 && (units_of(TH) > band_units || w_lds_max + tile_of(TH) + 32 > budget)) --TH;
+        while (TH > 1 && (units_of(TH) > band_units || w_lds_max + tile_of(TH) + otile_of(TH) + 32 > budget)) --TH;
         const int nb = (Ho + TH - 1) / TH;
         TH = (Ho + nb - 1) / nb;
     }
@@ -421,7 +421,8 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     if ((int64_t)G * n_pix >= (1 << 20) || (int64_t)Ho * Wo >= (1 << 20) || tile_stride >= (1 << 23) || (int64_t)ss * pitch >= (1 << 23))
         return fail(ACCERL_EUNSUPPORTED, "layer %d: image too large for the pixel index arithmetic", layer);
     c.pool = pool ? 1 : 0; c.pool_out = nullptr; c.PH = PH; c.PW = PW; c.TPH = TPH; c.pool_W = Wo_img;
-    c.pool_unit = pool_unit; c.pool_ush = pool_ush; c.lds_otile = G * otile_of(TH);
+    c.pool_unit = pool_unit; c.pool_ush = pool_ush; c.lds_otile = pool ? G * TH * Wo_img * pool_pix : 0;
+    c.lds_tab = (NT == 1 && !wp_G) ? (int)up((int64_t)8 * G * n_pix, 16) : 0;
     if (pool) { const int rowu = PW << pool_ush; c.inv_prow = 1.0f / (float)rowu; c.hinv_prow = 0.5f / (float)rowu; }
     st.pool_buf = pool ? pool_buf : -1;
     c.inv_wo = 1.0f / (float)Wo; c.hinv_wo = 0.5f / (float)Wo;
@@ -1259,7 +1260,7 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
         const Step& s = pol.steps[i];
         if (s.kind == ST_CONV) {
             const ConvParams& c = s.cp;
-            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles + (c.pool ? c.lds_otile : 0);
+            const long lds = (s.KS > 0 ? 0 : c.w_bytes + c.k_steps * 16 + CONV_LDS_CONST) + (long)c.lds_tiles + (c.pool ? c.lds_otile : 0) + c.lds_tab;
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
                      "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d fuse_next=%d\n",

@@ -205,6 +205,12 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     const float inv_npix = 1.0f / (float)n_pix, hinv_npix = 0.5f / (float)n_pix;
     char* otile = tiles_all + p.lds_tiles;                       // pooling: requantized conv rows of the batch
     const int otile_px = p.TH * p.Wo;                            // pixels per image in otile
+    // Thin layers keep a table of their pixels in LDS: pixel number of a batch -> (offset of its window in the
+    // input tiles, output pixel number).  It is the same for every batch, and one 8-byte read per tile
+    // replaces the reciprocal arithmetic below, which is a third of such a layer's vector instructions.
+    constexpr bool TAB = (NT == 1 && !WP);
+    typedef int v2i_t __attribute__((ext_vector_type(2)));
+    v2i_t* ptab = (v2i_t*)(otile + (p.pool ? p.lds_otile : 0));
     const int row_bytes_img = p.W * pix;
     const int lead = p.pad * pix;
     const int64_t n_batch = (p.B + p.G - 1) / p.G;
@@ -374,6 +380,15 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     const int64_t bstride = WP ? (int64_t)gridDim.y * NW : gridDim.y;
     if (batch < n_batch) prefetch(batch);
     setup_lds();
+    if constexpr (TAB) {
+        for (int pp = tid; pp < p.G * n_pix; pp += CONV_THREADS) {
+            const int img = qdiv(pp, inv_npix, hinv_npix);
+            const int rem = pp - __mul24(img, n_pix);
+            const int ty = qdiv(rem, p.inv_wo, p.hinv_wo), ox = rem - __mul24(ty, p.Wo);
+            ptab[pp] = (v2i_t){__mul24(img, p.tile_stride) + __mul24(ty, row_step) + __mul24(ox, col_step),
+                               do_pool ? __mul24(img, otile_px) + rem : pp + __mul24(img, band_skip)};
+        }
+    }
     __syncthreads();   // padding fill (and LDS weights) visible before the first commit / compute
     for (; batch < n_batch; batch += bstride) {
         commit(batch);
@@ -395,6 +410,11 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                 int pp = (t0 + u) * 16 + j;
                 ppix[u] = pp;
                 if (pp >= total_pix) pp = total_pix - 1;     // clamp to a valid pixel; result not stored
+                if constexpr (TAB) {
+                    const v2i_t e = ptab[pp];
+                    pb[u] = e[0]; pimg[u] = 0; prel[u] = e[1];
+                    continue;
+                }
                 // pixel -> (image, row, column): reciprocal multiplies and 24-bit integer multiplies, which
                 // issue at full rate (32-bit integer multiplies take four times as long)
                 const int img = qdiv(pp, inv_npix, hinv_npix);

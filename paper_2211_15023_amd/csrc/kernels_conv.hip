@@ -48,7 +48,7 @@ bool conv_wp_available(Elem el, int NT, int RD, int PT, int units) {
 
 hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
-    const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16 + CONV_LDS_CONST) + (size_t)p.lds_tiles + (size_t)(p.pool ? p.lds_otile : 0);
+    const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16 + CONV_LDS_CONST) + (size_t)p.lds_tiles + (size_t)(p.pool ? p.lds_otile : 0) + (size_t)p.lds_tab;
     dim3 grid((unsigned)p.n_bands, 1);
     if (p.wave_private) {
         if (KS != 0 || p.mode != CM_FLAT || p.res || p.pool || p.n_bands != 1 || p.G * p.units_img > 64 * CONV_WP_PF) return hipErrorInvalidValue;
