@@ -351,7 +351,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     if (pool && ((pool_pix % 8) != 0 || (pool_unit << pool_ush) != pool_pix || res_buf >= 0)) pool = false;
     const int PH = pool ? out_hw(Ho, 3, 2, 1) : 0, PW = pool ? out_hw(Wo_img, 3, 2, 1) : 0;
     auto conv_rows = [&](int tph) { return 2 * tph + 1 < Ho ? 2 * tph + 1 : Ho; };
-    auto otile_of = [&](int th) { return (pool ? th * Wo_img * pool_pix : 0) + (NT == 1 ? 8 * th * Wo + 16 : 0); };   // + a thin layer's pixel table
+    auto otile_of = [&](int th) { return (pool ? th * Wo_img * pool_pix : 0) + 8 * th * Wo + 16; };   // + the pixel table
     int TH = Ho, TPH = PH;
     if (pool) {
         if (!whole)
@@ -393,7 +393,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         double best = -1.0;
         for (int gg = 1; gg <= 8; ++gg) {
             const int wt = (int)up((int64_t)gg * tile_stride + 32, 16);
-            if (w_lds_max + CONV_WP_NWAVES * wt > lds_cap) break;
+            if (w_lds_max + CONV_WP_NWAVES * wt + 8 * gg * n_pix + 16 > lds_cap) break;
             for (int pt = 4; pt >= 3; --pt) {
                 if (!conv_wp_available(el, NT, RD, pt, gg * units_img)) continue;
                 const int tiles = (gg * n_pix + 15) / 16, slots = (tiles + pt - 1) / pt * pt;
@@ -422,7 +422,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         return fail(ACCERL_EUNSUPPORTED, "layer %d: image too large for the pixel index arithmetic", layer);
     c.pool = pool ? 1 : 0; c.pool_out = nullptr; c.PH = PH; c.PW = PW; c.TPH = TPH; c.pool_W = Wo_img;
     c.pool_unit = pool_unit; c.pool_ush = pool_ush; c.lds_otile = pool ? G * TH * Wo_img * pool_pix : 0;
-    c.lds_tab = (NT == 1 && !wp_G) ? (int)up((int64_t)8 * G * n_pix, 16) : 0;
+    c.lds_tab = (int)up((int64_t)8 * G * n_pix, 16);
     if (pool) { const int rowu = PW << pool_ush; c.inv_prow = 1.0f / (float)rowu; c.hinv_prow = 0.5f / (float)rowu; }
     st.pool_buf = pool ? pool_buf : -1;
     c.inv_wo = 1.0f / (float)Wo; c.hinv_wo = 0.5f / (float)Wo;

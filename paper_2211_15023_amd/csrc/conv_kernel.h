@@ -205,10 +205,9 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     const float inv_npix = 1.0f / (float)n_pix, hinv_npix = 0.5f / (float)n_pix;
     char* otile = tiles_all + p.lds_tiles;                       // pooling: requantized conv rows of the batch
     const int otile_px = p.TH * p.Wo;                            // pixels per image in otile
-    // Thin layers keep a table of their pixels in LDS: pixel number of a batch -> (offset of its window in the
-    // input tiles, output pixel number).  It is the same for every batch, and one 8-byte read per tile
-    // replaces the reciprocal arithmetic below, which is a third of such a layer's vector instructions.
-    constexpr bool TAB = (NT == 1 && !WP);
+    // A table of the batch's pixels in LDS: pixel number -> (offset of its window in the input tiles, output
+    // pixel number).  It is the same for every batch, and one 8-byte read per tile replaces the reciprocal
+    // arithmetic that fills it (a third of a thin layer's vector instructions).
     typedef int v2i_t __attribute__((ext_vector_type(2)));
     v2i_t* ptab = (v2i_t*)(otile + (p.pool ? p.lds_otile : 0));
     const int row_bytes_img = p.W * pix;
@@ -380,7 +379,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
     const int64_t bstride = WP ? (int64_t)gridDim.y * NW : gridDim.y;
     if (batch < n_batch) prefetch(batch);
     setup_lds();
-    if constexpr (TAB) {
+    {
         for (int pp = tid; pp < p.G * n_pix; pp += CONV_THREADS) {
             const int img = qdiv(pp, inv_npix, hinv_npix);
             const int rem = pp - __mul24(img, n_pix);
@@ -404,26 +403,14 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
         const char* res_b = (const char*)p.res + base_el * ESZ;
         int32_t* tap_b = p.tap_acc + base_el;
         for (int t0 = (WP ? 0 : wave * PT); t0 < n_tiles; t0 += (WP ? 1 : NW) * PT) {
-            int pb[PT], pimg[PT], ppix[PT], prel[PT];   // tile-relative pixel offset, tile offset, pixel number, output pixel
+            int pb[PT], ppix[PT], prel[PT];   // window offset in the tiles, pixel number, output pixel
 #pragma unroll
             for (int u = 0; u < PT; ++u) {
-                int pp = (t0 + u) * 16 + j;
+                const int pp = (t0 + u) * 16 + j;
                 ppix[u] = pp;
-                if (pp >= total_pix) pp = total_pix - 1;     // clamp to a valid pixel; result not stored
-                if constexpr (TAB) {
-                    const v2i_t e = ptab[pp];
-                    pb[u] = e[0]; pimg[u] = 0; prel[u] = e[1];
-                    continue;
-                }
-                // pixel -> (image, row, column): reciprocal multiplies and 24-bit integer multiplies, which
-                // issue at full rate (32-bit integer multiplies take four times as long)
-                const int img = qdiv(pp, inv_npix, hinv_npix);
-                const int rem = pp - __mul24(img, n_pix);
-                const int ty = qdiv(rem, p.inv_wo, p.hinv_wo), ox = rem - __mul24(ty, p.Wo);
-                pb[u] = __mul24(ty, row_step) + __mul24(ox, col_step);
-                pimg[u] = __mul24(img, p.tile_stride);
-                // output pixel relative to the first one this workgroup writes for the batch (pooling: inside otile)
-                prel[u] = do_pool ? __mul24(img, otile_px) + rem : pp + __mul24(img, band_skip);   // (of the clamped pixel)
+                const v2i_t e = ptab[min(pp, total_pix - 1)];   // past the end: a valid pixel, result not stored
+                pb[u] = e[0];
+                prel[u] = e[1];
             }
             v4i acc_i[PT][NT];
             v4f acc_f[PT][NT];
@@ -453,7 +440,7 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
             }
             auto load_b = [&](v4i (&bq)[PT], int off) {
 #pragma unroll
-                for (int u = 0; u < PT; ++u) bq[u] = read_chunk<RD>(tiles + pimg[u] + pb[u] + off);
+                for (int u = 0; u < PT; ++u) bq[u] = read_chunk<RD>(tiles + pb[u] + off);
             };
             auto load_a = [&](v4i (&a)[NT], int st) {
 #pragma unroll
