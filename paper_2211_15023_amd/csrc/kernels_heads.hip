@@ -45,6 +45,7 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
 #pragma unroll
         for (int st = 0; st < KM; ++st)
             wa[t][st] = ((const v4i*)p.wfrag)[(t * p.k_steps + min(st, p.k_steps - 1)) * 64 + lane];
+    const bool whole_steps = (p.Kp_bytes & 63) == 0;   // uniform: skips the per-chunk fix-ups below
     v4i acc_i[NT];
     v4f acc_f[NT];
 #pragma unroll
@@ -57,7 +58,9 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
         if (st < p.k_steps) {
             const int kb = st * 64 + g * 16;
             v4i v = xb[st];
-            if (kb >= p.Kp_bytes) {
+            if (whole_steps) {
+                // rows are whole MFMA steps: no chunk reaches past the end
+            } else if (kb >= p.Kp_bytes) {
                 v = (v4i){0, 0, 0, 0};
             } else if (kb > p.Kp_bytes - 16) {
                 const int sh = (16 - (p.Kp_bytes - kb)) >> 2;
