@@ -109,10 +109,12 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (p.logits) {
-        const int64_t rows = (p.B - row0 < 16) ? (p.B - row0) : 16;
-        for (int64_t i = lane; i < rows * A; i += 64) {
-            const int rr = (int)(i / A), a = (int)(i - (int64_t)rr * A);
-            p.logits[row0 * A + i] = stage[rr * HD_PITCH + a];
+        const int rows = (int)((p.B - row0 < 16) ? (p.B - row0) : 16);
+        const float inv_A = 1.0f / (float)A;
+        float* dst = p.logits + row0 * A;
+        for (int i = lane; i < rows * A; i += 64) {
+            const int rr = (int)(((float)i + 0.5f) * inv_A), a = i - rr * A;   // i < 1024: the float quotient is exact
+            dst[i] = stage[rr * HD_PITCH + a];
         }
     }
     if (p.action) {

@@ -9,11 +9,29 @@
 
 namespace accerl {
 
-__device__ __forceinline__ int8_t quant_clamp(float y, float lo) {
-    float r = rintf(y);
-    r = fminf(r, 127.0f);
-    r = fmaxf(r, lo);
-    return (int8_t)(int)r;
+// clamp(rint(y), -127, 127) as the bits of y + 1.5 * 2^23 (the addition rounds to the nearest integer, ties
+// to even, into the low mantissa bits; float bit patterns order like the values, so an integer clamp also
+// catches every |y| too large for the trick); the caller keeps the low byte.
+__device__ __forceinline__ int m_rne_clamp127(float y) {
+    const int b = (int)__float_as_uint(y + 12582912.0f);
+    return min(max(b, 0x4B400000 - 127), 0x4B400000 + 127);
+}
+__device__ __forceinline__ uint32_t m_pack_low_bytes(const int (&q)[4]) {
+    return __builtin_amdgcn_perm((uint32_t)q[1], (uint32_t)q[0], 0x0c0c0400u) | __builtin_amdgcn_perm((uint32_t)q[3], (uint32_t)q[2], 0x04000c0cu);
+}
+// four requantized values -> four int8 in a dword: lower clamp 0 (fused ReLU: the pack instruction rounds to
+// nearest even and saturates at 0, the median caps at 127) or -127
+__device__ __forceinline__ uint32_t requant4(const float (&y)[4], bool relu) {
+    if (relu) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(y[r], 0.0f, 127.0f), r, w);
+        return w;
+    }
+    int q[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) q[r] = m_rne_clamp127(y[r]);
+    return m_pack_low_bytes(q);
 }
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -60,6 +78,7 @@ __global__ __launch_bounds__(MLP_WAVES * 64) void mlp_i8_kernel(MlpParams p) {
     const int64_t n_waves = (int64_t)gridDim.x * MLP_WAVES;
     float* stage = s_logits[wave];
     const int D = p.D, A = p.A;
+    const float inv_A = 1.0f / (float)A;
 
     for (int64_t tile = wave_id; tile < n_tiles; tile += n_waves) {
         const int64_t row = tile * 16 + j;
@@ -78,13 +97,10 @@ __global__ __launch_bounds__(MLP_WAVES * 64) void mlp_i8_kernel(MlpParams p) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) if (f0 + e < D) v[e] = src[f0 + e];
                 }
-                uint32_t pk = 0;
+                float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int8_t qv = (f0 + e < D) ? quant_clamp(v[e] * p.inv_s0, -127.0f) : (int8_t)0;
-                    pk |= (uint32_t)(uint8_t)qv << (8 * e);
-                }
-                x[q] = (int)pk;
+                for (int e = 0; e < 4; ++e) y[e] = v[e] * p.inv_s0;         // features past D are zeros: quantize to 0
+                x[q] = (int)requant4(y, false);
             }
         }
         if (p.tap_act && p.tap_layer == -1 && live) {
@@ -102,19 +118,19 @@ __global__ __launch_bounds__(MLP_WAVES * 64) void mlp_i8_kernel(MlpParams p) {
             v4i nx;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                v4i acc = {0, 0, 0, 0};
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[l][t], x, acc, 0, 0, 0);
-                uint32_t pk = 0;
+                // the bias rides in the accumulator
+                const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[l][t], x, bs[l][t], 0, 0, 0);
+                float y[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int v = acc[r] + bs[l][t][r];
-                    const int8_t qv = quant_clamp((float)v * ml[l][t][r], (float)p.lo[l]);
-                    pk |= (uint32_t)(uint8_t)qv << (8 * r);
-                    if (p.tap_layer == l && live) {
+                for (int r = 0; r < 4; ++r) y[r] = (float)acc[r] * ml[l][t][r];
+                const uint32_t pk = requant4(y, p.lo[l] == 0);
+                if (p.tap_layer == l && live) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
                         const int n = 16 * t + 4 * g + r;
                         if (n < p.tap_n) {
-                            if (p.tap_acc) p.tap_acc[row * p.tap_n + n] = v;
-                            if (p.tap_act) p.tap_act[row * p.tap_n + n] = qv;
+                            if (p.tap_acc) p.tap_acc[row * p.tap_n + n] = acc[r];
+                            if (p.tap_act) p.tap_act[row * p.tap_n + n] = (int8_t)(pk >> (8 * r));
                         }
                     }
                 }
@@ -125,12 +141,11 @@ __global__ __launch_bounds__(MLP_WAVES * 64) void mlp_i8_kernel(MlpParams p) {
         // ---- heads: logits and value from the accumulators
 #pragma unroll
         for (int t = 0; t < HT; ++t) {
-            v4i acc = {0, 0, 0, 0};
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(hw[t], x, acc, 0, 0, 0);
+            const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(hw[t], x, hb[t], 0, 0, 0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int n = 16 * t + 4 * g + r;
-                const int v = acc[r] + hb[t][r];
+                const int v = acc[r];
                 const float o = (float)v * hd[t][r];
                 if (n <= A) stage[j * MLP_LOGIT_PITCH + n] = o;
                 if (p.tap_layer == NH && p.tap_acc && live && n <= A) p.tap_acc[row * (A + 1) + n] = v;
@@ -140,10 +155,11 @@ __global__ __launch_bounds__(MLP_WAVES * 64) void mlp_i8_kernel(MlpParams p) {
         // ---- outputs: coalesced logits, then one lane per state scans its row for the sampler
         if (p.logits) {
             const int64_t row0 = tile * 16;
-            const int64_t rows = (p.B - row0 < 16) ? (p.B - row0) : 16;
-            for (int64_t i = lane; i < rows * A; i += 64) {
-                const int rr = (int)(i / A), a = (int)(i - (int64_t)rr * A);
-                p.logits[row0 * A + i] = stage[rr * MLP_LOGIT_PITCH + a];
+            const int rows = (int)((p.B - row0 < 16) ? (p.B - row0) : 16);
+            float* dst = p.logits + row0 * A;
+            for (int i = lane; i < rows * A; i += 64) {
+                const int rr = (int)(((float)i + 0.5f) * inv_A), a = i - rr * A;   // i < 1024: the float quotient is exact
+                dst[i] = stage[rr * MLP_LOGIT_PITCH + a];
             }
         }
         if (g == 0 && live && p.action) {
