@@ -1216,7 +1216,7 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
         if (ch > 16384) ch = 16384;
         pol->chunk = ch;
     }
-    if (const char* env = getenv("ACCERL_CHUNK")) { const long v = atol(env); if (v > 0) pol->chunk = v; }
+    if (const char* env = getenv("ACCERL_CHUNK")) { const long v = atol(env); if (v > 0) pol->chunk = v < 65535 ? v : 65535; }
     return ACCERL_OK;
 }
 

@@ -254,10 +254,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 
 __global__ __launch_bounds__(256) void lstm_pack_kernel(LstmPackParams p) {
     const int K = p.In + p.Hd;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= p.B * K) return;
-    const int64_t b = i / K;
-    const int f = (int)(i - b * K);
+    const int f = blockIdx.x * 256 + threadIdx.x;      // one grid row per state: no division
+    if (f >= K) return;
+    const int64_t b = blockIdx.y;
+    const int64_t i = b * K + f;
     const bool dn = p.done && p.done[b] != 0;
     float v;
     if (f < p.In) {
@@ -288,8 +288,8 @@ __global__ __launch_bounds__(256) void lstm_pack_kernel(LstmPackParams p) {
 
 hipError_t launch_lstm_pack(const LstmPackParams& p, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
-    const int64_t n = p.B * (p.In + p.Hd);
-    lstm_pack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p);
+    if (p.B > 65535) return hipErrorInvalidValue;
+    lstm_pack_kernel<<<dim3((unsigned)((p.In + p.Hd + 255) / 256), (unsigned)p.B), dim3(256), 0, s>>>(p);
     return hipGetLastError();
 }
 
