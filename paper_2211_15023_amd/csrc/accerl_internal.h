@@ -107,6 +107,9 @@ constexpr int CONV_WP_NWAVES = 8;
 // first two int8 convolutions of an image policy in one kernel (the first layer's output stays in LDS)
 bool conv_fused_supported(const ConvParams& a, int NTA, int KSA, int RDA, const ConvParams& b, int NTB, int KSB, int RDB);
 hipError_t launch_conv_fused(const ConvParams& a, int NTA, const ConvParams& b, hipStream_t s);
+// the same pair for exactly the paper's original network (84x84x4 -> 8x8/4 x32 -> 4x4/2 x64): sizes fixed at compile time
+bool conv_front_supported(const ConvParams& a, int NTA, const ConvParams& b);
+hipError_t launch_conv_front(const ConvParams& a, const ConvParams& b, hipStream_t s);
 
 // ---------------------------------------------------------------- max pooling on NHWC
 hipError_t launch_maxpool(const void* in, void* out, int64_t B, int H, int W, int Cs, int Ho, int Wo,

@@ -11,6 +11,8 @@
 //            output are exactly one item each; requantized output goes to memory.
 // Both phases use the arithmetic of conv_kernel.h (same fragments, same epilogue), so accumulators and
 // activations are bit-identical to the unfused path; debug taps run the unfused kernels.
+#include <stdlib.h>
+
 #include "conv_kernel.h"
 
 namespace accerl {
@@ -286,6 +288,8 @@ bool conv_fused_supported(const ConvParams& a, int NTA, int KSA, int RDA, const 
 hipError_t launch_conv_fused(const ConvParams& a, int NTA, const ConvParams& b, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
     if (a.res || b.res) return hipErrorInvalidValue;
+    static const bool no_front = getenv("ACCERL_NO_CONV_FRONT") != nullptr;
+    if (!no_front && conv_front_supported(a, NTA, b)) return launch_conv_front(a, b, s);
     const size_t lds = conv_fused_lds(a, b);
     const void* fn = NTA == 1 ? (const void*)conv_fused_kernel<1, 4> : (const void*)conv_fused_kernel<2, 4>;
     static size_t set_lds[2] = {0, 0};
