@@ -2,21 +2,22 @@
 // of 4x4 on a 4x84x84 uint8 observation; strides 4 and 2, no padding) as one pipelined kernel with every
 // size known at compile time.
 //
-// A workgroup of eight wavefronts walks over observations.  In one tick
-//   wavefronts 4..7  compute the first convolution of observation n+1 from the LDS copy of its bytes and
-//                    write the requantized 20x20x32 image to one of two LDS tiles,
-//   wavefronts 0..3  compute the second convolution of observation n from the other tile and store the
-//                    requantized 9x9x64 image,
-//   everyone         has the bytes of observation n+2 in flight from memory,
-// then the workgroup meets, writes the bytes of observation n+2 to LDS and meets again.  The matrix-core
-// work of one role overlaps the requantization arithmetic of the other inside a workgroup, and there are
-// two barriers per observation.
+// A workgroup of twelve wavefronts (one per compute unit, three per SIMD) walks over pairs of
+// observations.  In one tick
+//   wavefronts 4..7 and 8..11  compute the first convolution of the two observations of pair n+1 from the
+//                    LDS copies of their bytes and write the requantized 20x20x32 images to LDS tiles,
+//   wavefronts 0..3  compute the second convolution of the two observations of pair n from the tiles written
+//                    in the tick before and store the requantized 9x9x64 images,
+//   the first-layer wavefronts have the bytes of pair n+2 in flight from memory,
+// then the workgroup meets, the bytes of pair n+2 go to LDS and the workgroup meets again.  Inside a
+// wavefront the code is a software pipeline in straight-line form: the MFMAs of one pixel tile are
+// interleaved with the requantization arithmetic of the tile before, so that matrix core and vector ALU
+// work at the same time.
 //
 // Weights live in registers: a first-layer wavefront holds all 32 filters (32 VGPRs); a second-layer
-// wavefront holds one half of the 64 filters (64 VGPRs) and computes three 16-pixel tiles with it, so a
-// pixel fragment read from LDS feeds two MFMAs.  The 81 output pixels are covered by the tiles
-// 0..47 and 33..80: the overlap is computed twice and stored twice with identical bytes, which keeps the
-// code free of per-pixel predicates.
+// wavefront holds one half of the 64 filters (64 VGPRs) and computes three 16-pixel tiles with it.  The
+// 81 output pixels are covered by the tiles 0..47 and 33..80: the overlap is computed twice and stored
+// twice with identical bytes, which keeps the code free of per-pixel predicates.
 //
 // Observation tile.  Chunk u (16 bytes) of the LDS copy is dword u of each of the four channel planes,
 // side by side: dword u of a plane holds 4 horizontally adjacent pixels and 84 = 21 dwords, so chunk u is
@@ -24,24 +25,34 @@
 // sign flip (obs - 128).  The weight fragments arrive ordered (kx, c) inside a chunk; they are
 // transposed to (c, kx) once per wavefront to match.
 //
+// First-layer output tile.  Pixels of even and odd columns are kept in two planes, [x & 1][y][x >> 1][32
+// channels]: the stride-2 second layer then reads 16 consecutive output pixels as consecutive 32-byte
+// pixels (measured: 1.4 times the LDS read rate of the plain channels-last image), and the plane offset
+// is an odd multiple of 16 bytes, which makes the 8-byte epilogue stores of neighbouring pixels fall into
+// disjoint banks (twice the store rate).
+//
 // Arithmetic, fragment layouts, bias (with the zero-point correction) and multipliers are those of
 // conv_kernel.h: accumulators and activations are bit-identical to the layer-by-layer path.
+#include <stdlib.h>
+
 #include "conv_kernel.h"
 
 namespace accerl {
 
 namespace {
-constexpr int FR_THREADS = 512;
+constexpr int FR_THREADS = 768;
 constexpr int FR_PLANE = 84 * 84;                 // bytes per channel plane
 constexpr int FR_UNITS = FR_PLANE / 4;            // 16-byte chunks of the observation tile (1764)
 constexpr int FR_TILE_A = FR_UNITS * 16;          // 28224
 constexpr int FR_ROW_A = 21 * 16;                 // LDS bytes per observation row
-constexpr int FR_NPIX1 = 400, FR_TILES1 = 25, FR_PIX1_BYTES = 32, FR_ROW_B = 20 * 32;
-constexpr int FR_TILE_B = FR_NPIX1 * FR_PIX1_BYTES;   // 12800
+constexpr int FR_NPIX1 = 400;               // 25 tiles of 16 pixels
+constexpr int FR_ROW_B = 10 * 32;                 // one row of one column-parity plane: 10 pixels of 32 channels
+constexpr int FR_PLANE_B = 20 * FR_ROW_B + 16;    // 6416: odd multiple of 16 (see above)
+constexpr int FR_TILE_B = 2 * FR_PLANE_B;         // 12832
 constexpr int FR_NPIX2 = 81, FR_PIX2_BYTES = 64;
-constexpr int FR_LDS = FR_TILE_A + 2 * FR_TILE_B;
+constexpr int FR_LDS = 2 * FR_TILE_A + 4 * FR_TILE_B;   // two observations; per observation two output tiles
 constexpr int FR_ROUNDS_A = 7;                    // tiles of the first layer per wavefront (25 over 4)
-constexpr int FR_STAGERS = 256;                  // lanes of the first-layer wavefronts: they stage the observations
+constexpr int FR_STAGERS = 256;                   // lanes that stage one observation (its four first-layer wavefronts)
 constexpr int FR_PF = (FR_UNITS + FR_STAGERS - 1) / FR_STAGERS;   // staging chunks per lane (7)
 
 struct FrontParams {
@@ -70,23 +81,26 @@ __device__ __forceinline__ uint32_t requant_relu4(v4i acc, v4f m) {
     return w;
 }
 
-__global__ __launch_bounds__(FR_THREADS, 4) void conv_front_kernel(const FrontParams p) {
+__global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef int v2i __attribute__((ext_vector_type(2)));
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
-    char* tileA = smem;
-    char* tileB = smem + FR_TILE_A;                     // two tiles, FR_TILE_B apart
-    const bool roleA = wave >= 4;
+    // LDS: observation tile of slot 0, of slot 1, then the output tiles [slot][buffer]
+    char* tilesB = smem + 2 * FR_TILE_A;
 
-    const int64_t stride = gridDim.x;
-    int64_t img = blockIdx.x;                           // observation whose second convolution runs this tick
+    // pair n of this workgroup: observations 2 * (blockIdx.x + n * gridDim.x) + {0, 1}
+    const int64_t stride = 2 * (int64_t)gridDim.x;
+    int64_t img = 2 * (int64_t)blockIdx.x;              // first observation of the pair whose second convolution runs this tick
     if (img >= p.B) return;
 
-    if (roleA) {
-        // ================= first-layer wavefronts (they also stage the observations)
-        const int aw = wave - 4, stid = tid - 256;
+    if (wave >= 4) {
+        // ================= first-layer wavefronts of slot `slot` (they also stage its observations)
+        const int slot = (wave - 4) >> 2, aw = (wave - 4) & 3, stid = (tid - 256) & 255;
+        char* tileA = smem + slot * FR_TILE_A;
+        char* tileB = tilesB + slot * (2 * FR_TILE_B);
+        img += slot;                                    // this group's observation of the current pair
         // staging: chunk u = dword u of the four planes
         uint32_t pre[FR_PF][4];
         auto stage_load = [&](int64_t im) {
@@ -107,7 +121,8 @@ __global__ __launch_bounds__(FR_THREADS, 4) void conv_front_kernel(const FrontPa
                                                     (int)(pre[k][2] ^ 0x80808080u), (int)(pre[k][3] ^ 0x80808080u)};
             }
         };
-        stage_load(img);
+        const bool have0 = img < p.B;
+        if (have0) stage_load(img);
         v4i wA[4][2];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
@@ -120,110 +135,162 @@ __global__ __launch_bounds__(FR_THREADS, 4) void conv_front_kernel(const FrontPa
             biA[t] = *(const v4i*)(p.biasA + 8 * g + 4 * t);
             mlA[t] = *(const v4f*)(p.multA + 8 * g + 4 * t);
         }
-        // window of this lane's pixel in each of its tiles; K step st adds two observation rows
-        int rbase[FR_ROUNDS_A];
+        // per tile of this wavefront: where the lane's pixel window starts in the observation tile (K step st
+        // adds two observation rows) and where its 8 output channels go in the output tile
+        int rbase[FR_ROUNDS_A + 1], wbase[FR_ROUNDS_A + 1];
 #pragma unroll
-        for (int r = 0; r < FR_ROUNDS_A; ++r) {
+        for (int r = 0; r < FR_ROUNDS_A + 1; ++r) {
             const int px = min((aw + 4 * r) * 16 + j, FR_NPIX1 - 1);
             const int oy = (px * 3277) >> 16, ox = px - oy * 20;       // px / 20 for px < 16384
             rbase[r] = oy * (4 * FR_ROW_A) + ox * 16 + (g >> 1) * FR_ROW_A + (g & 1) * 16;
+            wbase[r] = (ox & 1) * FR_PLANE_B + oy * FR_ROW_B + (ox >> 1) * 32 + 8 * g;
         }
-        const int wofs = (aw * 16 + j) * FR_PIX1_BYTES + 8 * g;       // tile r adds 4 * 16 pixels
 
+        // One tile = 8 MFMAs (4 K steps x 2 channel tiles) + 32 requantization operations.  While the matrix
+        // core works on tile r, the vector ALU requantizes tile r-1, and the fragment of K step st is
+        // re-loaded for tile r+1 as soon as the MFMAs of tile r have consumed it.  The group barriers pin
+        // that interleaving.
+        auto frag_a = [&](int r, int st) { return *(const v4i*)(tileA + rbase[r] + st * (2 * FR_ROW_A)); };
+        auto store_a = [&](char* dstB, int r, const v4i (&acc)[2]) {
+            const uint32_t w0 = requant_relu4(acc[0], mlA[0]), w1 = requant_relu4(acc[1], mlA[1]);
+            *(v2i*)(dstB + wbase[r]) = (v2i){(int)w0, (int)w1};
+        };
         auto conv_a = [&](char* dstB) {
-            v4i f[4];
+            v4i f[8];                                   // tile r uses slots 4 * (r & 1) + st; two tiles are in flight
 #pragma unroll
-            for (int st = 0; st < 4; ++st) f[st] = *(const v4i*)(tileA + rbase[0] + st * (2 * FR_ROW_A));
+            for (int st = 0; st < 8; ++st) f[st] = frag_a(st >> 2, st & 3);
+            v4i accO[2] = {biA[0], biA[1]};
 #pragma unroll
-            for (int r = 0; r < FR_ROUNDS_A; ++r) {
-                if (aw + 4 * r >= FR_TILES1) break;
-                v4i acc[2];
+            for (int r = 0; r < 6; ++r) {
+                v4i accN[2];
 #pragma unroll
-                for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[0][t], f[0], biA[t], 0, 0, 0);
+                for (int st = 0; st < 4; ++st) {
 #pragma unroll
-                for (int st = 1; st < 4; ++st)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[st], acc[t], 0, 0, 0);
-                if (r + 1 < FR_ROUNDS_A && aw + 4 * (r + 1) < FR_TILES1) {
-#pragma unroll
-                    for (int st = 0; st < 4; ++st) f[st] = *(const v4i*)(tileA + rbase[r + 1 < FR_ROUNDS_A ? r + 1 : r] + st * (2 * FR_ROW_A));
+                    for (int t = 0; t < 2; ++t) accN[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[4 * (r & 1) + st], st == 0 ? biA[t] : accN[t], 0, 0, 0);
+                    f[4 * (r & 1) + st] = frag_a(r + 2, st);   // tiles past the wavefront's last one read a valid pixel and are not used
                 }
-                const uint32_t w0 = requant_relu4(acc[0], mlA[0]), w1 = requant_relu4(acc[1], mlA[1]);
-                *(v2i*)(dstB + wofs + r * (64 * FR_PIX1_BYTES)) = (v2i){(int)w0, (int)w1};
+                if (r > 0) store_a(dstB, r - 1, accO);
+                accO[0] = accN[0]; accO[1] = accN[1];
+                if (r > 0) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (aw == 0) {                              // the 25th tile
+                v4i accN[2];
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) accN[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[st], st == 0 ? biA[t] : accN[t], 0, 0, 0);   // tile 6: slots 0..3
+                store_a(dstB, 5, accO);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                store_a(dstB, 6, accN);
+            } else {
+                store_a(dstB, 5, accO);
             }
         };
 
-        stage_commit();
-        __syncthreads();                                 // observation tile complete
-        conv_a(tileB);
+        if (have0) stage_commit();
+        __syncthreads();                                 // observation tiles complete
         const bool more = img + stride < p.B;
-        if (more) stage_load(img + stride);
-        __syncthreads();                                 // first tile B complete, observation tile free
+        if (more) stage_load(img + stride);             // in flight while the first convolution of the first pair runs
+        if (have0) conv_a(tileB);
+        __syncthreads();                                 // first output tiles complete, observation tiles free
         if (more) stage_commit();
         __syncthreads();
+        const int64_t img0 = img - slot;
         for (int n = 0;; ++n, img += stride) {
             const bool has_next = img + stride < p.B, has_next2 = img + 2 * stride < p.B;
             if (has_next2) stage_load(img + 2 * stride);
             if (has_next) conv_a(tileB + ((n + 1) & 1) * FR_TILE_B);
-            if (!has_next) break;
+            if (!(img0 + (n + 1) * stride < p.B)) break;          // the workgroup's pairs are done (same test in every wavefront)
             __syncthreads();
             if (has_next2) stage_commit();
             __syncthreads();
         }
     } else {
-        // ================= second-layer wavefronts
+        // ================= second-layer wavefronts: both observations of the pair, one after the other
         const int h = wave & 1, p0 = (wave >> 1) ? FR_NPIX2 - 48 : 0;
         v4i wB[8][2];
 #pragma unroll
         for (int st = 0; st < 8; ++st)
 #pragma unroll
             for (int t = 0; t < 2; ++t) wB[st][t] = p.wB[(st * 4 + 2 * h + t) * 64 + lane];
-        const v4i* biasB = (const v4i*)(p.biasB + 16 * g + 8 * h);   // fetched per observation (cache hits): no registers held
+        const v4i* biasB = (const v4i*)(p.biasB + 16 * g + 8 * h);
         const v4f* multB = (const v4f*)(p.multB + 16 * g + 8 * h);
+        // window of the lane's pixel of each tile: K step st = kernel row st >> 1, column pair st & 1; the lane's
+        // chunk is column parity g >> 1, channel half g & 1
         int rb[3];
 #pragma unroll
         for (int u = 0; u < 3; ++u) {
             const int px = p0 + 16 * u + j;
             const int oy = (px * 7282) >> 16, ox = px - oy * 9;       // px / 9 for px < 81
-            rb[u] = oy * (2 * FR_ROW_B) + ox * (2 * FR_PIX1_BYTES) + g * 16;
+            rb[u] = oy * (2 * FR_ROW_B) + ox * 32 + (g >> 1) * FR_PLANE_B + (g & 1) * 16;
         }
         const int oofs = (p0 + j) * FR_PIX2_BYTES + 16 * g + 8 * h;   // tile u adds 16 pixels
 
+        // Three pixel tiles, one after the other: 16 MFMAs (8 K steps x 2 channel tiles) each, with the
+        // requantization of the tile before interleaved.  Pixel fragments rotate through eight slots: the
+        // fragment of step q + 8 is requested as soon as step q has consumed its slot.
+        const v4i bi0 = biasB[0], bi1 = biasB[1];
+        const v4f m0 = multB[0], m1 = multB[1];
+        auto frag_b = [&](const char* srcB, int q) {
+            const int u = q >> 3, st = q & 7;
+            return *(const v4i*)(srcB + rb[u] + (st >> 1) * FR_ROW_B + (st & 1) * 32);
+        };
+        auto store_b = [&](int8_t* outp, int u, const v4i (&acc)[2]) {
+            const uint32_t w0 = requant_relu4(acc[0], m0), w1 = requant_relu4(acc[1], m1);
+            *(v2i*)(outp + oofs + u * (16 * FR_PIX2_BYTES)) = (v2i){(int)w0, (int)w1};
+        };
         auto conv_b = [&](const char* srcB, int8_t* outp) {
-            v4i acc[3][2];
-            v4i cur[3], nxt[3];
-            const v4i bi0 = biasB[0], bi1 = biasB[1];
+            v4i gq[8];
 #pragma unroll
-            for (int u = 0; u < 3; ++u) cur[u] = *(const v4i*)(srcB + rb[u]);
-#pragma unroll
-            for (int st = 0; st < 8; ++st) {
-                if (st + 1 < 8) {
-#pragma unroll
-                    for (int u = 0; u < 3; ++u) nxt[u] = *(const v4i*)(srcB + rb[u] + ((st + 1) >> 1) * FR_ROW_B + ((st + 1) & 1) * 64);
-                }
-#pragma unroll
-                for (int u = 0; u < 3; ++u) {
-                    acc[u][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st][0], cur[u], st == 0 ? bi0 : acc[u][0], 0, 0, 0);
-                    acc[u][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st][1], cur[u], st == 0 ? bi1 : acc[u][1], 0, 0, 0);
-                }
-#pragma unroll
-                for (int u = 0; u < 3; ++u) cur[u] = nxt[u];
-            }
-            const v4f m0 = multB[0], m1 = multB[1];
+            for (int q = 0; q < 8; ++q) gq[q] = frag_b(srcB, q);
+            v4i accO[2] = {bi0, bi1};
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
-                const uint32_t w0 = requant_relu4(acc[u][0], m0), w1 = requant_relu4(acc[u][1], m1);
-                *(v2i*)(outp + oofs + u * (16 * FR_PIX2_BYTES)) = (v2i){(int)w0, (int)w1};
+                v4i accN[2];
+#pragma unroll
+                for (int st = 0; st < 8; ++st) {
+                    const int q = u * 8 + st;
+                    accN[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st][0], gq[q & 7], st == 0 ? bi0 : accN[0], 0, 0, 0);
+                    accN[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st][1], gq[q & 7], st == 0 ? bi1 : accN[1], 0, 0, 0);
+                    if (q + 8 < 24) gq[q & 7] = frag_b(srcB, q + 8);
+                }
+                if (u > 0) store_b(outp, u - 1, accO);
+                accO[0] = accN[0]; accO[1] = accN[1];
+                if (u > 0) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        if (u * 8 + k + 8 < 24) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x040, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            store_b(outp, 2, accO);
         };
-
         __syncthreads();
         __syncthreads();
         __syncthreads();
         for (int n = 0;; ++n, img += stride) {
-            const bool has_next = img + stride < p.B;
-            conv_b(tileB + (n & 1) * FR_TILE_B, p.out + img * (int64_t)(FR_NPIX2 * FR_PIX2_BYTES));
-            if (!has_next) break;
+            conv_b(tilesB + (n & 1) * FR_TILE_B, p.out + img * (int64_t)(FR_NPIX2 * FR_PIX2_BYTES));
+            if (img + 1 < p.B)
+                conv_b(tilesB + (2 + (n & 1)) * FR_TILE_B, p.out + (img + 1) * (int64_t)(FR_NPIX2 * FR_PIX2_BYTES));
+            if (!(img + stride < p.B)) break;
             __syncthreads();
             __syncthreads();
         }
@@ -257,10 +324,11 @@ hipError_t launch_conv_front(const ConvParams& a, const ConvParams& b, hipStream
     p.wA = (const v4i*)a.wfrag; p.biasA = (const int*)a.bias; p.multA = a.mult;
     p.wB = (const v4i*)b.wfrag; p.biasB = (const int*)b.bias; p.multB = b.mult;
     p.B = a.B;
-    // resident workgroups striding over the observations, in even rounds
+    // resident workgroups striding over the pairs of observations, in even rounds
+    const int64_t pairs = (a.B + 1) / 2;
     const int64_t cap = (int64_t)occ * conv_num_cus();
-    const int64_t rounds = (a.B + cap - 1) / cap;
-    dim3 grid((unsigned)((a.B + rounds - 1) / rounds));
+    const int64_t rounds = (pairs + cap - 1) / cap;
+    dim3 grid((unsigned)((pairs + rounds - 1) / rounds));
     conv_front_kernel<<<grid, dim3(FR_THREADS), FR_LDS, s>>>(p);
     return hipGetLastError();
 }
