@@ -94,6 +94,10 @@ struct ConvParams {
     int lds_tab;             // LDS bytes of the pixel table of a thin layer (0 = none)
     float inv_prow, hinv_prow;   // 1/d and 0.5/d for d = pooling units per pooled row
     float r;                 // residual ratio (int8 path)
+    // output in the fragment order of the dense layer that reads it (see GemmParams::x_frag); int8, no pooling,
+    // no residual, one band
+    int out_frag;
+    int frag_ks;             // MFMA steps of that dense layer (64 bytes of K each)
 };
 // KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.
 // RD: alignment (16 / 8 / 4) of a chunk read in LDS.  PF: staging units per lane the kernel holds.
@@ -145,6 +149,10 @@ struct GemmParams {
     int relu;
     int A;                   // heads: actions
     int Hd;                  // lstm hidden
+    // x is stored in MFMA fragment order: [tile of 16 states][k_step][lane = 16 * (k % 64 / 16) + state % 16][16 B],
+    // so that a wavefront's fragment load is one contiguous KiB (a row-major x makes every lane of a quarter
+    // wavefront touch a different row).  Needs Kp_bytes == 64 * k_steps and storage for whole tiles of 16 states.
+    int x_frag;
 };
 hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s);
 

@@ -873,7 +873,8 @@ int ensure_workspace(accerl_policy* p, int64_t n, int layout, hipStream_t stream
     int64_t off = 0;
     const std::vector<int64_t>& sl = p->slots[layout];
     std::vector<int64_t> slot_off(sl.size());
-    for (size_t i = 0; i < sl.size(); ++i) { slot_off[i] = off; off += up(sl[i] * n + 256, 256); }
+    // (a buffer handed over in the fragment order of a dense layer holds whole tiles of 16 states)
+    for (size_t i = 0; i < sl.size(); ++i) { slot_off[i] = off; off += up(sl[i] * up(n, 16) + 256, 256); }
     for (auto& b : p->bufs) b.off = b.slot[layout] >= 0 ? slot_off[b.slot[layout]] : -1;
     hipError_t e = hipMalloc((void**)&p->ws, (size_t)off);
     if (e != hipSuccess) { (void)hipGetLastError(); return fail(ACCERL_ENOMEM, "workspace of %lld bytes: %s", (long long)off, hipGetErrorString(e)); }
@@ -1008,6 +1009,7 @@ int run(accerl_policy* p, const Call& c) {
                     cp.mult = s.o_mult >= 0 ? (const float*)(p->consts + s.o_mult) : nullptr;
                     cp.lut = s.o_lut >= 0 ? (const uint16_t*)(p->consts + s.o_lut) : nullptr;
                     cp.B = n;
+                    if (c.debug) cp.out_frag = 0;
                     // the fused max-pool is left out when this conv's own output is the tap
                     if (cp.pool && !tap_here) { cp.pool_out = bufp(s.pool_buf); pooled = true; }
                     else cp.pool = 0;
@@ -1030,6 +1032,7 @@ int run(accerl_policy* p, const Call& c) {
                     gp.h = c.h ? c.h + c0 * p->lstm_hidden : nullptr;
                     gp.c = c.c ? c.c + c0 * p->lstm_hidden : nullptr;
                     gp.B = n;
+                    if (c.debug) gp.x_frag = 0;
                     e = launch_gemm(gp, s.el, s.epi, c.stream);
                     break;
                 }
@@ -1202,6 +1205,31 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
                 if (pol->steps[sj].in_buf == sa.out_buf || pol->steps[sj].res_buf == sa.out_buf) read_elsewhere = true;
             if (read_elsewhere) continue;
             if (conv_fused_supported(sa.cp, sa.NT, sa.KS, sa.RD, sb.cp, sb.NT, sb.KS, sb.RD)) { sa.fuse_next = true; sb.fused_prev = true; }
+        }
+    }
+    // The last convolution hands its output to the dense layer in the dense layer's MFMA fragment order when
+    // nothing else reads that buffer: the dense kernel's state loads are then contiguous (row-major rows make
+    // every lane of a quarter wavefront touch a different row).  Debug calls keep the plain layout.
+    if (!getenv("ACCERL_NO_FRAG_HANDOFF")) {
+        for (size_t gi = 0; gi < pol->steps.size(); ++gi) {
+            Step& sg = pol->steps[gi];
+            if (sg.kind != ST_GEMM || sg.el != EL_I8 || sg.epi != EPI_REQUANT || sg.in_buf < 0) continue;
+            if (sg.gp.Kp_bytes != sg.gp.k_steps * 64) continue;
+            int writer = -1, readers = 0;
+            for (size_t sj = 0; sj < pol->steps.size(); ++sj) {
+                const Step& t = pol->steps[sj];
+                if (t.out_buf == sg.in_buf || t.pool_buf == sg.in_buf) writer = writer < 0 ? (int)sj : -2;
+                if (t.in_buf == sg.in_buf || t.res_buf == sg.in_buf) ++readers;
+            }
+            if (writer < 0 || readers != 1) continue;
+            Step& sc = pol->steps[writer];
+            if (sc.kind != ST_CONV || sc.el != EL_I8 || sc.out_buf != sg.in_buf || sc.fused_prev || sc.fuse_next) continue;
+            if (sc.res_buf >= 0 || sc.cp.pool || sc.cp.n_bands != 1 || sc.cp.sx != sc.cp.s) continue;
+            const int cs = sc.cp.Cs_out;                                   // a pixel's channels must not straddle 16-byte blocks
+            if (cs != 4 && cs != 8 && cs != 16 && cs != 32 && cs != 64) continue;
+            if ((int64_t)sc.cp.Ho * sc.cp.Wo * sc.cp.Cs_out != sg.gp.Kp_bytes || sc.cp.G >= 2048) continue;
+            sc.cp.out_frag = 1; sc.cp.frag_ks = sg.gp.k_steps;
+            sg.gp.x_frag = 1;
         }
     }
     assign_slots(pol, 0);

@@ -384,8 +384,14 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
             const int img = qdiv(pp, inv_npix, hinv_npix);
             const int rem = pp - __mul24(img, n_pix);
             const int ty = qdiv(rem, p.inv_wo, p.hinv_wo), ox = rem - __mul24(ty, p.Wo);
-            ptab[pp] = (v2i_t){__mul24(img, p.tile_stride) + __mul24(ty, row_step) + __mul24(ox, col_step),
-                               do_pool ? __mul24(img, otile_px) + rem : pp + __mul24(img, band_skip)};
+            int second = do_pool ? __mul24(img, otile_px) + rem : pp + __mul24(img, band_skip);
+            if (p.out_frag) {
+                // fragment order of the dense layer that follows: image number in the batch, and the offset of the
+                // pixel's first channel inside a tile of 16 states (K index k = rem * Cs_out: step k / 64, block k % 64 / 16)
+                const int k = __mul24(rem, p.Cs_out);
+                second = (img << 20) | (((k >> 6) << 10) + (((k & 63) >> 4) << 8) + (k & 15));
+            }
+            ptab[pp] = (v2i_t){__mul24(img, p.tile_stride) + __mul24(ty, row_step) + __mul24(ox, col_step), second};
         }
     }
     __syncthreads();   // padding fill (and LDS weights) visible before the first commit / compute
@@ -518,6 +524,11 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                             if (c0 + 4 * t < p.Cs_out) *(uint32_t*)(otile + o + 4 * t) = pk[t];
                     } else {
                         int8_t* dst = (int8_t*)out_b + o;
+                        if (p.out_frag) {
+                            const int64_t b = b0 + (prel[u] >> 20);
+                            dst = (int8_t*)p.out + (b >> 4) * ((int64_t)p.frag_ks << 10) + (prel[u] & 0xfffff) + (((int)b & 15) << 4)
+                                  + ((c0 >> 4) << 8) + (c0 & 15);
+                        }
                         if (NT == 4 && c0 + 16 <= p.Cs_out) {
                             *(v4i*)dst = (v4i){(int)pk[0], (int)pk[1 % NT], (int)pk[2 % NT], (int)pk[3 % NT]};
                         } else if (NT == 2 && c0 + 8 <= p.Cs_out) {

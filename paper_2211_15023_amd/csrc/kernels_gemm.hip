@@ -70,6 +70,8 @@ __global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_ke
         int64_t xrow = b0 + (wave * GM_RT + u) * 16 + j;
         if (xrow >= p.B) xrow = p.B - 1;        // a state past the batch re-reads the last one; its results are not stored
         xptr[u] = (const char*)p.x + xrow * p.Kp_bytes;
+        if (p.x_frag)                           // fragment order: the tile of 16 states of this wavefront, one KiB per step
+            xptr[u] = (const char*)p.x + (xrow >> 4) * ((int64_t)p.k_steps << 10) + lane * 16;
     }
     auto prefetch = [&](int s0) {
         const int ns = (p.k_steps - s0 < GM_KS) ? (p.k_steps - s0) : GM_KS;
@@ -83,6 +85,7 @@ __global__ __launch_bounds__(GM_THREADS, GM_THREADS == 256 ? 2 : 1) void gemm_ke
         for (int st = 0; st < GM_KS; ++st) {
             int kb = (s0 + st) * 64 + g * 16;
             if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
+            if (p.x_frag) kb = min(s0 + st, p.k_steps - 1) << 10;
 #pragma unroll
             for (int u = 0; u < GM_RT; ++u) xpre[u][st] = *(const v4i*)(xptr[u] + kb);
         }
@@ -261,6 +264,7 @@ __global__ __launch_bounds__(256) void gemm_small_i8_kernel(const GemmParams p) 
     const bool row_live = xrow < p.B;
     if (!row_live) xrow = p.B - 1;
     const char* xptr = (const char*)p.x + xrow * p.Kp_bytes;
+    if (p.x_frag) xptr = (const char*)p.x + (xrow >> 4) * ((int64_t)p.k_steps << 10) + lane * 16;
 
     v4i acc[GS_NT];
 #pragma unroll
@@ -272,6 +276,7 @@ __global__ __launch_bounds__(256) void gemm_small_i8_kernel(const GemmParams p) 
             a[t] = ((const v4i*)p.wfrag)[((int64_t)(nt0 + (t < nts ? t : 0)) * p.k_steps + sc) * 64 + lane];
         int kb = sc * 64 + g * 16;
         if (kb > p.Kp_bytes - 16) kb = (p.Kp_bytes - 16) & ~3;
+        if (p.x_frag) kb = sc << 10;
         x = *(const v4i*)(xptr + kb);
     };
     auto fix_x = [&](int st, v4i v) -> v4i {
