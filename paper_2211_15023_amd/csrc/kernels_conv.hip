@@ -1,4 +1,6 @@
 // Dispatch of the convolution kernel family (template in conv_kernel.h).
+#include <stdlib.h>
+
 #include "conv_kernel.h"
 
 namespace accerl {
@@ -48,6 +50,8 @@ bool conv_wp_available(Elem el, int NT, int RD, int PT, int units) {
 
 hipError_t launch_conv(const ConvParams& p, Elem el, int NT, int KS, int RD, int PF, hipStream_t s) {
     if (p.B <= 0) return hipSuccess;
+    static const bool no_tail = getenv("ACCERL_NO_CONV_TAIL") != nullptr;
+    if (el == EL_I8 && !no_tail && conv_tail_supported(p, NT)) return launch_conv_tail(p, s);
     const size_t lds = (KS > 0 ? 0 : (size_t)p.w_bytes + (size_t)p.k_steps * 16 + CONV_LDS_CONST) + (size_t)p.lds_tiles + (size_t)(p.pool ? p.lds_otile : 0) + (size_t)p.lds_tab;
     dim3 grid((unsigned)p.n_bands, 1);
     if (p.wave_private) {
