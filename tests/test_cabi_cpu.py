@@ -137,6 +137,23 @@ def test_planner_decisions_on_the_benchmark_networks(A):
     convs = [_fields(l) for l in steps if " conv " in l]
     assert [c["fuse_next"] for c in convs] == ["1", "0", "0"]
     assert convs[0]["mode"] == "2" and convs[0]["KS"] == "4" and convs[2]["wp"] == "1"
+    # the paper's original network gets the kernels with compile-time sizes, and its last convolution hands the
+    # dense layer its input in MFMA fragment order
+    assert [c["front"] for c in convs] == ["1", "0", "0"] and [c["tail"] for c in convs] == ["0", "0", "1"]
+    assert [c["out_frag"] for c in convs] == ["0", "0", "1"]
+    gemms = [_fields(l) for l in steps if " gemm " in l]
+    assert gemms[0]["x_frag"] == "1" and gemms[0]["k_steps"] == "49"
+    # the paper's smaller students (16 and 32 filters): layer by layer, and 9 * 9 * 32 bytes are not whole MFMA steps,
+    # so the dense layer reads plain rows
+    from workloads.configs import PAPER_STUDENTS
+    import oracle
+    net = PAPER_STUDENTS["net1"]
+    params = wl.init_params(net, wl.STREAM["weights_student"])
+    q1 = oracle.quantize_policy(net, params, wl.make_frames_u8(8, stream=wl.STREAM["calibration"]))
+    s1 = [l for l in _plan(A, net, "int8", q1.tensors, q1.act_scales).splitlines() if l.startswith("step")]
+    c1 = [_fields(l) for l in s1 if " conv " in l]
+    assert [c["front"] for c in c1] == ["0", "0"] and [c["tail"] for c in c1] == ["0", "0"]
+    assert all(c["out_frag"] == "0" for c in c1) and all(_fields(l)["x_frag"] == "0" for l in s1 if " gemm " in l)
     # config 3 student: thin layers are pixel-packed (8 stored channels -> 16-row tiles at half the width),
     # the three stack convs carry their max-pool, residual convs do not
     nt, pt, ns, ps, qp = policies(3, 8)

@@ -98,7 +98,8 @@ def test_single_state_and_odd_batches(A):
     """B = 1 and batches that end inside a pixel tile, an image batch and a GEMM tile."""
     nt, pt, ns, ps, qp = policies(2)
     pol = A.Policy(ns, "int8", student_tensors(qp), qp.act_scales)
-    for B in (1, 2, 7, 65, 129):
+    # 513 and 1030: more pairs / groups of four than resident workgroups, an odd tail, a last tile of 16 states cut short
+    for B in (1, 2, 7, 65, 129, 513, 1030):
         x = wl.make_frames_u8(B, first=500)
         u = wl.make_uniforms(B, first=500)
         ref = oracle.forward_int8(ns, qp, x, u)
