@@ -45,13 +45,11 @@ constexpr int FR_PLANE = 84 * 84;                 // bytes per channel plane
 constexpr int FR_UNITS = FR_PLANE / 4;            // 16-byte chunks of the observation tile (1764)
 constexpr int FR_TILE_A = FR_UNITS * 16;          // 28224
 constexpr int FR_ROW_A = 21 * 16;                 // LDS bytes per observation row
-constexpr int FR_NPIX1 = 400;               // 25 tiles of 16 pixels
 constexpr int FR_ROW_B = 10 * 32;                 // one row of one column-parity plane: 10 pixels of 32 channels
 constexpr int FR_PLANE_B = 20 * FR_ROW_B + 16;    // 6416: odd multiple of 16 (see above)
 constexpr int FR_TILE_B = 2 * FR_PLANE_B;         // 12832
 constexpr int FR_NPIX2 = 81, FR_PIX2_BYTES = 64;
 constexpr int FR_LDS = 2 * FR_TILE_A + 4 * FR_TILE_B;   // two observations; per observation two output tiles
-constexpr int FR_ROUNDS_A = 7;                    // tiles of the first layer per wavefront (25 over 4)
 constexpr int FR_STAGERS = 256;                   // lanes that stage one observation (its four first-layer wavefronts)
 constexpr int FR_PF = (FR_UNITS + FR_STAGERS - 1) / FR_STAGERS;   // staging chunks per lane (7)
 
@@ -135,59 +133,81 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
             biA[t] = *(const v4i*)(p.biasA + 8 * g + 4 * t);
             mlA[t] = *(const v4f*)(p.multA + 8 * g + 4 * t);
         }
-        // per tile of this wavefront: where the lane's pixel window starts in the observation tile (K step st
-        // adds two observation rows) and where its 8 output channels go in the output tile
-        int rbase[FR_ROUNDS_A + 1], wbase[FR_ROUNDS_A + 1];
+        // The 20 x 20 output pixels of the first layer are split into a block of 16 columns, whose tiles are the
+        // output rows (16 pixels in a row: wavefront aw owns the five rows 5aw .. 5aw+4, a chain), and the
+        // remaining 4 columns, whose five tiles are 4 x 4 pixels (wavefront aw owns tile aw, wavefront 0 also the
+        // fifth).  Along a chain the windows of two vertically adjacent pixels share their lower and upper
+        // halves: K steps 2 and 3 of a row (observation rows 4oy+4 .. 4oy+7) are K steps 0 and 1 of the row
+        // below, so a chain tile re-reads only two of its four fragments from LDS (68 instead of 100
+        // fragment reads per observation).
+        // chain: window of the lane's pixel (row 5aw, column j), K step st adds two observation rows, the next
+        // chain tile four; output address of that pixel, the next chain tile adds one output row
+        const int rb_chain = (5 * aw) * (4 * FR_ROW_A) + j * 16 + (g >> 1) * FR_ROW_A + (g & 1) * 16;
+        const int wb_chain = (j & 1) * FR_PLANE_B + (5 * aw) * FR_ROW_B + (j >> 1) * 32 + 8 * g;
+        // 4 x 4 tiles: pixel (4b + j / 4, 16 + j % 4) of tile b = aw, and of tile 4 for the first wavefront
+        int rb_blk[2], wb_blk[2];
 #pragma unroll
-        for (int r = 0; r < FR_ROUNDS_A + 1; ++r) {
-            const int px = min((aw + 4 * r) * 16 + j, FR_NPIX1 - 1);
-            const int oy = (px * 3277) >> 16, ox = px - oy * 20;       // px / 20 for px < 16384
-            rbase[r] = oy * (4 * FR_ROW_A) + ox * 16 + (g >> 1) * FR_ROW_A + (g & 1) * 16;
-            wbase[r] = (ox & 1) * FR_PLANE_B + oy * FR_ROW_B + (ox >> 1) * 32 + 8 * g;
+        for (int k = 0; k < 2; ++k) {
+            const int b = k == 0 ? aw : 4, oy = 4 * b + (j >> 2), ox = 16 + (j & 3);
+            rb_blk[k] = oy * (4 * FR_ROW_A) + ox * 16 + (g >> 1) * FR_ROW_A + (g & 1) * 16;
+            wb_blk[k] = (ox & 1) * FR_PLANE_B + oy * FR_ROW_B + (ox >> 1) * 32 + 8 * g;
         }
 
         // One tile = 8 MFMAs (4 K steps x 2 channel tiles) + 32 requantization operations.  While the matrix
-        // core works on tile r, the vector ALU requantizes tile r-1, and the fragment of K step st is
-        // re-loaded for tile r+1 as soon as the MFMAs of tile r have consumed it.  The group barriers pin
-        // that interleaving.
-        auto frag_a = [&](int r, int st) { return *(const v4i*)(tileA + rbase[r] + st * (2 * FR_ROW_A)); };
+        // core works on tile r, the vector ALU requantizes tile r-1 and the fragments of tile r+1 are read.
+        // The group barriers pin that interleaving.  Tiles 0..4 are the chain, 5 and 6 the 4 x 4 tiles.
+        auto frag_a = [&](int r, int st) {
+            const int base = r < 5 ? rb_chain + r * (4 * FR_ROW_A) : rb_blk[r - 5];
+            return *(const v4i*)(tileA + base + st * (2 * FR_ROW_A));
+        };
         auto store_a = [&](char* dstB, int r, const v4i (&acc)[2]) {
             const uint32_t w0 = requant_relu4(acc[0], mlA[0]), w1 = requant_relu4(acc[1], mlA[1]);
-            *(v2i*)(dstB + wbase[r]) = (v2i){(int)w0, (int)w1};
+            *(v2i*)(dstB + (r < 5 ? wb_chain + r * FR_ROW_B : wb_blk[r - 5])) = (v2i){(int)w0, (int)w1};
+        };
+        auto mfma_a = [&](const v4i (&f)[4], v4i (&acc)[2]) {
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[st], st == 0 ? biA[t] : acc[t], 0, 0, 0);
         };
         auto conv_a = [&](char* dstB) {
-            v4i f[8];                                   // tile r uses slots 4 * (r & 1) + st; two tiles are in flight
+            v4i f[4];
 #pragma unroll
-            for (int st = 0; st < 8; ++st) f[st] = frag_a(st >> 2, st & 3);
+            for (int st = 0; st < 4; ++st) f[st] = frag_a(0, st);
             v4i accO[2] = {biA[0], biA[1]};
 #pragma unroll
             for (int r = 0; r < 6; ++r) {
-                v4i accN[2];
+                v4i accN[2], fn[4];
+                mfma_a(f, accN);
+                // fragments of tile r+1: a chain tile inherits steps 0 and 1 from steps 2 and 3 of the tile above
+                if (r + 1 < 5) {
+                    fn[0] = f[2]; fn[1] = f[3];
+                    fn[2] = frag_a(r + 1, 2); fn[3] = frag_a(r + 1, 3);
+                } else if (r + 1 == 5 || aw == 0) {     // tile 6 belongs to the first wavefront only
 #pragma unroll
-                for (int st = 0; st < 4; ++st) {
+                    for (int st = 0; st < 4; ++st) fn[st] = frag_a(r + 1, st);
+                } else {
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) accN[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[4 * (r & 1) + st], st == 0 ? biA[t] : accN[t], 0, 0, 0);
-                    f[4 * (r & 1) + st] = frag_a(r + 2, st);   // tiles past the wavefront's last one read a valid pixel and are not used
+                    for (int st = 0; st < 4; ++st) fn[st] = f[st];
                 }
                 if (r > 0) store_a(dstB, r - 1, accO);
                 accO[0] = accN[0]; accO[1] = accN[1];
+#pragma unroll
+                for (int st = 0; st < 4; ++st) f[st] = fn[st];
                 if (r > 0) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        if (r + 1 >= 5 || k < 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                         __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
                     }
                     __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (aw == 0) {                              // the 25th tile
+            if (aw == 0) {                              // the fifth 4 x 4 tile
                 v4i accN[2];
-#pragma unroll
-                for (int st = 0; st < 4; ++st)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) accN[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[st], st == 0 ? biA[t] : accN[t], 0, 0, 0);   // tile 6: slots 0..3
+                mfma_a(f, accN);
                 store_a(dstB, 5, accO);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
