@@ -158,6 +158,9 @@ struct GemmParams {
     int x_frag;
 };
 hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s);
+// int8 + requantizing epilogue for large batches whose rows are whole MFMA steps (launch_gemm picks it)
+bool gemm_stream_supported(const GemmParams& p);
+hipError_t launch_gemm_stream(const GemmParams& p, hipStream_t s);
 
 // policy heads + sampler in one kernel (K up to 16 MFMA steps; wider inputs go through launch_gemm + launch_sample)
 struct HeadsParams {

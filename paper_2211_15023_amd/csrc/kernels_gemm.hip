@@ -6,6 +6,8 @@
 // requantize to int8, bias+ReLU to bf16, policy heads (logits / value in fp32), or the LSTM cell
 // (weight rows are interleaved on the host so that the 4 accumulators of a lane are the i,f,g,o
 // pre-activations of one hidden unit).
+#include <stdlib.h>
+
 #include "accerl_internal.h"
 
 namespace accerl {
@@ -365,7 +367,11 @@ hipError_t launch_gemm(const GemmParams& p, Elem el, GemmEpi epi, hipStream_t s)
         gemm_small_i8_kernel<<<gs, dim3(256), 0, s>>>(p);
         return hipGetLastError();
     }
-    if (el == EL_I8 && epi == EPI_REQUANT) return gemm_go<EL_I8, EPI_REQUANT>(p, grid, s);
+    if (el == EL_I8 && epi == EPI_REQUANT) {
+        static const bool no_stream = getenv("ACCERL_NO_GEMM_STREAM") != nullptr;
+        if (!no_stream && gemm_stream_supported(p)) return launch_gemm_stream(p, s);
+        return gemm_go<EL_I8, EPI_REQUANT>(p, grid, s);
+    }
     if (el == EL_I8 && epi == EPI_HEADS_I8) return gemm_go<EL_I8, EPI_HEADS_I8>(p, grid, s);
     if (el == EL_BF16 && epi == EPI_BF16) return gemm_go<EL_BF16, EPI_BF16>(p, grid, s);
     if (el == EL_BF16 && epi == EPI_HEADS_F32ACC) return gemm_go<EL_BF16, EPI_HEADS_F32ACC>(p, grid, s);
