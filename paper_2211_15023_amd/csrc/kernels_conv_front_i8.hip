@@ -101,14 +101,16 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
         img += slot;                                    // this group's observation of the current pair
         // staging: chunk u = dword u of the four planes
         uint32_t pre[FR_PF][4];
+        auto stage_load_part = [&](const uint8_t* src, int k) {
+            const int u = min(stid + k * FR_STAGERS, FR_UNITS - 1);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) pre[k][c] = *(const uint32_t*)(src + c * FR_PLANE + 4 * u);
+        };
+        auto obs_of = [&](int64_t im) { return p.obs + min(im, p.B - 1) * (int64_t)(4 * FR_PLANE); };   // past the batch: the last observation, never used
         auto stage_load = [&](int64_t im) {
-            const uint8_t* src = p.obs + im * (int64_t)(4 * FR_PLANE);
+            const uint8_t* src = obs_of(im);
 #pragma unroll
-            for (int k = 0; k < FR_PF; ++k) {
-                const int u = min(stid + k * FR_STAGERS, FR_UNITS - 1);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) pre[k][c] = *(const uint32_t*)(src + c * FR_PLANE + 4 * u);
-            }
+            for (int k = 0; k < FR_PF; ++k) stage_load_part(src, k);
         };
         auto stage_commit = [&]() {
 #pragma unroll
@@ -170,7 +172,9 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
 #pragma unroll
                 for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st][t], f[st], st == 0 ? biA[t] : acc[t], 0, 0, 0);
         };
-        auto conv_a = [&](char* dstB) {
+        // conv_a also requests the observation `next` (the one staged after this tick), four loads per tile:
+        // in one burst at the top of the tick the 28 loads cost a wavefront 14 % of the tick in issue time
+        auto conv_a = [&](char* dstB, const uint8_t* next) {
             v4i f[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st) f[st] = frag_a(0, st);
@@ -179,6 +183,7 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
             for (int r = 0; r < 6; ++r) {
                 v4i accN[2], fn[4];
                 mfma_a(f, accN);
+                stage_load_part(next, r);
                 // fragments of tile r+1: a chain tile inherits steps 0 and 1 from steps 2 and 3 of the tile above
                 if (r + 1 < 5) {
                     fn[0] = f[2]; fn[1] = f[3];
@@ -202,9 +207,12 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
                         __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
                     }
                     __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            static_assert(FR_PF == 7, "six tiles carry one staging part each, the seventh follows");
+            stage_load_part(next, 6);
             if (aw == 0) {                              // the fifth 4 x 4 tile
                 v4i accN[2];
                 mfma_a(f, accN);
@@ -224,16 +232,14 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
         if (have0) stage_commit();
         __syncthreads();                                 // observation tiles complete
         const bool more = img + stride < p.B;
-        if (more) stage_load(img + stride);             // in flight while the first convolution of the first pair runs
-        if (have0) conv_a(tileB);
+        if (have0) conv_a(tileB, obs_of(img + stride));  // the second pair's observation is in flight meanwhile
         __syncthreads();                                 // first output tiles complete, observation tiles free
         if (more) stage_commit();
         __syncthreads();
         const int64_t img0 = img - slot;
         for (int n = 0;; ++n, img += stride) {
             const bool has_next = img + stride < p.B, has_next2 = img + 2 * stride < p.B;
-            if (has_next2) stage_load(img + 2 * stride);
-            if (has_next) conv_a(tileB + ((n + 1) & 1) * FR_TILE_B);
+            if (has_next) conv_a(tileB + ((n + 1) & 1) * FR_TILE_B, obs_of(img + 2 * stride));
             if (!(img0 + (n + 1) * stride < p.B)) break;          // the workgroup's pairs are done (same test in every wavefront)
             __syncthreads();
             if (has_next2) stage_commit();
