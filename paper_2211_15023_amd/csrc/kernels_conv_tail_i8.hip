@@ -28,9 +28,10 @@ namespace accerl {
 namespace {
 constexpr int TL_SLOTS = 2, TL_THREADS = 128 * TL_SLOTS;
 constexpr int TL_IMG = 81 * 64;                  // bytes per input image
+constexpr int TL_UNITS = TL_IMG / 16;            // 324 staging chunks
 constexpr int TL_PLANE = 1536;                   // one channel block of an image in LDS: 81 pixels of 16 bytes, padded to a multiple of 256
 constexpr int TL_COPY = 4 * TL_PLANE;            // one LDS copy of an image
-constexpr int TL_PF = 3;                         // staging chunks per lane of a slot's two wavefronts: 6 groups of (16 pixels x 4 channel blocks)
+constexpr int TL_PF = (TL_UNITS + 127) / 128;    // staging chunks per lane of a slot's two wavefronts (3)
 constexpr int TL_LDS = TL_SLOTS * 2 * TL_COPY;
 constexpr int TL_NPIX = 49, TL_PIX_BYTES = 64;
 
@@ -65,29 +66,24 @@ __global__ __launch_bounds__(TL_THREADS, 2) void conv_tail_kernel(const TailPara
     const int64_t img_first = TL_SLOTS * (int64_t)blockIdx.x;     // the workgroup's first image (the same in every wavefront)
     if (img_first >= p.B) return;
 
-    // staging: a wavefront's load covers 16 consecutive pixels (one contiguous KiB), lane l taking channel block
-    // l / 16 of pixel l % 16, so that the 16 lanes of a quarter wavefront write 256 consecutive bytes of one plane
-    // (with lane l on pixel l / 4 the four planes of a pixel met in one bank group: a 4-way conflict per store)
+    // staging: chunk u = (pixel u / 4, channel block u % 4) goes to plane u % 4
     const int stid = tid & 127;
     v4i pre[TL_PF];
-    int sofs[TL_PF], dofs[TL_PF];
-    bool live[TL_PF];
+    int dofs[TL_PF];
 #pragma unroll
     for (int k = 0; k < TL_PF; ++k) {
-        const int v = stid + 128 * k, px = (v >> 6) * 16 + (v & 15), cb = (v >> 4) & 3;
-        live[k] = px < 81;
-        sofs[k] = min(px, 80) * 64 + cb * 16;
-        dofs[k] = cb * TL_PLANE + min(px, 80) * 16;
+        const int u = min(stid + 128 * k, TL_UNITS - 1);
+        dofs[k] = (u & 3) * TL_PLANE + (u >> 2) * 16;
     }
     auto stage_load = [&](int64_t im) {
         const int8_t* src = p.in + im * (int64_t)TL_IMG;
 #pragma unroll
-        for (int k = 0; k < TL_PF; ++k) pre[k] = *(const v4i*)(src + sofs[k]);
+        for (int k = 0; k < TL_PF; ++k) pre[k] = *(const v4i*)(src + 16 * min(stid + 128 * k, TL_UNITS - 1));
     };
     auto stage_commit = [&](char* dst) {
 #pragma unroll
         for (int k = 0; k < TL_PF; ++k)
-            if (live[k]) *(v4i*)(dst + dofs[k]) = pre[k];
+            if (stid + 128 * k < TL_UNITS) *(v4i*)(dst + dofs[k]) = pre[k];
     };
 
     if (img < p.B) stage_load(img);
