@@ -219,6 +219,24 @@ def main():
         s160 = time_forward(student, x[:b160].contiguous(), u[:b160].contiguous(), o160, 200, 20, **kw160)
         t160 = time_forward(teacher, xt[:b160].contiguous(), u[:b160].contiguous(), teacher.alloc_outputs(b160), 100, 10, **kw160)
         extra["latency_B160_us"] = dict(student=round(s160 * 1e6, 2), teacher=round(t160 * 1e6, 2))
+        # two Actors on one GPU (Actor section: several actor threads share an accelerator): a second policy object with
+        # its own workspace and stream, forwards issued alternately; one batch fills while the other drains
+        if not student.recurrent:
+            second = A.Policy(ns, "int8", tensors, act_scales)
+            pair = [(student, outs, torch.cuda.Stream()), (second, second.alloc_outputs(B), torch.cuda.Stream())]
+            torch.cuda.synchronize()
+
+            def alternate(n):
+                for i in range(n):
+                    pol, o, st = pair[i & 1]
+                    pol.forward(x, u, outputs=o, stream=st)
+                torch.cuda.synchronize()
+            alternate(2 * args.warmup)
+            t0 = time.perf_counter()
+            alternate(2 * args.steps)
+            t2 = (time.perf_counter() - t0) / (2 * args.steps)
+            extra["two_actor_streams"] = dict(states_per_s=round(B / t2, 1), ms_per_step=round(t2 * 1e3, 5))
+            second.close()
         # the two consumers of the behaviour logits, on one unroll of 16 steps x B environments
         # (Monitor section, KL equation; Corrector section, V-trace equation); both HBM-bound
         nA = ns.n_actions
