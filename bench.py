@@ -280,8 +280,9 @@ def main():
                                          frac_hbm_peak=round(vt_bytes / t_vt / PEAK["hbm"], 4))
 
     if args.ceilings:
-        def span(fn, n=10):
-            fn()
+        def span(fn, n=60):
+            for _ in range(10):          # clocks up before the timed launches
+                fn()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(n):
