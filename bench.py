@@ -228,6 +228,23 @@ def main():
         s160 = time_forward(student, x[:b160].contiguous(), u[:b160].contiguous(), o160, 2000, 200, **kw160)
         t160 = time_forward(teacher, xt[:b160].contiguous(), u[:b160].contiguous(), teacher.alloc_outputs(b160), 1000, 100, **kw160)
         extra["latency_B160_us"] = dict(student=round(s160 * 1e6, 2), teacher=round(t160 * 1e6, 2))
+
+        # spread of the per-call time: 200 chains of 10 back-to-back calls, an event before and after each chain
+        # (both on the stream the kernels run on), p10 / median / p90 of chain time / 10
+        def spread(pol, xs, us, o, **kws):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+            for _ in range(200):
+                pol.forward(xs, us, outputs=o, **kws)
+            for a, b in evs:
+                a.record()
+                for _ in range(10):
+                    pol.forward(xs, us, outputs=o, **kws)
+                b.record()
+            torch.cuda.synchronize()
+            t = np.sort(np.array([a.elapsed_time(b) for a, b in evs])) * 100.0      # ms per chain -> us per call
+            return dict(p10=round(float(t[20]), 2), p50=round(float(t[100]), 2), p90=round(float(t[180]), 2))
+        extra["per_call_us_spread"] = dict(student=spread(student, x, u, outs, **kw),
+                                           student_B160=spread(student, x[:b160].contiguous(), u[:b160].contiguous(), o160, **kw160))
         # two Actors on one GPU (Actor section: several actor threads share an accelerator): a second policy object with
         # its own workspace and stream, forwards issued alternately; one batch fills while the other drains
         if not student.recurrent:
