@@ -114,6 +114,9 @@ hipError_t launch_conv_fused(const ConvParams& a, int NTA, const ConvParams& b, 
 // the same pair for exactly the paper's original network (84x84x4 -> 8x8/4 x32 -> 4x4/2 x64): sizes fixed at compile time
 bool conv_front_supported(const ConvParams& a, int NTA, const ConvParams& b);
 hipError_t launch_conv_front(const ConvParams& a, const ConvParams& b, hipStream_t s);
+// a residual block (ReLU - conv3x3 - ReLU - conv3x3 + skip) of the pruned IMPALA student in one kernel: a = first, b = second convolution
+bool resblock_supported(const ConvParams& a, int NTA, const ConvParams& b, int NTB);
+hipError_t launch_resblock(const ConvParams& a, const ConvParams& b, hipStream_t s);
 // the third layer of that network (9x9x64 -> 3x3/1 x64) with sizes fixed at compile time
 bool conv_tail_supported(const ConvParams& p, int NT);
 hipError_t launch_conv_tail(const ConvParams& p, hipStream_t s);

@@ -164,6 +164,7 @@ struct Step {
     bool fused = false;         // maxpool: normally done by the conv step before it
     bool fuse_next = false;     // conv: normally runs together with the conv step after it (its output stays on chip)
     bool fused_prev = false;    // conv: normally done by the conv step before it
+    bool resblock = false;      // conv with fuse_next: the pair is a residual block (skip connection from this step's input)
     ConvParams cp{};
     Elem el = EL_I8;
     int NT = 1, KS = 0, RD = 16, PF = 16;
@@ -996,7 +997,7 @@ int run(accerl_policy* p, const Call& c) {
                         cb.in = nullptr; cb.out = bufp(nx.out_buf); cb.res = nullptr; cb.tap_acc = nullptr;
                         cb.wfrag = p->consts + nx.o_w; cb.bias = p->consts + nx.o_bias; cb.mult = (const float*)(p->consts + nx.o_mult);
                         cb.B = n;
-                        e = launch_conv_fused(ca, s.NT, cb, c.stream);
+                        e = s.resblock ? launch_resblock(ca, cb, c.stream) : launch_conv_fused(ca, s.NT, cb, c.stream);
                         conv_pair_done = true;
                         break;
                     }
@@ -1207,6 +1208,22 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
             if (conv_fused_supported(sa.cp, sa.NT, sa.KS, sa.RD, sb.cp, sb.NT, sb.KS, sb.RD)) { sa.fuse_next = true; sb.fused_prev = true; }
         }
     }
+    // Residual blocks of the shapes the block kernel covers: both convolutions in one launch (the first one's output
+    // has no other reader by construction: it is the block's inner tensor).
+    if (!getenv("ACCERL_NO_RESBLOCK_FUSE")) {
+        for (size_t si = 0; si + 1 < pol->steps.size(); ++si) {
+            Step& sa = pol->steps[si];
+            Step& sb = pol->steps[si + 1];
+            if (sa.kind != ST_CONV || sb.kind != ST_CONV || sa.el != EL_I8 || sb.el != EL_I8) continue;
+            if (sa.fused_prev || sa.fuse_next || sb.fuse_next || sa.res_buf >= 0 || sb.res_buf < 0) continue;
+            if (sb.in_buf != sa.out_buf || sb.res_buf != sa.in_buf || sa.in_buf < 0 || sa.pool_buf >= 0 || sb.pool_buf >= 0) continue;
+            bool read_elsewhere = false;
+            for (size_t sj = si + 2; sj < pol->steps.size(); ++sj)
+                if (pol->steps[sj].in_buf == sa.out_buf || pol->steps[sj].res_buf == sa.out_buf) read_elsewhere = true;
+            if (read_elsewhere) continue;
+            if (resblock_supported(sa.cp, sa.NT, sb.cp, sb.NT)) { sa.fuse_next = true; sa.resblock = true; sb.fused_prev = true; }
+        }
+    }
     // The last convolution hands its output to the dense layer in the dense layer's MFMA fragment order when
     // nothing else reads that buffer: the dense kernel's state loads are then contiguous (row-major rows make
     // every lane of a quarter wavefront touch a different row).  Debug calls keep the plain layout.
@@ -1292,11 +1309,11 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
                      "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d fuse_next=%d "
-                     "front=%d tail=%d out_frag=%d\n",
+                     "front=%d tail=%d out_frag=%d resblock=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
                      s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt, c.pool, c.TPH, (int)s.fuse_next,
                      (int)(s.fuse_next && i + 1 < pol.steps.size() && conv_front_supported(c, s.NT, pol.steps[i + 1].cp)),
-                     (int)(s.el == EL_I8 && !s.fused_prev && conv_tail_supported(c, s.NT)), c.out_frag);
+                     (int)(s.el == EL_I8 && !s.fused_prev && conv_tail_supported(c, s.NT)), c.out_frag, (int)s.resblock);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d x_frag=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu, s.gp.x_frag);
