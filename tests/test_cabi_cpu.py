@@ -163,9 +163,13 @@ def test_planner_decisions_on_the_benchmark_networks(A):
     assert [c["pool"] for c in convs].count("1") == 3 and convs[0]["pool"] == "1"
     assert all(int(c["PF"]) <= 4 for c in convs)                   # small batches: four workgroups per compute unit
     assert sum(1 for l in steps if " maxpool " in l) == 3          # kept in the plan for debug taps
+    # every residual block of the student is one launch: its first convolution carries the second
+    assert [c["resblock"] for c in convs] == ["0", "1", "0", "1", "0", "0", "1", "0", "1", "0", "0", "1", "0", "1", "0"]
+    assert [c["fuse_next"] for c in convs] == [c["resblock"] for c in convs]
     # the teacher's wider layers are not packed
     tsteps = [l for l in _plan(A, nt, "bf16", [dict(w=w, b=b) for _, w, b in pt]).splitlines() if l.startswith("step")]
     assert _fields([l for l in tsteps if " conv " in l][0])["out"] == "84x84x16"
+    assert all(_fields(l)["resblock"] == "0" for l in tsteps if " conv " in l)   # bf16 blocks run layer by layer
 
 
 def test_workspace_slots_are_shared(A):
