@@ -64,13 +64,23 @@ __device__ __forceinline__ v4i read_chunk(const char* p) {
     }
 }
 
-// per-byte signed maximum: bytes compared as the high bytes of packed 16-bit lanes
-__device__ __forceinline__ uint32_t pmax_i8x4(uint32_t a, uint32_t b) {
+// Per-byte signed maximum over many dwords, bytes compared as the high bytes of packed 16-bit lanes: each dword
+// is split once into its even and its odd bytes (two instructions), the running maxima stay in that form (two
+// packed maxima per dword), and one byte permute puts them together at the end.
+struct I8x4Max {
     typedef short v2s __attribute__((ext_vector_type(2)));
-    const v2s e = __builtin_elementwise_max(__builtin_bit_cast(v2s, (a & 0x00ff00ffu) << 8), __builtin_bit_cast(v2s, (b & 0x00ff00ffu) << 8));
-    const v2s o = __builtin_elementwise_max(__builtin_bit_cast(v2s, a & 0xff00ff00u), __builtin_bit_cast(v2s, b & 0xff00ff00u));
-    return ((__builtin_bit_cast(uint32_t, e) >> 8) & 0x00ff00ffu) | (__builtin_bit_cast(uint32_t, o) & 0xff00ff00u);
-}
+    v2s e, o;
+    __device__ __forceinline__ explicit I8x4Max(uint32_t x)
+        : e(__builtin_bit_cast(v2s, __builtin_amdgcn_perm(x, x, 0x020c000cu))), o(__builtin_bit_cast(v2s, x & 0xff00ff00u)) {}
+    __device__ __forceinline__ void take(uint32_t x) {
+        const I8x4Max t(x);
+        e = __builtin_elementwise_max(e, t.e);
+        o = __builtin_elementwise_max(o, t.o);
+    }
+    __device__ __forceinline__ uint32_t get() const {
+        return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
+    }
+};
 __device__ __forceinline__ uint32_t pmax_bf16x2(uint32_t a, uint32_t b) {
     const float a0 = bf2f(a & 0xffffu), a1 = bf2f(a >> 16), b0 = bf2f(b & 0xffffu), b1 = bf2f(b >> 16);
     return ((b0 > a0) ? (b & 0xffffu) : (a & 0xffffu)) | (((b1 > a1) ? (b >> 16) : (a >> 16)) << 16);
@@ -598,21 +608,45 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                     char* dst = (char*)p.pool_out + (b0 + img) * out_img + ((int64_t)__mul24(py0 + py, rowu) + r2) * U;
                     if (U == 16) {
                         v4i m = *(const v4i*)(src + ((ro[0] + co[0]) << ush) * 16);
+                        if constexpr (EL == EL_I8) {
+                            I8x4Max mx[4] = {I8x4Max((uint32_t)m[0]), I8x4Max((uint32_t)m[1]), I8x4Max((uint32_t)m[2]), I8x4Max((uint32_t)m[3])};
 #pragma unroll
-                        for (int t = 1; t < 9; ++t) {
-                            const v4i v = *(const v4i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 16);
+                            for (int t = 1; t < 9; ++t) {
+                                const v4i v = *(const v4i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 16);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) m[e] = (int)((EL == EL_I8) ? pmax_i8x4((uint32_t)m[e], (uint32_t)v[e]) : pmax_bf16x2((uint32_t)m[e], (uint32_t)v[e]));
+                                for (int e = 0; e < 4; ++e) mx[e].take((uint32_t)v[e]);
+                            }
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) m[e] = (int)mx[e].get();
+                        } else {
+#pragma unroll
+                            for (int t = 1; t < 9; ++t) {
+                                const v4i v = *(const v4i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 16);
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) m[e] = (int)pmax_bf16x2((uint32_t)m[e], (uint32_t)v[e]);
+                            }
                         }
                         *(v4i*)dst = m;
                     } else {
                         typedef int v2i __attribute__((ext_vector_type(2)));
                         v2i m = *(const v2i*)(src + ((ro[0] + co[0]) << ush) * 8);
+                        if constexpr (EL == EL_I8) {
+                            I8x4Max mx[2] = {I8x4Max((uint32_t)m[0]), I8x4Max((uint32_t)m[1])};
 #pragma unroll
-                        for (int t = 1; t < 9; ++t) {
-                            const v2i v = *(const v2i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 8);
+                            for (int t = 1; t < 9; ++t) {
+                                const v2i v = *(const v2i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 8);
 #pragma unroll
-                            for (int e = 0; e < 2; ++e) m[e] = (int)((EL == EL_I8) ? pmax_i8x4((uint32_t)m[e], (uint32_t)v[e]) : pmax_bf16x2((uint32_t)m[e], (uint32_t)v[e]));
+                                for (int e = 0; e < 2; ++e) mx[e].take((uint32_t)v[e]);
+                            }
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) m[e] = (int)mx[e].get();
+                        } else {
+#pragma unroll
+                            for (int t = 1; t < 9; ++t) {
+                                const v2i v = *(const v2i*)(src + ((ro[t / 3] + co[t % 3]) << ush) * 8);
+#pragma unroll
+                                for (int e = 0; e < 2; ++e) m[e] = (int)pmax_bf16x2((uint32_t)m[e], (uint32_t)v[e]);
+                            }
                         }
                         *(v2i*)dst = m;
                     }
