@@ -488,9 +488,17 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         for (int n = 0; n < CoutK; ++n) if (n % Cs_img < Cout) bf[n] = B.bias(t)[n % Cs_img];
         st.o_bias = B.put(bf.data(), bf.size() * 4);
         if (src_u8) {
+            // the staged value of an observation byte: bf16(v / 255).  The kernel computes it as bf16(float(v) * (1 / 255))
+            // when that gives the same 256 values (it does with IEEE single arithmetic); a table is the fallback.
             std::vector<uint16_t> lut(256);
-            for (int v = 0; v < 256; ++v) lut[v] = host_bf16((float)v / 255.0f);
-            st.o_lut = B.put(lut.data(), 512);
+            bool same = true;
+            const volatile float k255 = 1.0f / 255.0f;
+            for (int v = 0; v < 256; ++v) {
+                lut[v] = host_bf16((float)v / 255.0f);
+                const volatile float prod = (float)v * k255;
+                same = same && host_bf16(prod) == lut[v];
+            }
+            if (!same || getenv("ACCERL_OBS_LUT")) st.o_lut = B.put(lut.data(), 512);
         }
     }
     B.pol->steps.push_back(st);

@@ -370,15 +370,32 @@ __global__ __launch_bounds__(NW * 64, conv_min_blocks(NT, KS, PF, PT, NW, MODE))
                     }
                 } else {
                     uint32_t* d = (uint32_t*)(tiles + doff[i]);
+                    if (p.lut == nullptr) {
+                        // bf16(v / 255) as bf16(float(v) * (1 / 255)): the host has checked all 256 values against the table
+                        typedef float v2f __attribute__((ext_vector_type(2)));
+                        typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+                        const float k255 = 1.0f / 255.0f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        uint32_t c0 = p.lut[px[e] & 0xff], c1 = p.lut[(px[e] >> 8) & 0xff];
-                        uint32_t c2 = p.lut[(px[e] >> 16) & 0xff], c3 = p.lut[px[e] >> 24];
-                        if (p.Cin_real < 2) c1 = 0;
-                        if (p.Cin_real < 3) c2 = 0;
-                        if (p.Cin_real < 4) c3 = 0;
-                        d[2 * e] = c0 | (c1 << 16);
-                        d[2 * e + 1] = c2 | (c3 << 16);
+                        for (int e = 0; e < 4; ++e) {
+                            v2f lo = {(float)(px[e] & 0xff) * k255, (float)((px[e] >> 8) & 0xff) * k255};
+                            v2f hi = {(float)((px[e] >> 16) & 0xff) * k255, (float)(px[e] >> 24) * k255};
+                            if (p.Cin_real < 2) lo[1] = 0.0f;
+                            if (p.Cin_real < 3) hi[0] = 0.0f;
+                            if (p.Cin_real < 4) hi[1] = 0.0f;
+                            d[2 * e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, v2bf));
+                            d[2 * e + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, v2bf));
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            uint32_t c0 = p.lut[px[e] & 0xff], c1 = p.lut[(px[e] >> 8) & 0xff];
+                            uint32_t c2 = p.lut[(px[e] >> 16) & 0xff], c3 = p.lut[px[e] >> 24];
+                            if (p.Cin_real < 2) c1 = 0;
+                            if (p.Cin_real < 3) c2 = 0;
+                            if (p.Cin_real < 4) c3 = 0;
+                            d[2 * e] = c0 | (c1 << 16);
+                            d[2 * e + 1] = c2 | (c3 << 16);
+                        }
                     }
                 }
             }
