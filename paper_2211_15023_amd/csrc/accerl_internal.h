@@ -98,6 +98,10 @@ struct ConvParams {
     // no residual, one band
     int out_frag;
     int frag_ks;             // MFMA steps of that dense layer (64 bytes of K each)
+    // int8 layer with the fused ReLU whose accumulators are all below 2^23 whatever the input (worked out from the
+    // weights when the plan is built): a kernel may then start its accumulators at bias + 0x4B000000, read the result's
+    // bits as the float 2^23 + acc and requantize with one fused multiply-add (see requant_relu4_p23)
+    int pos23;
 };
 // KS > 0: weights in registers, that many MFMA steps unrolled; KS = 0: weights in LDS, runtime loop.
 // RD: alignment (16 / 8 / 4) of a chunk read in LDS.  PF: staging units per lane the kernel holds.

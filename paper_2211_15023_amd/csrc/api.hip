@@ -436,7 +436,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     //      4*NT*(i/4) + 4*tt + i%4, so that a lane's accumulators are consecutive channels
     std::vector<char> frag((size_t)w_bytes, 0);
     const int epc = 16 / esz;                       // elements per chunk
-    std::vector<int64_t> wsum(NT * 16, 0);
+    std::vector<int64_t> wsum(NT * 16, 0), wpos(NT * 16, 0), wabs(NT * 16, 0);
     for (int stp = 0; stp < k_steps; ++stp)
         for (int tt = 0; tt < NT; ++tt)
             for (int lane = 0; lane < 64; ++lane) {
@@ -462,6 +462,8 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
                         const int8_t v = B.wq(t)[src];
                         dst[e] = (char)v;
                         wsum[n] += v;
+                        wpos[n] += v > 0 ? v : 0;
+                        wabs[n] += v > 0 ? v : -v;
                     } else {
                         const uint16_t v = host_bf16(B.wf(t)[src]);
                         memcpy(dst + 2 * e, &v, 2);
@@ -472,10 +474,14 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     if (el == EL_I8) {
         std::vector<int32_t> bq(NT * 16, 0);
         std::vector<float> ml(NT * 16, 0.f);
+        bool pos23 = relu;
         for (int n = 0; n < CoutK; ++n) {
             const int ch = n % Cs_img;
             if (ch >= Cout) continue;
             int64_t b = Builder::biasq(B.bias(t)[ch], s_in, B.sw(t)[ch]);
+            // the largest accumulator any input can produce: observations are 0 .. 255, activations -127 .. 127
+            const int64_t top = b + (src_u8 ? 255 * wpos[n] : 127 * wabs[n]);
+            if (top >= (1 << 23) || b <= -(1 << 30)) pos23 = false;
             if (src_u8) b += 128 * wsum[n];          // observations are staged as obs - 128
             bq[n] = (int32_t)b;
             ml[n] = Builder::mult(s_in, B.sw(t)[ch], s_out);
@@ -483,6 +489,7 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
         st.o_bias = B.put(bq.data(), bq.size() * 4);
         st.o_mult = B.put(ml.data(), ml.size() * 4);
         c.r = res_buf >= 0 ? (float)((double)s_res / (double)s_out) : 0.f;
+        c.pos23 = pos23 ? 1 : 0;
     } else {
         std::vector<float> bf(NT * 16, 0.f);
         for (int n = 0; n < CoutK; ++n) if (n % Cs_img < Cout) bf[n] = B.bias(t)[n % Cs_img];

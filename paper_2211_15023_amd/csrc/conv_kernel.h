@@ -101,6 +101,25 @@ __device__ __forceinline__ uint32_t pack_low_bytes(const int (&q)[4]) {
     return lo | hi;
 }
 
+// Requantization with the fused ReLU, clamp(rint(float(acc) * m), 0, 127), of four accumulators into four bytes.
+// P23 = false: as written (convert, multiply, clamp, pack: four instructions per value).
+// P23 = true (ConvParams::pos23 layers, accumulators started at bias + 0x4B000000): the integer 0x4B000000 + acc, read
+// as a float, is exactly 2^23 + acc for 0 <= acc < 2^23, so fma(that, m, -2^23 * m) is acc * m rounded once -- the very
+// float the definition rounds to an integer (the conversion of acc is exact) -- in three instructions per value.  A
+// negative acc gives a float below 2^23, hence a negative product, and the clamp returns the same 0.  c = -2^23 * m
+// is exact (a power of two times m).
+template <bool P23>
+__device__ __forceinline__ uint32_t requant_relu4_p23(v4i acc, v4f m, v4f c) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float y = P23 ? __builtin_fmaf(__int_as_float(acc[r]), m[r], c[r]) : (float)acc[r] * m[r];
+        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(y, 0.0f, 127.0f), r, w);
+    }
+    return w;
+}
+constexpr int P23_MAGIC = 0x4B000000;
+
 // Copy n16 16-byte units from memory to LDS with `nthr` lanes: eight loads per lane are in flight before
 // the first LDS store (a plain copy loop would wait for every load in turn).
 __device__ __forceinline__ void lds_copy16(char* dst, const void* src, int n16, int tid, int nthr) {

@@ -70,15 +70,8 @@ __device__ __forceinline__ v4i transpose4x4(v4i v) {
                  (int)__builtin_amdgcn_perm(hi23, hi01, 0x05040100u), (int)__builtin_amdgcn_perm(hi23, hi01, 0x07060302u)};
 }
 
-// clamp(rint(acc * m), 0, 127) of four accumulators -> four bytes
-__device__ __forceinline__ uint32_t requant_relu4(v4i acc, v4f m) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc[r] * m[r], 0.0f, 127.0f), r, w);
-    return w;
-}
-
+// P23: both layers' accumulators stay below 2^23, so requantization takes the three-instruction form of requant_relu4_p23
+template <bool P23>
 __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef int v2i __attribute__((ext_vector_type(2)));
@@ -129,11 +122,13 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
 #pragma unroll
             for (int t = 0; t < 2; ++t) wA[st][t] = transpose4x4(p.wA[(st * 2 + t) * 64 + lane]);
         v4i biA[2];
-        v4f mlA[2];
+        v4f mlA[2], cA[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             biA[t] = *(const v4i*)(p.biasA + 8 * g + 4 * t);
             mlA[t] = *(const v4f*)(p.multA + 8 * g + 4 * t);
+            cA[t] = mlA[t] * -8388608.0f;
+            if (P23) biA[t] += P23_MAGIC;
         }
         // The 20 x 20 output pixels of the first layer are split into a block of 16 columns, whose tiles are the
         // output rows (16 pixels in a row: wavefront aw owns the five rows 5aw .. 5aw+4, a chain), and the
@@ -163,7 +158,7 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
             return *(const v4i*)(tileA + base + st * (2 * FR_ROW_A));
         };
         auto store_a = [&](char* dstB, int r, const v4i (&acc)[2]) {
-            const uint32_t w0 = requant_relu4(acc[0], mlA[0]), w1 = requant_relu4(acc[1], mlA[1]);
+            const uint32_t w0 = requant_relu4_p23<P23>(acc[0], mlA[0], cA[0]), w1 = requant_relu4_p23<P23>(acc[1], mlA[1], cA[1]);
             *(v2i*)(dstB + (r < 5 ? wb_chain + r * FR_ROW_B : wb_blk[r - 5])) = (v2i){(int)w0, (int)w1};
         };
         auto mfma_a = [&](const v4i (&f)[4], v4i (&acc)[2]) {
@@ -204,7 +199,7 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
                     for (int k = 0; k < 4; ++k) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                         if (r + 1 >= 5 || k < 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, P23 ? 6 : 8, 0);
                     }
                     __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
@@ -220,7 +215,7 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, P23 ? 6 : 8, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 store_a(dstB, 6, accN);
@@ -269,14 +264,15 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
         // Three pixel tiles, one after the other: 16 MFMAs (8 K steps x 2 channel tiles) each, with the
         // requantization of the tile before interleaved.  Pixel fragments rotate through eight slots: the
         // fragment of step q + 8 is requested as soon as step q has consumed its slot.
-        const v4i bi0 = biasB[0], bi1 = biasB[1];
+        const v4i bi0 = biasB[0] + (P23 ? P23_MAGIC : 0), bi1 = biasB[1] + (P23 ? P23_MAGIC : 0);
         const v4f m0 = multB[0], m1 = multB[1];
+        const v4f c0 = m0 * -8388608.0f, c1 = m1 * -8388608.0f;
         auto frag_b = [&](const char* srcB, int q) {
             const int u = q >> 3, st = q & 7;
             return *(const v4i*)(srcB + rb[u] + (st >> 1) * FR_ROW_B + (st & 1) * 32);
         };
         auto store_b = [&](int8_t* outp, int u, const v4i (&acc)[2]) {
-            const uint32_t w0 = requant_relu4(acc[0], m0), w1 = requant_relu4(acc[1], m1);
+            const uint32_t w0 = requant_relu4_p23<P23>(acc[0], m0, c0), w1 = requant_relu4_p23<P23>(acc[1], m1, c1);
             *(v2i*)(outp + oofs + u * (16 * FR_PIX2_BYTES)) = (v2i){(int)w0, (int)w1};
         };
         auto conv_b = [&](const char* srcB, int8_t* outp) {
@@ -301,7 +297,7 @@ __global__ __launch_bounds__(FR_THREADS, 3) void conv_front_kernel(const FrontPa
                     for (int k = 0; k < 8; ++k) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                         if (u * 8 + k + 8 < 24) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, P23 ? 3 : 4, 0);
                     }
                     __builtin_amdgcn_sched_group_barrier(0x040, 1, 0);
                 }
@@ -334,29 +330,35 @@ bool conv_front_supported(const ConvParams& a, int NTA, const ConvParams& b) {
     return true;
 }
 
-hipError_t launch_conv_front(const ConvParams& a, const ConvParams& b, hipStream_t s) {
-    if (a.B <= 0) return hipSuccess;
+template <bool P23>
+static hipError_t front_go(const FrontParams& p, hipStream_t s) {
     static int occ = 0;
     if (!occ) {
-        hipError_t e = hipFuncSetAttribute((const void*)conv_front_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FR_LDS);
+        hipError_t e = hipFuncSetAttribute((const void*)conv_front_kernel<P23>, hipFuncAttributeMaxDynamicSharedMemorySize, FR_LDS);
         if (e != hipSuccess) return e;
         int o = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)conv_front_kernel, FR_THREADS, FR_LDS);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)conv_front_kernel<P23>, FR_THREADS, FR_LDS);
         if (e != hipSuccess) return e;
         occ = o < 1 ? 1 : o;
     }
+    // resident workgroups striding over the pairs of observations, in even rounds
+    const int64_t pairs = (p.B + 1) / 2;
+    const int64_t cap = (int64_t)occ * conv_num_cus();
+    const int64_t rounds = (pairs + cap - 1) / cap;
+    dim3 grid((unsigned)((pairs + rounds - 1) / rounds));
+    conv_front_kernel<P23><<<grid, dim3(FR_THREADS), FR_LDS, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_front(const ConvParams& a, const ConvParams& b, hipStream_t s) {
+    if (a.B <= 0) return hipSuccess;
     FrontParams p;
     p.obs = (const uint8_t*)a.in; p.out = (int8_t*)b.out;
     p.wA = (const v4i*)a.wfrag; p.biasA = (const int*)a.bias; p.multA = a.mult;
     p.wB = (const v4i*)b.wfrag; p.biasB = (const int*)b.bias; p.multB = b.mult;
     p.B = a.B;
-    // resident workgroups striding over the pairs of observations, in even rounds
-    const int64_t pairs = (a.B + 1) / 2;
-    const int64_t cap = (int64_t)occ * conv_num_cus();
-    const int64_t rounds = (pairs + cap - 1) / cap;
-    dim3 grid((unsigned)((pairs + rounds - 1) / rounds));
-    conv_front_kernel<<<grid, dim3(FR_THREADS), FR_LDS, s>>>(p);
-    return hipGetLastError();
+    static const bool no_p23 = getenv("ACCERL_NO_P23") != nullptr;
+    return (a.pos23 && b.pos23 && !no_p23) ? front_go<true>(p, s) : front_go<false>(p, s);
 }
 
 }  // namespace accerl
