@@ -43,14 +43,8 @@ struct TailParams {
     int out_frag, frag_ks;
 };
 
-__device__ __forceinline__ uint32_t tl_requant_relu4(v4i acc, v4f m) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc[r] * m[r], 0.0f, 127.0f), r, w);
-    return w;
-}
-
+// P23: the layer's accumulators stay below 2^23: requantization in the three-instruction form of requant_relu4_p23
+template <bool P23>
 __global__ __launch_bounds__(TL_THREADS, 2) void conv_tail_kernel(const TailParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef int v2i __attribute__((ext_vector_type(2)));
@@ -92,8 +86,9 @@ __global__ __launch_bounds__(TL_THREADS, 2) void conv_tail_kernel(const TailPara
     for (int st = 0; st < 9; ++st)
 #pragma unroll
         for (int t = 0; t < 2; ++t) w[st][t] = p.w[(st * 4 + 2 * h + t) * 64 + lane];
-    const v4i bi0 = *(const v4i*)(p.bias + 16 * g + 8 * h), bi1 = *(const v4i*)(p.bias + 16 * g + 8 * h + 4);
+    const v4i bi0 = *(const v4i*)(p.bias + 16 * g + 8 * h) + (P23 ? P23_MAGIC : 0), bi1 = *(const v4i*)(p.bias + 16 * g + 8 * h + 4) + (P23 ? P23_MAGIC : 0);
     const v4f m0 = *(const v4f*)(p.mult + 16 * g + 8 * h), m1 = *(const v4f*)(p.mult + 16 * g + 8 * h + 4);
+    const v4f c0 = m0 * -8388608.0f, c1 = m1 * -8388608.0f;
 
     // the lane's pixel in each of the four tiles: tile u = output rows 2u and 2u+1 (tile 3: row 6 and, again, row 5);
     // lanes 14 and 15 repeat lane 13's pixel
@@ -114,7 +109,7 @@ __global__ __launch_bounds__(TL_THREADS, 2) void conv_tail_kernel(const TailPara
         return *(const v4i*)(src + rb[u] + ((st / 3) * 9 + (st % 3)) * 16);
     };
     auto store = [&](int8_t* outp, int u, const v4i (&acc)[2]) {
-        const uint32_t w0 = tl_requant_relu4(acc[0], m0), w1 = tl_requant_relu4(acc[1], m1);
+        const uint32_t w0 = requant_relu4_p23<P23>(acc[0], m0, c0), w1 = requant_relu4_p23<P23>(acc[1], m1, c1);
         *(v2i*)(outp + oofs[u]) = (v2i){(int)w0, (int)w1};
     };
     auto compute = [&](const char* src, int8_t* outp) {
@@ -139,7 +134,7 @@ __global__ __launch_bounds__(TL_THREADS, 2) void conv_tail_kernel(const TailPara
                 for (int k = 0; k < 9; ++k) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                     if (u * 9 + k + 8 < 36) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, P23 ? 3 : 4, 0);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x040, 1, 0);
             }
@@ -175,28 +170,34 @@ bool conv_tail_supported(const ConvParams& p, int NT) {
     return true;
 }
 
-hipError_t launch_conv_tail(const ConvParams& c, hipStream_t s) {
-    if (c.B <= 0) return hipSuccess;
+template <bool P23>
+static hipError_t tail_go(const TailParams& p, hipStream_t s) {
     static int occ = 0;
     if (!occ) {
-        hipError_t e = hipFuncSetAttribute((const void*)conv_tail_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS);
+        hipError_t e = hipFuncSetAttribute((const void*)conv_tail_kernel<P23>, hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS);
         if (e != hipSuccess) return e;
         int o = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)conv_tail_kernel, TL_THREADS, TL_LDS);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)conv_tail_kernel<P23>, TL_THREADS, TL_LDS);
         if (e != hipSuccess) return e;
         occ = o < 1 ? 1 : o;
     }
+    // resident workgroups striding over groups of TL_SLOTS images, in even rounds
+    const int64_t groups = (p.B + TL_SLOTS - 1) / TL_SLOTS;
+    const int64_t cap = (int64_t)occ * conv_num_cus();
+    const int64_t rounds = (groups + cap - 1) / cap;
+    dim3 grid((unsigned)((groups + rounds - 1) / rounds));
+    conv_tail_kernel<P23><<<grid, dim3(TL_THREADS), TL_LDS, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_tail(const ConvParams& c, hipStream_t s) {
+    if (c.B <= 0) return hipSuccess;
     TailParams p;
     p.in = (const int8_t*)c.in; p.out = (int8_t*)c.out;
     p.w = (const v4i*)c.wfrag; p.bias = (const int*)c.bias; p.mult = c.mult;
     p.B = c.B; p.out_frag = c.out_frag; p.frag_ks = c.frag_ks;
-    // resident workgroups striding over groups of TL_SLOTS images, in even rounds
-    const int64_t groups = (c.B + TL_SLOTS - 1) / TL_SLOTS;
-    const int64_t cap = (int64_t)occ * conv_num_cus();
-    const int64_t rounds = (groups + cap - 1) / cap;
-    dim3 grid((unsigned)((groups + rounds - 1) / rounds));
-    conv_tail_kernel<<<grid, dim3(TL_THREADS), TL_LDS, s>>>(p);
-    return hipGetLastError();
+    static const bool no_p23 = getenv("ACCERL_NO_P23") != nullptr;
+    return (c.pos23 && !no_p23) ? tail_go<true>(p, s) : tail_go<false>(p, s);
 }
 
 }  // namespace accerl

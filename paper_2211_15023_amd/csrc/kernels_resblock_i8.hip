@@ -54,7 +54,8 @@ struct RbShape {
     static_assert(H % P == 0 && IMG == NPX * 16 && (H * C) % 16 == 0 && COLS <= RB_PF * RB_THREADS, "shape");
 };
 
-template <int C, int H>
+// P23: conv A's accumulators stay below 2^23 (its requantization then takes the form of requant_relu4_p23)
+template <int C, int H, bool P23>
 __global__ __launch_bounds__(RB_THREADS, 2) void resblock_kernel(const ResParams p) {
     typedef RbShape<C, H> S;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -75,8 +76,9 @@ __global__ __launch_bounds__(RB_THREADS, 2) void resblock_kernel(const ResParams
         wA[st] = p.wA[st * 64 + lane];
         wB[st] = p.wB[st * 64 + lane];
     }
-    const v4i biA = *(const v4i*)(p.biasA + 4 * g), biB = *(const v4i*)(p.biasB + 4 * g);
+    const v4i biA = *(const v4i*)(p.biasA + 4 * g) + (P23 ? P23_MAGIC : 0), biB = *(const v4i*)(p.biasB + 4 * g);
     const v4f mlA = *(const v4f*)(p.multA + 4 * g), mlB = *(const v4f*)(p.multB + 4 * g);
+    const v4f cA = mlA * -8388608.0f;
 
     // staging: unit u of a batch = 16 bytes of image u / NPX, row (u % NPX) / UPR; where it lands in the tiles
     v4i pre[RB_PF];
@@ -141,10 +143,7 @@ __global__ __launch_bounds__(RB_THREADS, 2) void resblock_kernel(const ResParams
 #pragma unroll
             for (int st = 0; st < S::KS; ++st)
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st], *(const v4i*)(tileX + base + koff[st]), acc, 0, 0, 0);
-            uint32_t w = 0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f((float)acc[r] * mlA[r], 0.0f, 127.0f), r, w);
+            const uint32_t w = requant_relu4_p23<P23>(acc, mlA, cA);
             // the column's own pixel(s) sit one row and one pixel inside its window
             if (col < total) *(uint32_t*)(tileM + base + S::PITCH + C + 4 * g) = w;
         }
@@ -184,15 +183,15 @@ bool rb_shape_ok(const ConvParams& a, const ConvParams& b) {
     return true;
 }
 
-template <int C, int H>
+template <int C, int H, bool P23>
 hipError_t rb_go(const ResParams& p, hipStream_t s) {
     typedef RbShape<C, H> S;
     static int occ = 0;
     if (!occ) {
-        hipError_t e = hipFuncSetAttribute((const void*)resblock_kernel<C, H>, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
+        hipError_t e = hipFuncSetAttribute((const void*)resblock_kernel<C, H, P23>, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
         if (e != hipSuccess) return e;
         int o = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)resblock_kernel<C, H>, RB_THREADS, S::LDS);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)resblock_kernel<C, H, P23>, RB_THREADS, S::LDS);
         if (e != hipSuccess) return e;
         occ = o < 1 ? 1 : o;
     }
@@ -201,7 +200,7 @@ hipError_t rb_go(const ResParams& p, hipStream_t s) {
     const int64_t cap = (int64_t)occ * conv_num_cus();
     const int64_t rounds = (batches + cap - 1) / cap;
     dim3 grid((unsigned)((batches + rounds - 1) / rounds));
-    resblock_kernel<C, H><<<grid, dim3(RB_THREADS), S::LDS, s>>>(p);
+    resblock_kernel<C, H, P23><<<grid, dim3(RB_THREADS), S::LDS, s>>>(p);
     return hipGetLastError();
 }
 }  // namespace
@@ -220,9 +219,11 @@ hipError_t launch_resblock(const ConvParams& a, const ConvParams& b, hipStream_t
     p.wA = (const v4i*)a.wfrag; p.biasA = (const int*)a.bias; p.multA = a.mult;
     p.wB = (const v4i*)b.wfrag; p.biasB = (const int*)b.bias; p.multB = b.mult;
     p.r = b.r; p.B = a.B;
-    if (rb_shape_ok<8, 42>(a, b)) return rb_go<8, 42>(p, s);
-    if (rb_shape_ok<16, 21>(a, b)) return rb_go<16, 21>(p, s);
-    if (rb_shape_ok<16, 11>(a, b)) return rb_go<16, 11>(p, s);
+    static const bool no_p23 = getenv("ACCERL_NO_P23") != nullptr;
+    const bool p23 = a.pos23 && !no_p23;
+    if (rb_shape_ok<8, 42>(a, b)) return p23 ? rb_go<8, 42, true>(p, s) : rb_go<8, 42, false>(p, s);
+    if (rb_shape_ok<16, 21>(a, b)) return p23 ? rb_go<16, 21, true>(p, s) : rb_go<16, 21, false>(p, s);
+    if (rb_shape_ok<16, 11>(a, b)) return p23 ? rb_go<16, 11, true>(p, s) : rb_go<16, 11, false>(p, s);
     return hipErrorInvalidValue;
 }
 
