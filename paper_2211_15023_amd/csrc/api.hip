@@ -1324,11 +1324,11 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
                      "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d fuse_next=%d "
-                     "front=%d tail=%d out_frag=%d resblock=%d\n",
+                     "front=%d tail=%d out_frag=%d resblock=%d pos23=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
                      s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt, c.pool, c.TPH, (int)s.fuse_next,
                      (int)(s.fuse_next && i + 1 < pol.steps.size() && conv_front_supported(c, s.NT, pol.steps[i + 1].cp)),
-                     (int)(s.el == EL_I8 && !s.fused_prev && conv_tail_supported(c, s.NT)), c.out_frag, (int)s.resblock);
+                     (int)(s.el == EL_I8 && !s.fused_prev && conv_tail_supported(c, s.NT)), c.out_frag, (int)s.resblock, c.pos23);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d x_frag=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu, s.gp.x_frag);

@@ -141,6 +141,8 @@ def test_planner_decisions_on_the_benchmark_networks(A):
     # dense layer its input in MFMA fragment order
     assert [c["front"] for c in convs] == ["1", "0", "0"] and [c["tail"] for c in convs] == ["0", "0", "1"]
     assert [c["out_frag"] for c in convs] == ["0", "0", "1"]
+    # with these weights no input can drive an accumulator of the three layers to 2^23: three-instruction requantization
+    assert [c["pos23"] for c in convs] == ["1", "1", "1"]
     gemms = [_fields(l) for l in steps if " gemm " in l]
     assert gemms[0]["x_frag"] == "1" and gemms[0]["k_steps"] == "49"
     # the paper's smaller students (16 and 32 filters): layer by layer, and 9 * 9 * 32 bytes are not whole MFMA steps,
@@ -166,6 +168,8 @@ def test_planner_decisions_on_the_benchmark_networks(A):
     # every residual block of the student is one launch: its first convolution carries the second
     assert [c["resblock"] for c in convs] == ["0", "1", "0", "1", "0", "0", "1", "0", "1", "0", "0", "1", "0", "1", "0"]
     assert [c["fuse_next"] for c in convs] == [c["resblock"] for c in convs]
+    # the stack convolutions have no ReLU before their max-pool, so the offset accumulators are not for them
+    assert [c["pos23"] for c in convs][0] == "0" and convs[1]["pos23"] == "1"
     # the teacher's wider layers are not packed
     tsteps = [l for l in _plan(A, nt, "bf16", [dict(w=w, b=b) for _, w, b in pt]).splitlines() if l.startswith("step")]
     assert _fields([l for l in tsteps if " conv " in l][0])["out"] == "84x84x16"
