@@ -1,10 +1,11 @@
-"""The specialised kernels of the paper's original network against the generic ones on whole forwards.
+"""The specialised kernels against the generic ones, and the two requantization forms, on whole forwards.
 
 The planner picks the pipelined conv1+conv2 kernel, the third-convolution kernel, the fragment-order handoff and
-the streaming dense kernel for this network; environment switches, read when the library first plans or launches,
-send the same network through the generic convolution and dense kernels instead.  A child process runs with the
-switches set and hands its outputs back through a file; both processes must produce the same bits, and both are
-checked against the oracle on the rows it recomputes.
+the streaming dense kernel for the paper's original network, and the three-instruction requantization where the
+accumulators provably stay below 2^23; environment switches, read when the library first plans or launches, select
+the generic kernels or the four-instruction form instead.  A child process runs with the switches set and hands its
+outputs back through a file; both processes must produce the same bits, and the child's are checked against the
+oracle on the rows it recomputes.
 """
 import os
 import subprocess
@@ -21,7 +22,9 @@ from helpers import policies, student_tensors, check_actions
 pytestmark = pytest.mark.gpu
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-B = 4133           # large-batch kernels, with a last workgroup of 37 states
+
+GENERIC = dict(ACCERL_NO_CONV_FRONT="1", ACCERL_NO_CONV_TAIL="1", ACCERL_NO_GEMM_STREAM="1", ACCERL_NO_FRAG_HANDOFF="1")
+PLAIN_REQUANT = dict(ACCERL_NO_P23="1")
 
 CHILD = r"""
 import sys
@@ -31,7 +34,7 @@ import workloads as wl
 import paper_2211_15023_amd as A
 from helpers import policies, student_tensors
 A.load_library()
-nt, pt, ns, ps, qp = policies(2)
+nt, pt, ns, ps, qp = policies({ci})
 x = wl.make_frames_u8({B}); u = wl.make_uniforms({B})
 pol = A.Policy(ns, "int8", student_tensors(qp), qp.act_scales)
 logits, value, action = pol.forward(torch.from_numpy(x).cuda(), torch.from_numpy(u).cuda())
@@ -40,30 +43,32 @@ np.savez({out!r}, logits=logits.cpu().numpy(), value=value.cpu().numpy(), action
 """
 
 
-def test_generic_and_specialised_kernels_agree(tmp_path):
+# 4133 states of config 2: the large-batch kernels, with a last workgroup of 37 states; 23 states of config 3: the
+# residual-block kernel with its last batches cut short
+@pytest.mark.parametrize("name,env,ci,B", [("generic", GENERIC, 2, 4133), ("plain-requant", PLAIN_REQUANT, 2, 4133),
+                                           ("plain-requant", PLAIN_REQUANT, 3, 23)])
+def test_kernel_choices_agree(tmp_path, name, env, ci, B):
     import paper_2211_15023_amd as A
     A.load_library()
-    out = str(tmp_path / "generic.npz")
-    env = dict(os.environ, ACCERL_NO_CONV_FRONT="1", ACCERL_NO_CONV_TAIL="1", ACCERL_NO_GEMM_STREAM="1",
-               ACCERL_NO_FRAG_HANDOFF="1")
-    print("child process: generic kernels", flush=True)
-    r = subprocess.run([sys.executable, "-c", CHILD.format(root=ROOT, tests=os.path.join(ROOT, "tests"), B=B, out=out)],
-                       env=env, capture_output=True, text=True, timeout=110)
+    out = str(tmp_path / "child.npz")
+    print(f"child process: {name}, cfg{ci} B={B}", flush=True)
+    r = subprocess.run([sys.executable, "-c", CHILD.format(root=ROOT, tests=os.path.join(ROOT, "tests"), ci=ci, B=B, out=out)],
+                       env=dict(os.environ, **env), capture_output=True, text=True, timeout=110)
     assert r.returncode == 0, r.stderr[-2000:]
     gen = np.load(out)
 
-    nt, pt, ns, ps, qp = policies(2)
+    nt, pt, ns, ps, qp = policies(ci)
     x = wl.make_frames_u8(B)
     u = wl.make_uniforms(B)
     pol = A.Policy(ns, "int8", student_tensors(qp), qp.act_scales)
-    print("this process: specialised kernels", flush=True)
+    print("this process: default plan", flush=True)
     logits, value, action = pol.forward(torch.from_numpy(x).cuda(), torch.from_numpy(u).cuda())
     torch.cuda.synchronize()
     pol.close()
     assert np.array_equal(logits.cpu().numpy(), gen["logits"])
     assert np.array_equal(value.cpu().numpy(), gen["value"])
     assert np.array_equal(action.cpu().numpy(), gen["action"])
-    rows = np.r_[0:64, B - 64:B]
+    rows = np.r_[0:min(64, B // 2), B - min(64, B // 2):B]
     ref = oracle.forward_int8(ns, qp, x[rows], u[rows])
     assert np.array_equal(gen["logits"][rows], ref["logits"])
     assert np.array_equal(gen["value"][rows], ref["value"])
