@@ -91,7 +91,10 @@ def main():
     import torch
     import workloads as wl
     import paper_2211_15023_amd as A
-    from paper_2211_15023_amd import compressor
+    # Post-training quantization and pruning are the Compressor's offline step (Section 2.2), outside the library:
+    # the oracle's host helper produces the policy bytes, exactly as the parity tests do, so that the timed policy
+    # is the one the oracle is compared with.
+    import oracle
 
     A.load_library()
     ci = args.config
@@ -112,10 +115,12 @@ def main():
     elif cfg["student_from"] == "independent":
         ps = wl.init_params(ns, wl.STREAM["weights_student"])
     else:
-        ps = compressor.prune_policy(nt, pt, ns)
-    tensors, act_scales = compressor.quantize_policy(ns, ps, states(ns, cfg["calib"], wl.STREAM["calibration"]))
+        ps, _ = oracle.prune_policy(nt, pt, ns)
+    qp = oracle.quantize_policy(ns, ps, states(ns, cfg["calib"], wl.STREAM["calibration"]))
+    tensors, act_scales = qp.tensors, qp.act_scales
+    teacher_tensors = lambda params: [dict(name=n, w=w, b=b) for n, w, b in params]
     student = A.Policy(ns, "int8", tensors, act_scales)
-    teacher = A.Policy(nt, tprec, compressor.teacher_tensors(pt))
+    teacher = A.Policy(nt, tprec, teacher_tensors(pt))
 
     # ---- inputs, resident in HBM before any timed region
     x_host = states(ns, B, wl.STREAM["states"])
@@ -326,8 +331,8 @@ def main():
         nets = [("original_fc2048", wl.nature_cnn("original_fc2048", fc=2048))] + list(wl.configs.PAPER_STUDENTS.items())
         for name, net in nets:
             params = wl.init_params(net, wl.STREAM["weights_student"])
-            qt, qs = compressor.quantize_policy(net, params, states(net, 64, wl.STREAM["calibration"]))
-            pols = dict(int8=A.Policy(net, "int8", qt, qs), bf16=A.Policy(net, "bf16", compressor.teacher_tensors(params)))
+            qn = oracle.quantize_policy(net, params, states(net, 64, wl.STREAM["calibration"]))
+            pols = dict(int8=A.Policy(net, "int8", qn.tensors, qn.act_scales), bf16=A.Policy(net, "bf16", teacher_tensors(params)))
             row = {}
             for bb in (160, B):
                 xb, ub = x[:bb].contiguous(), u[:bb].contiguous()
@@ -342,11 +347,9 @@ def main():
     # ---- the CPU oracle on a sample of the same states (rank 0, N = 1 only)
     cpu = None
     if not args.no_cpu:
-        import oracle
         from oracle import layers as OL
         nsamp = {0: B, 1: B, 2: 4096, 3: 2048, 4: 2048}.get(ci, 256)
         nsamp = min(nsamp, B)
-        qp = oracle.QuantPolicy(tensors=tensors, act_scales=act_scales)
         okw = {}
         if student.recurrent:
             hh, cc = wl.make_hc(B, 256)

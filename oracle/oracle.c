@@ -325,7 +325,7 @@ void orc_lstm_step(const float* x, int64_t B, int In, int Hd, const uint8_t* don
 }
 
 /* ------------------------------------------------------------------------------------------
- * Monitor indicators and off-policy correction (paper Section 2.4 "Corrector", Section 2.5
+ * Monitor indicators and off-policy correction (paper Section 2.3 "Corrector", Section 2.4
  * "Monitor").  fp64 throughout; inputs are the fp32 logits / values the actor and the
  * learner's network produced.
  * ------------------------------------------------------------------------------------------ */

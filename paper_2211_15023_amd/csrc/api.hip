@@ -948,7 +948,9 @@ int run(accerl_policy* p, const Call& c) {
             const Step& s = p->steps[last_step];
             tap_elems = tap_acc ? s.acc_elems : s.out_elems;
             if (!tap_acc && s.kind == ST_GEMM) {
-                if (s.epi != EPI_REQUANT) return fail(ACCERL_EINVAL, "layer %d: activation tap not available", c.layer);
+                // int8 rows are copied out without their padding; bf16 rows are converted whole, so they must have none
+                if (s.epi != EPI_REQUANT && !(s.epi == EPI_BF16 && s.gp.N == s.gp.Np))
+                    return fail(ACCERL_EINVAL, "layer %d: activation tap not available", c.layer);
                 tap_elems = s.gp.N;
             }
             tap_esz = tap_acc ? 4 : (a.precision == ACCERL_INT8 && s.el == EL_I8 && s.kind != ST_LSTM_PACK) ? 1 : 4;
@@ -1098,7 +1100,7 @@ int run(accerl_policy* p, const Call& c) {
             }
             if (tap_here && !tap_acc) {
                 const char* src = bufp(s.out_buf);
-                if (s.kind == ST_GEMM) {
+                if (s.kind == ST_GEMM && s.epi == EPI_REQUANT) {
                     HIP_TRY(hipMemcpy2DAsync(tap_out, (size_t)s.gp.N, src, (size_t)s.gp.Np, (size_t)s.gp.N, (size_t)n,
                                              hipMemcpyDeviceToDevice, c.stream));
                 } else if (tap_esz == 1 || s.kind == ST_GEMM_F32) {
@@ -1277,6 +1279,9 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
         pol->chunk = ch;
     }
     if (const char* env = getenv("ACCERL_CHUNK")) { const long v = atol(env); if (v > 0) pol->chunk = v < 65535 ? v : 65535; }
+    // whole tiles of 64 states per pass: every pass after the first then starts on a 16-byte boundary of the uniforms,
+    // values and actions, and on a tile boundary of the buffers handed over in fragment order
+    if (pol->chunk > 0) pol->chunk = pol->chunk < 64 ? 64 : pol->chunk / 64 * 64;
     return ACCERL_OK;
 }
 

@@ -66,3 +66,14 @@ def check_actions(got, ref_action, ref_logits, u, delta):
         m = action_margin(ref_logits, u)
         assert np.all(m[bad] <= delta), f"{bad.sum()} actions differ, margins {m[bad][:8]}"
     return int(bad.sum())
+
+
+def check_sampler_self_consistency(got_action, got_logits, u, delta=1e-5):
+    """Sampler correctness apart from logit noise: the oracle's sampler run on the HIP path's OWN logits with the
+    same uniforms must return the HIP path's actions, except where the uniform lies within delta of a boundary of
+    that distribution's CDF (expf differs by ulps between the two sides)."""
+    from oracle import layers as L
+    got_logits = np.ascontiguousarray(got_logits, np.float32)
+    u = np.ascontiguousarray(u, np.float32)
+    want = L.softmax_sample(got_logits, u)
+    return check_actions(got_action, want, got_logits, u, delta)

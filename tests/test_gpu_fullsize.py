@@ -10,7 +10,7 @@ import torch
 
 import oracle
 import workloads as wl
-from helpers import policies, rel_err_rows, student_tensors, teacher_tensors, check_actions
+from helpers import policies, rel_err_rows, student_tensors, teacher_tensors, check_actions, check_sampler_self_consistency
 
 pytestmark = pytest.mark.gpu
 
@@ -70,6 +70,7 @@ def test_cnn_teacher_full_batch_sampled(A):
     assert rel_err_rows(logits.cpu().numpy()[rows], ref["logits"]).max() <= 2e-2
     assert rel_err_rows(value.cpu().numpy()[rows], ref["value"]).max() <= 2e-2
     check_actions(action.cpu().numpy()[rows], ref["action"], ref["logits"], u[rows], 2e-2)
+    check_sampler_self_consistency(action.cpu().numpy(), logits.cpu().numpy(), u)      # every row
     pol.close()
 
 

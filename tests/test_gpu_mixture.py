@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import workloads as wl
-from helpers import policies, make_states, rel_err_rows, student_tensors, teacher_tensors, check_actions
+from helpers import policies, make_states, rel_err_rows, student_tensors, teacher_tensors, check_actions, check_sampler_self_consistency
 
 pytestmark = pytest.mark.gpu
 
@@ -54,6 +54,7 @@ def test_mixture_rows_match_their_network(A, B, alpha):
         assert rel_err_rows(gl[~m], ref["logits"][~m]).max() <= 2e-2
         assert rel_err_rows(gv[~m], ref["value"][~m]).max() <= 2e-2
         check_actions(ga[~m], ref["action"][~m], ref["logits"][~m], u[~m], 2e-2)
+    check_sampler_self_consistency(ga, gl, u)      # every row, whichever network produced it
     # and bit-identical to what each policy computes for those rows in a plain forward
     ls, vs, as_ = p_small.forward(dx, du)
     lo, vo, ao = p_orig.forward(dx, du)

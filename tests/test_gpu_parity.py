@@ -11,7 +11,8 @@ import torch
 
 import oracle
 import workloads as wl
-from helpers import policies, make_states, rel_err_rows, student_tensors, teacher_tensors, check_actions
+from helpers import (policies, make_states, rel_err_rows, student_tensors, teacher_tensors, check_actions,
+                     check_sampler_self_consistency)
 
 pytestmark = pytest.mark.gpu
 
@@ -96,6 +97,8 @@ def run_teacher(A, ci, B, first=0):
     assert e <= tol, e
     assert rel_err_rows(value.cpu().numpy(), ref["value"]).max() <= tol
     check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 1e-5 if prec == "fp32" else tol)
+    # the sampler on its own: the oracle's sampler on the GPU's logits must give the GPU's actions
+    check_sampler_self_consistency(action.cpu().numpy(), logits.cpu().numpy(), u)
     return e
 
 
@@ -179,6 +182,7 @@ def test_recurrent_unroll(A, role):
         else:
             assert np.quantile(el, 0.9) <= 2e-2 and el.max() <= 6e-2 and ev <= 6e-2 and eh <= 0.2 and ec <= 0.2
             check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 6e-2)
+        check_sampler_self_consistency(action.cpu().numpy(), logits.cpu().numpy(), u)
         # carry the oracle's state on the GPU side too, so that each step is compared on equal inputs
         dh.copy_(torch.from_numpy(h_ref))
         dc.copy_(torch.from_numpy(c_ref))

@@ -10,7 +10,7 @@ import torch
 import oracle
 import workloads as wl
 from workloads import Net, conv, dense, maxpool, resblock, relu, flatten
-from helpers import make_states, rel_err_rows, teacher_tensors, check_actions
+from helpers import make_states, rel_err_rows, teacher_tensors, check_actions, check_sampler_self_consistency
 from test_gpu_parity import nhwc
 
 pytestmark = pytest.mark.gpu
@@ -89,4 +89,5 @@ def test_bf16_within_tolerance(A, name):
     assert rel_err_rows(logits.cpu().numpy(), ref["logits"]).max() <= 2e-2
     assert rel_err_rows(value.cpu().numpy(), ref["value"]).max() <= 2e-2
     check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 2e-2)
+    check_sampler_self_consistency(action.cpu().numpy(), logits.cpu().numpy(), u)
     pol.close()

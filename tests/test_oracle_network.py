@@ -231,3 +231,62 @@ def test_generators_are_counter_based():
     f = wl.make_frames_u8(16)
     # rectangles leave flat regions: many horizontally equal neighbours, unlike pure noise
     assert (f[..., 1:] == f[..., :-1]).mean() > 0.2
+
+
+def test_recurrent_handoff_hand_example():
+    """int8 torso -> bf16 recurrent core: the FC's int8 output is dequantized by the FC's own output scale
+    (the last activation scale), and the cell reads that vector.  A two-unit FC in front of a one-unit LSTM
+    whose only live input path is the candidate gate g, with i and o held open by their biases: everything
+    is a closed form of the two dequantized features."""
+    net = wl.Net("tiny_rec", "f32", (2,), 2, [wl.dense(2, 2, True), wl.lstm(2, 1)])
+    w_ih = np.zeros((4, 2), np.float32)
+    w_ih[2] = [1.0, 2.0]                                   # gate order i, f, g, o
+    bias = np.array([20.0, 0.0, 0.0, 20.0], np.float32)
+    qp = oracle.QuantPolicy(
+        tensors=[dict(name="l0.dense", wq=np.array([[127, 0], [0, 64]], np.int8), s_w=np.array([0.01, 0.02], np.float32),
+                      b=np.zeros(2, np.float32)),
+                 dict(name="l1.lstm_ih", w=w_ih, b=bias),
+                 dict(name="l1.lstm_hh", w=np.zeros((4, 1), np.float32), b=None),
+                 dict(name="heads", w=np.array([[1.0], [-1.0], [0.5]], np.float32), b=np.array([0.0, 0.25, 1.0], np.float32))],
+        act_scales=np.array([0.5, 0.25], np.float32))
+    # x = [1.0, 0.5] -> q = [2, 1]; acc = [254, 64]; m = 0.5 * s_w / 0.25 = [.02, .04] -> 5.08, 2.56 -> [5, 3]
+    # dequantized with the FC's output scale 0.25: [1.25, 0.75] (0.5 or a weight scale would give other values)
+    x = np.array([[1.0, 0.5]], np.float32)
+    taps = {}
+    r = oracle.forward_int8(net, qp, x, np.array([0.0], np.float32), h=np.zeros((1, 1), np.float32),
+                            c=np.zeros((1, 1), np.float32), taps=taps)
+    assert taps[(0, "act")].tolist() == [[5, 3]]
+    sig = lambda v: 1.0 / (1.0 + np.exp(-v))
+    g = 1.0 * 1.25 + 2.0 * 0.75
+    c_ref = sig(0.0) * 0.0 + sig(20.0) * np.tanh(g)
+    h_ref = sig(20.0) * np.tanh(c_ref)
+    assert abs(float(r["c"][0, 0]) - c_ref) < 1e-6 and abs(float(r["h"][0, 0]) - h_ref) < 1e-6
+    # the heads read bf16(h'): one rounding of 2^-9 relative at most
+    hb = float(L.bf16_round(r["h"])[0, 0])
+    assert abs(hb - h_ref) <= abs(h_ref) * 2.0 ** -8
+    np.testing.assert_allclose(r["logits"], [[hb, -hb + 0.25]], rtol=1e-6)
+    np.testing.assert_allclose(r["value"], [0.5 * hb + 1.0], rtol=1e-6)
+    # a carried state enters through the forget gate (sigma(0) = 1/2) and is wiped by done
+    r2 = oracle.forward_int8(net, qp, x, None, h=np.full((1, 1), 0.3, np.float32), c=np.full((1, 1), 0.8, np.float32))
+    assert abs(float(r2["c"][0, 0]) - (0.5 * 0.8 + sig(20.0) * np.tanh(g))) < 1e-6
+    r3 = oracle.forward_int8(net, qp, x, None, h=np.full((1, 1), 0.3, np.float32), c=np.full((1, 1), 0.8, np.float32),
+                             done=np.array([1], np.uint8))
+    assert np.array_equal(r3["c"], r["c"]) and np.array_equal(r3["h"], r["h"])
+
+
+def test_mixture_rows_equal_each_networks_own_forward():
+    """Section 3.2 mixture: a row holds exactly what the chosen network alone produces for it."""
+    nt, pt, ns, ps, qp = policies(1)
+    B = 23
+    x = make_states(ns, B, wl.STREAM["states"])
+    u = wl.make_uniforms(B)
+    own_s = oracle.forward_int8(ns, qp, x, u)
+    own_t = oracle.forward_float(nt, pt, x, u, "fp32")
+    flags = (rng.random(B) < 0.4).astype(np.uint8)
+    assert flags.any() and not flags.all()
+    for use in (flags, np.ones(B, np.uint8), np.zeros(B, np.uint8)):
+        mix = oracle.forward_mixture(ns, qp, nt, pt, "fp32", x, u, use)
+        sel = use.astype(bool)
+        for k in ("logits", "value", "action"):
+            assert np.array_equal(mix[k][sel], own_s[k][sel]), k
+            assert np.array_equal(mix[k][~sel], own_t[k][~sel]), k
