@@ -175,14 +175,14 @@ def test_recurrent_unroll(A, role):
         # sides and only fp32-vs-fp64 accumulation separates them.  teacher: 16 bf16 layers in front of
         # saturating gates amplify single bf16 rounding flips of the torso (an fp32-accumulating CPU
         # implementation deviates from the oracle by 3.5e-2 at most, see test_bf16_noise_floor_cpu), so
-        # the 2e-2 bar is applied to the bulk (90th percentile) and 6e-2 to the worst element; h and c within 0.12 of
-        # max |ref| (measured 9.3e-2 at most).  test_gpu_recurrent.py::test_bf16_teacher_layer_by_layer holds every
+        # the 2e-2 bar is applied to the bulk (90th percentile) and 6e-2 to the worst element; h and c within 0.15 of
+        # max |ref| (measured 0.107 at most).  test_gpu_recurrent.py::test_bf16_teacher_layer_by_layer holds every
         # kernel of this path, on its own input, to one bf16 rounding and the core to 1e-4.
         if role == "student":
             assert el.max() <= 2e-3 and ev <= 2e-3 and eh <= 1e-4 and ec <= 1e-4
             check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 2e-3)
         else:
-            assert np.quantile(el, 0.9) <= 2e-2 and el.max() <= 6e-2 and ev <= 6e-2 and eh <= 0.12 and ec <= 0.12
+            assert np.quantile(el, 0.9) <= 2e-2 and el.max() <= 6e-2 and ev <= 6e-2 and eh <= 0.15 and ec <= 0.15
             check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 6e-2)
         check_sampler_self_consistency(action.cpu().numpy(), logits.cpu().numpy(), u)
         # carry the oracle's state on the GPU side too, so that each step is compared on equal inputs

@@ -103,8 +103,8 @@ def test_recurrent_teacher_unroll_16_steps(A):
     initialised core saturates, so the end-to-end bound is wider than the feed-forward 2e-2; the per-layer test
     below shows every kernel on its own is within one bf16 rounding of the oracle's layer, and the core itself,
     fed the HIP path's own FC output, within 1e-6 on h and c.  Measured over the 16 steps: logits 2.6e-2, value
-    2.3e-2, h 9.3e-2, c 7.1e-2 of max |ref|; bars: 4e-2 on logits and value, 0.12 on h and c."""
-    unroll(A, "teacher", 37, np.arange(37), 0.1, (4e-2, 4e-2, 0.12))
+    2.3e-2, h 9.3e-2, c 7.1e-2 of max |ref|; bars: 4e-2 on logits and value, 0.15 on h and c (0.107 is the largest seen when every step starts from the oracle's state)."""
+    unroll(A, "teacher", 37, np.arange(37), 0.1, (4e-2, 4e-2, 0.15))
 
 
 def _ordinal(a):
