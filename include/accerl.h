@@ -239,6 +239,22 @@ int accerl_monitor_kl(const float* logits_original, const float* logits_smaller,
                       float* out_kl, float* out_entropy, double* out_stats, void* hip_stream);
 
 /*
+ * accerl_monitor_kl for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same results as
+ * accerl_monitor_kl; the per-workgroup partial sums go to a fixed 40 KiB array inside the library's device
+ * image (1024 records of 5 doubles; each GPU the library runs on holds its own copy until the process ends)
+ * instead of a buffer allocated at first use, and the call makes no hipMalloc / hipFree and no allocating
+ * library call.  B is limited to 16 777 216 (2^24) rows per call; a larger B returns ACCERL_EINVAL with a
+ * message and enqueues nothing (split the batch).  Every call on a GPU uses that GPU's one array: calls that
+ * overlap in time on one GPU (different streams or threads) race and must be serialised by the caller; calls
+ * in sequence need no clearing in between, since a pass overwrites every record that its fold reads.
+ * With more than 1024 x 256 rows the row pass runs over 1024 workgroups where accerl_monitor_kl uses up to
+ * 2048, so the fp64 sums may differ from it in their last bits; out_kl and out_entropy are identical.
+ */
+int accerl_monitor_kl_noalloc(const float* logits_original, const float* logits_smaller, int64_t B, int A,
+                              float* out_kl, float* out_entropy, double* out_stats, void* hip_stream);
+
+/*
  * Knowledge-distillation loss, forward value only (Section 2.2, Eq. 1): per state
  *     loss_b = KL(pi_original(.|s_b) || pi_smaller(.|s_b)) + (v_original(s_b) - v_smaller(s_b))^2 / 2
  *              - beta H(pi_smaller(.|s_b)),

@@ -58,6 +58,8 @@ def load_library():
     lib.accerl_monitor_kl.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
     lib.accerl_vtrace.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, C.c_float, C.c_float, vp, vp, vp, vp]
     lib.accerl_monitor_kl.restype = C.c_int
+    lib.accerl_monitor_kl_noalloc.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
+    lib.accerl_monitor_kl_noalloc.restype = C.c_int
     lib.accerl_probe_mfma.argtypes = [i32, i32, vp, vp]
     lib.accerl_probe_mfma.restype = C.c_int
     lib.accerl_probe_copy.argtypes = [vp, vp, i64, vp]
@@ -260,6 +262,17 @@ def accerl_monitor_kl(logits_original, logits_smaller, out_kl, out_entropy, out_
     _check(load_library().accerl_monitor_kl(_ptr(logits_original, torch.float32), _ptr(logits_smaller, torch.float32), B, A,
                                             _ptr(out_kl, torch.float32), _ptr(out_entropy, torch.float32),
                                             _ptr(out_stats, torch.float64), _stream(stream)))
+
+
+def accerl_monitor_kl_noalloc(logits_original, logits_smaller, out_kl, out_entropy, out_stats, stream=None):
+    """accerl_monitor_kl on the library's fixed partial-sum array: no device allocation, at most 2^24 rows."""
+    import torch
+    B, A = logits_original.shape
+    if tuple(logits_smaller.shape) != (B, A):
+        raise ValueError("logit tables differ in shape")
+    _check(load_library().accerl_monitor_kl_noalloc(_ptr(logits_original, torch.float32), _ptr(logits_smaller, torch.float32), B, A,
+                                                    _ptr(out_kl, torch.float32), _ptr(out_entropy, torch.float32),
+                                                    _ptr(out_stats, torch.float64), _stream(stream)))
 
 
 def accerl_distill_loss(logits_original, logits_smaller, value_original, value_smaller, beta, out_loss, out_mean, stream=None):

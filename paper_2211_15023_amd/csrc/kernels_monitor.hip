@@ -3,6 +3,7 @@
 // bound by HBM traffic: a wavefront copies 64 consecutive rows of both tables into LDS with coalesced
 // 16-byte loads and every lane then works on its own row out of LDS.
 #include <cstdio>
+#include <mutex>
 
 #include "accerl_internal.h"
 
@@ -213,6 +214,28 @@ static double* mon_parts(int dev) {
     return parts[dev];
 }
 
+// Partial sums of the entry point that allocates nothing: a fixed array in the library's device image (every GPU the
+// library runs on holds its own copy for the life of the process).  Host code never passes the array's name to a kernel
+// or a copy: its device address on the current GPU is looked up once per device and kept.
+constexpr int MON_STATIC_PARTS = 1024;                       // workgroups of a pass over the static array
+constexpr int64_t MON_STATIC_MAX_ROWS = (int64_t)1 << 24;    // most rows per call of that entry point
+static __device__ __align__(256) __attribute__((used)) double scratch[MON_STATIC_PARTS * MON_NSTAT];
+
+static double* scratch_address(int dev, hipError_t* err) {
+    static std::mutex mu;
+    static double* ptr[64] = {nullptr};
+    *err = hipSuccess;
+    if (dev < 0 || dev >= 64) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the address on the device that is current now
+        if (*err != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        ptr[dev] = (double*)p;
+    }
+    return ptr[dev];
+}
+
 static int hip_fail(const char* what, hipError_t e) {
     char buf[256];
     snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
@@ -231,7 +254,7 @@ using namespace accerl;
 
 static int run_kl(const char* who, const float* logits_original, const float* logits_smaller, const float* v_o, const float* v_s,
                   float beta, int64_t B, int A, float* out_kl, float* out_entropy, float* out_loss, double* out_stats,
-                  int loss_only, void* hip_stream) {
+                  int loss_only, void* hip_stream, bool static_parts = false) {
     char msg[160];
     if (B < 0 || A < 1 || A > MON_AMAX) { snprintf(msg, sizeof msg, "%s: need B >= 0 and 1 <= A <= 64", who); return set_error(ACCERL_EINVAL, msg); }
     if (B == 0) return ACCERL_OK;
@@ -243,12 +266,25 @@ static int run_kl(const char* who, const float* logits_original, const float* lo
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail("hipGetDevice", e);
-    double* parts = mon_parts(dev);
-    if (!parts) return set_error(ACCERL_ENOMEM, "partial-sum buffer");
+    double* parts = nullptr;
+    int max_parts = MON_PARTS;
+    if (static_parts) {
+        if (B > MON_STATIC_MAX_ROWS) {
+            snprintf(msg, sizeof msg, "%s: %lld rows exceed the %lld this entry point takes per call (split the batch)", who,
+                     (long long)B, (long long)MON_STATIC_MAX_ROWS);
+            return set_error(ACCERL_EINVAL, msg);
+        }
+        parts = scratch_address(dev, &e);
+        if (!parts) return hip_fail("hipGetSymbolAddress(scratch)", e);
+        max_parts = MON_STATIC_PARTS;
+    } else {
+        parts = mon_parts(dev);
+        if (!parts) return set_error(ACCERL_ENOMEM, "partial-sum buffer");
+    }
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t n_tiles = (B + 63) / 64;
     const int64_t want = (n_tiles + MON_WAVES - 1) / MON_WAVES;
-    const int blocks = (int)(want < MON_PARTS ? want : MON_PARTS);
+    const int blocks = (int)(want < max_parts ? want : max_parts);
     const size_t lds = (size_t)MON_WAVES * 2 * 64 * A * sizeof(float);
     if (int rc = raise_lds((const void*)kl_rows_kernel, lds)) return rc;
     kl_rows_kernel<<<dim3(blocks), dim3(MON_WAVES * 64), lds, s>>>(logits_original, logits_smaller, B, A, out_kl, out_entropy, parts,
@@ -262,6 +298,14 @@ static int run_kl(const char* who, const float* logits_original, const float* lo
 extern "C" int accerl_monitor_kl(const float* logits_original, const float* logits_smaller, int64_t B, int A,
                                  float* out_kl, float* out_entropy, double* out_stats, void* hip_stream) {
     return run_kl("monitor", logits_original, logits_smaller, nullptr, nullptr, 0.0f, B, A, out_kl, out_entropy, nullptr, out_stats, 0, hip_stream);
+}
+
+// Every workgroup of the row pass writes its whole record and the fold reads exactly the records of that pass, so the
+// array needs no clearing between calls, whatever the call before it left there.
+extern "C" int accerl_monitor_kl_noalloc(const float* logits_original, const float* logits_smaller, int64_t B, int A,
+                                         float* out_kl, float* out_entropy, double* out_stats, void* hip_stream) {
+    return run_kl("monitor (no allocation)", logits_original, logits_smaller, nullptr, nullptr, 0.0f, B, A, out_kl, out_entropy, nullptr,
+                  out_stats, 0, hip_stream, true);
 }
 
 extern "C" int accerl_distill_loss(const float* logits_original, const float* logits_smaller, const float* value_original,
