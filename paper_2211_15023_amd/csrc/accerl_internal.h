@@ -121,6 +121,10 @@ hipError_t launch_conv_front(const ConvParams& a, const ConvParams& b, hipStream
 // a residual block (ReLU - conv3x3 - ReLU - conv3x3 + skip) of the pruned IMPALA student in one kernel: a = first, b = second convolution
 bool resblock_supported(const ConvParams& a, int NTA, const ConvParams& b, int NTB);
 hipError_t launch_resblock(const ConvParams& a, const ConvParams& b, hipStream_t s);
+// a whole stack of the IMPALA-style student (conv3x3 + max-pool 3x3/2 + two residual blocks) in one kernel:
+// c = the stack convolution planned with its fused pool, a1 / b1 and a2 / b2 = the two blocks' convolutions
+bool stack_supported(const ConvParams& c, int NTC, const ConvParams& a1, const ConvParams& b1, const ConvParams& a2, const ConvParams& b2);
+hipError_t launch_stack(const ConvParams& c, const ConvParams& a1, const ConvParams& b1, const ConvParams& a2, const ConvParams& b2, hipStream_t s);
 // the third layer of that network (9x9x64 -> 3x3/1 x64) with sizes fixed at compile time
 bool conv_tail_supported(const ConvParams& p, int NT);
 hipError_t launch_conv_tail(const ConvParams& p, hipStream_t s);

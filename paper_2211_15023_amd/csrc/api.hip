@@ -165,6 +165,8 @@ struct Step {
     bool fuse_next = false;     // conv: normally runs together with the conv step after it (its output stays on chip)
     bool fused_prev = false;    // conv: normally done by the conv step before it
     bool resblock = false;      // conv with fuse_next: the pair is a residual block (skip connection from this step's input)
+    bool stack_head = false;    // conv: normally runs together with its max-pool and the two residual blocks behind it (steps +1 .. +5)
+    bool stack_member = false;  // max-pool / conv: normally done by the stack kernel of an earlier step
     ConvParams cp{};
     Elem el = EL_I8;
     int NT = 1, KS = 0, RD = 16, PF = 16;
@@ -973,6 +975,7 @@ int run(accerl_policy* p, const Call& c) {
         auto bufp = [&](int b) -> char* { return b < 0 ? const_cast<char*>(states) : p->ws + p->bufs[b].off; };
         bool pooled = false;   // the last conv step also did the max-pool that follows it
         bool conv_pair_done = false;   // the last conv step also did the conv that follows it
+        int stack_skip = 0;            // conv steps still to pass over: a stack kernel has done them
         hipEvent_t prof_prev = nullptr;
         for (int si = 0; si <= last_step; ++si) {
             const Step& s = p->steps[si];
@@ -1004,6 +1007,24 @@ int run(accerl_policy* p, const Call& c) {
                     e = launch_quant_obs((const float*)states, n, s.D, s.Dpad, s.inv_s0, (int8_t*)bufp(s.out_buf), c.stream);
                     break;
                 case ST_CONV: {
+                    if (stack_skip > 0) { --stack_skip; launched = false; break; }                             // done by the stack kernel
+                    if (s.stack_head && !c.debug) {
+                        ConvParams cv[5];
+                        const int idx[5] = {si, si + 2, si + 3, si + 4, si + 5};
+                        for (int k = 0; k < 5; ++k) {
+                            const Step& t = p->steps[idx[k]];
+                            cv[k] = t.cp;
+                            cv[k].in = nullptr; cv[k].out = nullptr; cv[k].res = nullptr; cv[k].tap_acc = nullptr;
+                            cv[k].wfrag = p->consts + t.o_w; cv[k].bias = p->consts + t.o_bias; cv[k].mult = (const float*)(p->consts + t.o_mult);
+                            cv[k].B = n;
+                        }
+                        cv[0].in = bufp(s.in_buf);
+                        cv[4].out = bufp(p->steps[si + 5].out_buf);
+                        e = launch_stack(cv[0], cv[1], cv[2], cv[3], cv[4], c.stream);
+                        pooled = true;          // the max-pool step behind this one is done too
+                        stack_skip = 4;         // and so are the four convolutions of the two blocks
+                        break;
+                    }
                     if (s.fused_prev && conv_pair_done) { conv_pair_done = false; launched = false; break; }   // done by the step before
                     if (s.fuse_next && !c.debug) {
                         const Step& nx = p->steps[si + 1];
@@ -1154,11 +1175,13 @@ static void assign_slots(accerl_policy* pol, int layout) {
     for (int si = 0; si < ns; ++si) {
         const Step& st = pol->steps[si];
         int touched[4] = {st.in_buf, st.res_buf, st.out_buf, -1};
-        if (layout == 0 && st.kind == ST_CONV && st.pool_buf >= 0) touched[2] = st.pool_buf;   // writes the pooled image only
+        if (layout == 0 && st.kind == ST_CONV && st.pool_buf >= 0 && !st.stack_head) touched[2] = st.pool_buf;   // writes the pooled image only
         if (layout == 1 && st.kind == ST_CONV) touched[3] = st.pool_buf;                       // may run either way
+        if (layout == 0 && st.stack_member) continue;                                           // done by the stack kernel
+        if (layout == 0 && st.stack_head) touched[2] = pol->steps[si + 5].out_buf;              // reads its input, writes the stack's output
         if (layout == 0 && st.kind == ST_MAXPOOL && st.fused) continue;                         // never launched
         if (layout == 0 && st.kind == ST_CONV && st.fused_prev) continue;                       // done by the step before
-        if (layout == 0 && st.kind == ST_CONV && st.fuse_next) touched[2] = pol->steps[si + 1].out_buf;
+        if (layout == 0 && st.kind == ST_CONV && st.fuse_next && !st.stack_head) touched[2] = pol->steps[si + 1].out_buf;
         for (int b : touched) {
             if (b < 0) continue;
             first[b] = std::min(first[b], si);
@@ -1239,6 +1262,31 @@ static int create_host(const accerl_arch* arch, const void* weights, int64_t wei
                 if (pol->steps[sj].in_buf == sa.out_buf || pol->steps[sj].res_buf == sa.out_buf) read_elsewhere = true;
             if (read_elsewhere) continue;
             if (resblock_supported(sa.cp, sa.NT, sb.cp, sb.NT)) { sa.fuse_next = true; sa.resblock = true; sb.fused_prev = true; }
+        }
+    }
+    // Whole stacks: a convolution with its fused pool followed by two fused residual blocks of the shapes the stack
+    // kernel covers run as one launch (the tensors in between have no other reader by construction).
+    if (!getenv("ACCERL_NO_STACK_FUSE")) {
+        for (size_t si = 0; si + 5 < pol->steps.size(); ++si) {
+            Step& sc = pol->steps[si];
+            Step& sp = pol->steps[si + 1];
+            Step& a1 = pol->steps[si + 2];
+            Step& b1 = pol->steps[si + 3];
+            Step& a2 = pol->steps[si + 4];
+            Step& b2 = pol->steps[si + 5];
+            if (sc.kind != ST_CONV || sc.el != EL_I8 || sc.pool_buf < 0 || sc.fuse_next || sc.fused_prev || sc.res_buf >= 0) continue;
+            if (sp.kind != ST_MAXPOOL || !sp.fused || sp.out_buf != sc.pool_buf) continue;
+            if (!(a1.kind == ST_CONV && a1.fuse_next && a1.resblock && b1.kind == ST_CONV && b1.fused_prev)) continue;
+            if (!(a2.kind == ST_CONV && a2.fuse_next && a2.resblock && b2.kind == ST_CONV && b2.fused_prev)) continue;
+            if (a1.in_buf != sc.pool_buf || a2.in_buf != b1.out_buf) continue;
+            bool read_elsewhere = false;             // the pooled image and the first block's output feed the blocks only
+            for (size_t sj = si + 6; sj < pol->steps.size(); ++sj)
+                for (int b : {sc.pool_buf, b1.out_buf})
+                    if (pol->steps[sj].in_buf == b || pol->steps[sj].res_buf == b) read_elsewhere = true;
+            if (read_elsewhere) continue;
+            if (!stack_supported(sc.cp, sc.NT, a1.cp, b1.cp, a2.cp, b2.cp)) continue;
+            sc.stack_head = true;
+            sp.stack_member = a1.stack_member = b1.stack_member = a2.stack_member = b2.stack_member = true;
         }
     }
     // The last convolution hands its output to the dense layer in the dense layer's MFMA fragment order when
@@ -1329,11 +1377,11 @@ int accerl_plan_describe(const accerl_arch* arch, const void* weights, int64_t w
             snprintf(line, sizeof line,
                      "step %zu conv layer=%d sub=%d el=%d in=%dx%dx%d out=%dx%dx%d k=%d s=%d pad=%d mode=%d NT=%d KS=%d "
                      "k_steps=%d RD=%d PF=%d TH=%d bands=%d G=%d units_img=%d pitch=%d tile_stride=%d lds=%ld wp=%d pt=%d pool=%d TPH=%d fuse_next=%d "
-                     "front=%d tail=%d out_frag=%d resblock=%d pos23=%d\n",
+                     "front=%d tail=%d out_frag=%d resblock=%d pos23=%d stack=%d\n",
                      i, s.layer, s.sub, (int)s.el, c.H, c.W, c.Cs_in, c.Ho, c.Wo, c.Cs_out, c.k, c.s, c.pad, c.mode,
                      s.NT, s.KS, c.k_steps, s.RD, s.PF, c.TH, c.n_bands, c.G, c.units_img, c.pitch, c.tile_stride, lds, c.wave_private, c.wp_pt, c.pool, c.TPH, (int)s.fuse_next,
                      (int)(s.fuse_next && i + 1 < pol.steps.size() && conv_front_supported(c, s.NT, pol.steps[i + 1].cp)),
-                     (int)(s.el == EL_I8 && !s.fused_prev && conv_tail_supported(c, s.NT)), c.out_frag, (int)s.resblock, c.pos23);
+                     (int)(s.el == EL_I8 && !s.fused_prev && conv_tail_supported(c, s.NT)), c.out_frag, (int)s.resblock, c.pos23, s.stack_head ? 1 : s.stack_member ? 2 : 0);
         } else if (s.kind == ST_GEMM) {
             snprintf(line, sizeof line, "step %zu gemm layer=%d el=%d epi=%d N=%d Np=%d Kp_bytes=%d k_steps=%d n_tiles=%d relu_in=%d relu=%d x_frag=%d\n",
                      i, s.layer, (int)s.el, (int)s.epi, s.gp.N, s.gp.Np, s.gp.Kp_bytes, s.gp.k_steps, s.gp.n_tiles, s.gp.relu_in, s.gp.relu, s.gp.x_frag);
