@@ -31,9 +31,11 @@
 namespace accerl {
 
 
+// max(x, 0) on four signed bytes: a negative byte's sign bit t gives t - (t >> 7) = 0x7f, and 0x7f | t = 0xff is its mask
+// (full-rate instructions only: a 32-bit multiply takes four issue slots)
 __device__ __forceinline__ uint32_t relu_i8x4(uint32_t x) {
-    const uint32_t neg = (x & 0x80808080u) >> 7;
-    return x & ~(neg * 0xffu);
+    const uint32_t t = x & 0x80808080u;
+    return x & ~((t - (t >> 7)) | t);
 }
 __device__ __forceinline__ uint32_t relu_bf16x2(uint32_t x) {
     const uint32_t neg = (x & 0x80008000u) >> 15;

@@ -94,7 +94,7 @@ struct StShape {
     static constexpr int O_RAW = O_TM + G * TILE_B;
     static constexpr int O_T1 = O_RAW + G * IMG;
     static constexpr int O_TABB = O_T1 + T1_BYTES;
-    static constexpr int O_CST = O_TABB + st_up16((TILES + 12) * 16 * 2);   // the block loops read a step (up to 12 tiles) ahead
+    static constexpr int O_CST = O_TABB + st_up16((TILES + 20) * 16 * 2);   // the block loops read two steps (up to 20 tiles) ahead
     static constexpr int LDS = O_CST + 5 * 2 * 16 * 4;
     static_assert(H % P == 0 && IMG == NPX * 16 && (U8 ? (HIN % 4 == 0 && CI == 4) : (HIN * CI) % 16 == 0), "shape");
     static_assert(G * TILE_IN + 64 < 65536 && G * TILE_B < 32768 && G * SLOTS < (1 << 20) && COLS < (1 << 20), "offsets");
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
                 ((v2i*)tab1)[sidx] = (v2i){(int)(a0 | (a1 << 16)), (int)(ox | (orr << 16))};
             }
         }
-        for (int c = tid; c < (S::TILES + 12) * 16; c += ST_THREADS) {
+        for (int c = tid; c < (S::TILES + 20) * 16; c += ST_THREADS) {
             const int cc = min(c, S::COLS - 1);            // columns past the end repeat the last one (never stored)
             const int img = cc / S::NPX, w = cc - img * S::NPX, y = w / S::WP, xp = w - y * S::WP;
             tabB[c] = (uint16_t)(img * S::TILE_B + y * S::PITCH_B + xp * 16);
@@ -279,20 +279,24 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
                 }
             };
             if constexpr (S::P == 2) {
-                // work item: (pair of pooled rows rp, strip): conv rows 4rp-1 .. 4rp+3, the middle one shared
+                // work item: (pair of pooled rows rp, strip): conv rows 4rp-1 .. 4rp+3, the middle one shared.  The five
+                // window reads of the next item are issued before the current item's maxima are formed and requantized.
                 constexpr int N_IT = (S::H / 2) * S::NS;
-                for (int it = wave; it < N_IT; it += 4) {
-                    const int rp = it / S::NS, strip = it - rp * S::NS;
-                    const v4i e = ((const v4i*)tab1)[strip * 64 + lane];
+                auto issue = [&](int it, v4i (&o)[5], v4i& e, int& rp) {
+                    it = min(it, N_IT - 1);                  // past the end: a valid item, read and dropped
+                    rp = it / S::NS;
+                    e = ((const v4i*)tab1)[(it - rp * S::NS) * 64 + lane];
                     const char* a0 = tin + e[0] + max(4 * rp - 1, 0) * S::PITCH_IN;
                     const char* a1 = tin + e[0] + 4 * rp * S::PITCH_IN;
-                    v4i c[5];
-                    c[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], read_chunk<S::RD_E>(a0), biC, 0, 0, 0);
+                    o[0] = read_chunk<S::RD_E>(a0);
 #pragma unroll
-                    for (int k = 1; k < 5; ++k)
-                        c[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], read_chunk<S::RD_E>(a1 + (k - 1) * S::PITCH_IN), biC, 0, 0, 0);
-                    // E in lanes 0-31, O in lanes 32-63 of each row's tile: O takes its left neighbour in, then one swap
-                    // per register puts E and O of the upper row into the lower lanes and of the lower row into the upper
+                    for (int k = 1; k < 5; ++k) o[k] = read_chunk<S::RD_E>(a1 + (k - 1) * S::PITCH_IN);
+                };
+                v4i oA[5], oB[5], eA, eB;
+                int rpA, rpB;
+                // E in lanes 0-31, O in lanes 32-63 of each row's tile: O takes its left neighbour in, then one swap per
+                // register puts E and O of the upper row into the lower lanes and of the lower row into the upper
+                auto pool_store = [&](const v4i (&c)[5], const v4i& e, int rp) {
                     v4i pooled;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -302,6 +306,19 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
                         pooled[r] = max((int)sw[0], (int)sw[1]);
                     }
                     finish(pooled, e[1] + (2 * rp + 1) * S::PITCH_B, e[2] + 2 * rp * S::H * C, e[3] != 0);
+                };
+                issue(wave, oA, eA, rpA);
+                for (int it = wave; it < N_IT; it += 8) {
+                    v4i c[5];
+#pragma unroll
+                    for (int k = 0; k < 5; ++k) c[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], oA[k], biC, 0, 0, 0);
+                    issue(it + 4, oB, eB, rpB);
+                    pool_store(c, eA, rpA);
+                    if (it + 4 >= N_IT) break;
+#pragma unroll
+                    for (int k = 0; k < 5; ++k) c[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], oB[k], biC, 0, 0, 0);
+                    issue(it + 8, oA, eA, rpA);
+                    pool_store(c, eB, rpB);
                 }
             } else {
                 constexpr bool ODD = (HIN & 1) != 0;
@@ -345,24 +362,34 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
 
         const int total = gc * S::NPX;
         const int n_tiles = (total + 15) >> 4;
-        // Block convolutions: two column tiles per step, so that the LDS reads and the MFMA chain of one overlap with the
-        // other's; the table entries of the next step are requested a step ahead.
+        // Block convolutions: two column tiles per step; the window reads of the next step are issued before the current
+        // step's epilogue, and the table entries two steps ahead of their use.
+        auto load_ops = [&](const char* src, const int (&b)[2], v4i (&o)[2][S::KS_B]) {
+#pragma unroll
+            for (int st = 0; st < S::KS_B; ++st)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) o[u][st] = *(const v4i*)(src + b[u] + koffB[st]);
+        };
         // ---- a block's first convolution: max(x, 0) -> inner tensor, requantized with the fused ReLU
         auto conv_a = [&](const v4i (&wA)[S::KS_B], int cv) {
             const v4i biA = *(const v4i*)(cst + cv * 32 + 4 * g) + (P23 ? P23_MAGIC : 0);
             const v4f mlA = *(const v4f*)(cst + cv * 32 + 16 + 4 * g);
             const v4f cA = mlA * -8388608.0f;
-            int nb0 = tabB[wave * 16 + j], nb1 = tabB[(wave + 4) * 16 + j];
+            int bN[2] = {tabB[wave * 16 + j], tabB[(wave + 4) * 16 + j]};
+            int bNN[2] = {tabB[(wave + 8) * 16 + j], tabB[(wave + 12) * 16 + j]};
+            v4i ops[2][S::KS_B];
+            load_ops(tX, bN, ops);
             for (int t = wave; t < n_tiles; t += 8) {
-                const int base[2] = {nb0, nb1};
-                nb0 = tabB[(t + 8) * 16 + j];
-                nb1 = tabB[(t + 12) * 16 + j];
+                const int base[2] = {bN[0], bN[1]};
                 v4i acc[2] = {biA, biA};
 #pragma unroll
                 for (int st = 0; st < S::KS_B; ++st)
 #pragma unroll
-                    for (int u = 0; u < 2; ++u)
-                        acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st], *(const v4i*)(tX + base[u] + koffB[st]), acc[u], 0, 0, 0);
+                    for (int u = 0; u < 2; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st], ops[u][st], acc[u], 0, 0, 0);
+                bN[0] = bNN[0]; bN[1] = bNN[1];
+                bNN[0] = tabB[(t + 16) * 16 + j];
+                bNN[1] = tabB[(t + 20) * 16 + j];
+                load_ops(tX, bN, ops);
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const uint32_t w = requant_relu4_p23<P23>(acc[u], mlA, cA);
@@ -377,20 +404,27 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
             const v4i biB = *(const v4i*)(cst + cv * 32 + 4 * g);
             const v4f mlB = *(const v4f*)(cst + cv * 32 + 16 + 4 * g);
             int8_t* outp = p.out + b0 * (int64_t)S::IMG;
-            int nb0 = tabB[wave * 16 + j], nb1 = tabB[(wave + 4) * 16 + j];
-            for (int t = wave; t < n_tiles; t += 8) {
-                const int base[2] = {nb0, nb1};
-                nb0 = tabB[(t + 8) * 16 + j];
-                nb1 = tabB[(t + 12) * 16 + j];
-                uint32_t xr[2];
-                v4i acc[2] = {biB, biB};
+            int bN[2] = {tabB[wave * 16 + j], tabB[(wave + 4) * 16 + j]};
+            int bNN[2] = {tabB[(wave + 8) * 16 + j], tabB[(wave + 12) * 16 + j]};
+            v4i ops[2][S::KS_B];
+            uint32_t xn[2];
+            load_ops(tM, bN, ops);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) xr[u] = *(const uint32_t*)(xraw + (uint32_t)min((t + 4 * u) * 16 + j, total - 1) * 16u + 4 * g);
+            for (int u = 0; u < 2; ++u) xn[u] = *(const uint32_t*)(xraw + (uint32_t)min((wave + 4 * u) * 16 + j, total - 1) * 16u + 4 * g);
+            for (int t = wave; t < n_tiles; t += 8) {
+                const int base[2] = {bN[0], bN[1]};
+                const uint32_t xr[2] = {xn[0], xn[1]};
+                v4i acc[2] = {biB, biB};
 #pragma unroll
                 for (int st = 0; st < S::KS_B; ++st)
 #pragma unroll
-                    for (int u = 0; u < 2; ++u)
-                        acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st], *(const v4i*)(tM + base[u] + koffB[st]), acc[u], 0, 0, 0);
+                    for (int u = 0; u < 2; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st], ops[u][st], acc[u], 0, 0, 0);
+                bN[0] = bNN[0]; bN[1] = bNN[1];
+                bNN[0] = tabB[(t + 16) * 16 + j];
+                bNN[1] = tabB[(t + 20) * 16 + j];
+                load_ops(tM, bN, ops);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) xn[u] = *(const uint32_t*)(xraw + (uint32_t)min((t + 8 + 4 * u) * 16 + j, total - 1) * 16u + 4 * g);
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int col = (t + 4 * u) * 16 + j;
