@@ -52,6 +52,19 @@ def io_bytes(net):
     return obs + 4 + net.n_actions * 4 + 4 + 4
 
 
+def kernel_source_hash():
+    """sha256 over the kernel sources: a counter summary under profiles/ quotes the hash of the sources it was measured
+    on, and is only used while it still matches."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2211_15023_amd", "csrc", "*"))):
+        if f.endswith((".hip", ".h")):
+            h.update(os.path.basename(f).encode())
+            h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def time_forward(pol, x, u, outs, steps, warmup, **kw):
     import torch
     for _ in range(warmup):
@@ -81,7 +94,11 @@ def main():
                     help="also measure what this machine sustains: register-resident MFMA loops and a streaming copy")
     ap.add_argument("--copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference for HBM counters)")
+    ap.add_argument("--source-hash", action="store_true", help="print the hash of the kernel sources and exit")
     args = ap.parse_args()
+    if args.source_hash:
+        print(kernel_source_hash())
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (states are independent rows; a fleet of actors "
               "shards by row with no exchange on the forward path). Run with --gpus 1.", file=sys.stderr)
@@ -209,11 +226,17 @@ def main():
                         launches_per_step=launches)
     roofline["event_span_us"] = round(span_s * 1e6, 2)
     roofline["event_cost_us"] = round(event_s * 1e6, 2)
+    # HBM bytes per launch of that kernel from the committed counter summary, if it was measured on these very sources
     tfile = os.path.join(ROOT, "profiles", f"traffic_cfg{ci}_B{B}.txt")
+    roofline["traffic_note"] = "no counter summary for this workload"
     if os.path.exists(tfile):
-        for line in open(tfile):
-            if line.startswith("traffic_bytes_per_launch"):
-                roofline["traffic"] = float(line.split("=")[1])
+        kv = dict(l.strip().split("=", 1) for l in open(tfile) if "=" in l and not l.startswith("#"))
+        if kv.get("kernel_source_hash") == kernel_source_hash():
+            roofline["traffic"] = float(kv["traffic_bytes_per_launch"])
+            roofline["traffic_note"] = "FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from " + os.path.basename(tfile)
+        else:
+            roofline["traffic_note"] = ("stale: " + os.path.basename(tfile) + " was measured on other kernel sources (hash " +
+                                        str(kv.get("kernel_source_hash")) + ", now " + kernel_source_hash() + ")")
 
     total_macs = sum(macs.values())
     whole = dict(useful_tops=round(2 * total_macs * B / sec / 1e12, 2), frac_int8_peak=round(2 * total_macs * B / sec / PEAK["int8"], 4),
@@ -233,6 +256,20 @@ def main():
         s160 = time_forward(student, x[:b160].contiguous(), u[:b160].contiguous(), o160, 2000, 200, **kw160)
         t160 = time_forward(teacher, xt[:b160].contiguous(), u[:b160].contiguous(), teacher.alloc_outputs(b160), 1000, 100, **kw160)
         extra["latency_B160_us"] = dict(student=round(s160 * 1e6, 2), teacher=round(t160 * 1e6, 2))
+        # what a launch costs on this machine: chains of a kernel that does nothing, back to back on the same stream,
+        # timed like the forwards (host clock around 2000 launches) -- the floor under the latency of the small batches
+        for _ in range(200):
+            A.accerl_probe_empty()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2000):
+            A.accerl_probe_empty()
+        torch.cuda.synchronize()
+        floor = (time.perf_counter() - t0) / 2000
+        n_l = int(round(n_launch_step))
+        extra["launch_floor_us"] = dict(one_empty_launch=round(floor * 1e6, 2), launches_per_forward=n_l,
+                                        floor_per_forward=round(floor * n_l * 1e6, 2),
+                                        student_B160_over_floor=round(s160 / (floor * n_l), 2))
 
         # spread of the per-call time: 200 chains of 10 back-to-back calls, an event before and after each chain
         # (both on the stream the kernels run on), p10 / median / p90 of chain time / 10
@@ -367,6 +404,18 @@ def main():
             dt = (time.perf_counter() - t0) / reps
         cpu = dict(value=round(nsamp / dt, 1), unit="states/s", cores=OL.num_threads(), kind="oracle",
                    sample=f"first {nsamp} of the {B} benchmark states, int8 student, {dt:.2f} s per pass")
+        # the same oracle on one thread, on a prefix sized for a few seconds
+        n1 = max(1, min(nsamp, int(nsamp / dt * 3.0 / max(1, OL.num_threads()))))
+        all_threads = OL.num_threads()
+        OL.set_threads(1)
+        try:
+            t0 = time.perf_counter()
+            oracle.forward_int8(ns, qp, x_host[:n1], u_host[:n1], **{k: v[:n1] for k, v in okw.items()})
+            d1 = time.perf_counter() - t0
+        finally:
+            OL.set_threads(all_threads)
+        cpu["single_thread"] = dict(value=round(n1 / d1, 1), unit="states/s", cores=1,
+                                    sample=f"first {n1} states, {d1:.2f} s")
         # the same sample doubles as an end-of-run parity check of the timed configuration
         got = outs[0][:nsamp].cpu().numpy()
         extra["parity_sample_logits_equal"] = bool(np.array_equal(got, ref["logits"])) if not student.recurrent else None

@@ -297,6 +297,9 @@ int accerl_vtrace(const float* logits_original, const float* logits_smaller, con
  */
 int accerl_probe_mfma(int32_t bf16, int32_t iters, int32_t* sink, void* hip_stream);
 int accerl_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
+/* One launch of a kernel that does nothing (one wavefront): chains of it give the launch floor that the latency of
+ * the small configured batches is quoted against. */
+int accerl_probe_empty(void* hip_stream);
 
 /* Message of the last error on this thread ("" if none). */
 const char* accerl_last_error(void);

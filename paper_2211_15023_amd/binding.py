@@ -64,6 +64,8 @@ def load_library():
     lib.accerl_probe_mfma.restype = C.c_int
     lib.accerl_probe_copy.argtypes = [vp, vp, i64, vp]
     lib.accerl_probe_copy.restype = C.c_int
+    lib.accerl_probe_empty.argtypes = [vp]
+    lib.accerl_probe_empty.restype = C.c_int
     lib.accerl_actor_forward_mixture.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.accerl_actor_forward_mixture.restype = C.c_int
     lib.accerl_mixture_alpha.argtypes = [C.c_double, C.c_double, C.c_double]
@@ -251,6 +253,10 @@ def accerl_probe_mfma(bf16, iters, sink, stream=None):
 def accerl_probe_copy(src, dst, stream=None):
     n = src.numel() * src.element_size()
     _check(load_library().accerl_probe_copy(_ptr(src), _ptr(dst), n, _stream(stream)))
+
+
+def accerl_probe_empty(stream=None):
+    _check(load_library().accerl_probe_empty(_stream(stream)))
 
 
 def accerl_monitor_kl(logits_original, logits_smaller, out_kl, out_entropy, out_stats, stream=None):

@@ -338,12 +338,10 @@ int plan_conv(Builder& B, int layer, int sub, const TensorSpec& t, Elem el, bool
     // MFMAs: they get small batches, so that the kernel needs few staging registers and four workgroups
     // share a compute unit.
     const bool thin = NT == 1 && k_steps <= 3 && !getenv("ACCERL_NO_THIN");
-    int thin_units = 1024;
-    if (const char* env = getenv("ACCERL_THIN_UNITS")) { const int v = atoi(env); if (v >= 256) thin_units = v; }
+    const int thin_units = 1024;
     const int band_units = thin ? thin_units : 4096;
     if (thin) {   // LDS per workgroup small enough for several workgroups per compute unit
-        int thin_lds = 32 * 1024;
-        if (const char* env = getenv("ACCERL_THIN_LDS")) { const int v = atoi(env); if (v >= 8192) thin_lds = v; }
+        const int thin_lds = 32 * 1024;
         if (budget > thin_lds) budget = thin_lds;
     }
     // fused pooling: the requantized conv rows of a band wait in LDS for the pooling pass

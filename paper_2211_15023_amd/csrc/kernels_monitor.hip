@@ -28,15 +28,49 @@ __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// max and log-sum-exp normaliser of one row in LDS: logp[a] = row[a] - m - lz.  Lane l walks its row
-// starting at element `rot` = l mod A, so that the lanes of a wavefront (rows A floats apart) do not all
-// hit the same LDS bank when A is a multiple of 16.
-__device__ __forceinline__ void row_norm(const float* row, int A, int rot, float& m, float& lz) {
-    m = row[rot];
+// Row arithmetic.  With m = max_a l_a, d_a = l_a - m, e_a = exp(d_a), Z = sum_a e_a the softmax is p_a = e_a / Z and
+// log p_a = d_a - log Z, so that (o = original, s = smaller policy)
+//     KL(o || s) = sum_a p_o,a (log p_o,a - log p_s,a) = (sum_a e_o,a (d_o,a - d_s,a)) / Z_o - log Z_o + log Z_s
+//     H(s)       = -sum_a p_s,a log p_s,a              = log Z_s - (sum_a e_s,a d_s,a) / Z_s
+// two exponentials per action instead of one per probability and one per normaliser.  Identical rows give d_o = d_s and
+// Z_o = Z_s bit for bit, hence KL = 0 exactly.  The exponential is the hardware's 2^x on x log2(e) (d lies in [-large, 0]:
+// about 1e-6 relative error over the range the logits span), the logarithm its log2 -- well inside the 2e-4 relative
+// that per-row values are held to against an fp64 evaluation.
+// Lane l walks its row in LDS starting at element `rot` = l mod A, so that the lanes of a wavefront (rows A floats
+// apart) do not all hit the same LDS bank when A is a multiple of 16.
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.693147180559945309f; }
+
+__device__ __forceinline__ float row_max(const float* row, int A, int rot) {
+    float m = row[rot];
     for (int a = 1; a < A; ++a) { int k = a + rot; k -= (k >= A) ? A : 0; m = fmaxf(m, row[k]); }
+    return m;
+}
+
+// KL(o || s) and H(s) of one pair of rows
+__device__ __forceinline__ void row_kl_entropy(const float* ro, const float* rs, int A, int rot, float& kl, float& h) {
+    const float mo = row_max(ro, A, rot), ms = row_max(rs, A, rot);
+    float zo = 0.0f, zs = 0.0f, so = 0.0f, ss = 0.0f;
+    for (int a = 0; a < A; ++a) {
+        int k = a + rot;
+        k -= (k >= A) ? A : 0;
+        const float d_o = ro[k] - mo, d_s = rs[k] - ms;
+        const float eo = fast_exp(d_o), es = fast_exp(d_s);
+        zo += eo; zs += es;
+        so += eo * (d_o - d_s);
+        ss += es * d_s;
+    }
+    const float lzo = fast_log(zo), lzs = fast_log(zs);
+    kl = so / zo - lzo + lzs;
+    h = lzs - ss / zs;
+}
+
+// log of the normaliser of one row: log p_a = (l_a - m) - lz
+__device__ __forceinline__ void row_norm(const float* row, int A, int rot, float& m, float& lz) {
+    m = row_max(row, A, rot);
     float Z = 0.0f;
-    for (int a = 0; a < A; ++a) { int k = a + rot; k -= (k >= A) ? A : 0; Z += expf(row[k] - m); }
-    lz = logf(Z);
+    for (int a = 0; a < A; ++a) { int k = a + rot; k -= (k >= A) ? A : 0; Z += fast_exp(row[k] - m); }
+    lz = fast_log(Z);
 }
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -74,17 +108,8 @@ __global__ __launch_bounds__(MON_WAVES * 64) void kl_rows_kernel(const float* __
             const float* ro = so + lane * A;
             const float* rs = ss + lane * A;
             const int rot = lane % A;
-            float mo, lzo, ms, lzs;
-            row_norm(ro, A, rot, mo, lzo);
-            row_norm(rs, A, rot, ms, lzs);
-            float kl = 0.0f, h = 0.0f;
-            for (int a = 0; a < A; ++a) {
-                int k = a + rot;
-                k -= (k >= A) ? A : 0;
-                const float lpo = ro[k] - mo - lzo, lps = rs[k] - ms - lzs;
-                kl += expf(lpo) * (lpo - lps);
-                h -= expf(lps) * lps;
-            }
+            float kl, h;
+            row_kl_entropy(ro, rs, A, rot, kl, h);
             if (out_kl) out_kl[r0 + lane] = kl;
             if (out_ent) out_ent[r0 + lane] = h;
             s_kl += (double)kl;
@@ -157,7 +182,7 @@ __global__ __launch_bounds__(MON_WAVES * 64) void is_ratio_kernel(const float* _
             row_norm(rs, A, rot, ms, lzs);
             int a = act[r0 + lane];
             a = min(max(a, 0), A - 1);
-            ratio[r0 + lane] = expf((ro[a] - mo - lzo) - (rs[a] - ms - lzs));
+            ratio[r0 + lane] = fast_exp((ro[a] - mo - lzo) - (rs[a] - ms - lzs));
         }
         wave_sync_lds();
     }

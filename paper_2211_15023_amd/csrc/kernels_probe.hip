@@ -29,9 +29,18 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const v4i* __restrict_
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// nothing at all: what one launch costs on this machine
+__global__ void empty_kernel() {}
+
 }  // namespace accerl
 
 using namespace accerl;
+
+extern "C" int accerl_probe_empty(void* hip_stream) {
+    empty_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)hip_stream>>>();
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? ACCERL_OK : set_error(ACCERL_EHIP, hipGetErrorString(e));
+}
 
 extern "C" int accerl_probe_mfma(int32_t bf16, int32_t iters, int32_t* sink, void* hip_stream) {
     if (iters < 1 || !sink) return set_error(ACCERL_EINVAL, "probe: iters >= 1 and a device sink word are needed");

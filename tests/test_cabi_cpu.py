@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(A):
     names = set(re.findall(r"\b(accerl_[a-z_0-9]+)\s*\(", hdr))
     assert {"accerl_policy_create", "accerl_actor_forward", "accerl_actor_forward_teacher",
             "accerl_actor_forward_recurrent", "accerl_actor_forward_debug", "accerl_policy_destroy",
-            "accerl_last_error", "accerl_blob_sizes", "accerl_monitor_kl", "accerl_monitor_kl_noalloc", "accerl_vtrace", "accerl_distill_loss", "accerl_actor_forward_mixture", "accerl_mixture_alpha", "accerl_probe_mfma", "accerl_probe_copy"} <= names
+            "accerl_last_error", "accerl_blob_sizes", "accerl_monitor_kl", "accerl_monitor_kl_noalloc", "accerl_vtrace", "accerl_distill_loss", "accerl_actor_forward_mixture", "accerl_mixture_alpha", "accerl_probe_mfma", "accerl_probe_copy", "accerl_probe_empty"} <= names
     lib = A.load_library()
     for n in names:
         assert hasattr(lib, n), n
