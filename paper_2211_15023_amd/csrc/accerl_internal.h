@@ -33,6 +33,9 @@ struct MlpParams {
     const int32_t* bias;     // [layer][64] integer bias (heads last)
     const float* mult;       // [layer][64] requant multiplier (heads: dequant d)
     int lo[MLP_MAX_LAYERS];  // lower clamp per hidden layer (0 = fused ReLU, -127 otherwise)
+    int k32;                 // D <= 32: the first layer's fragments are laid out for the K = 32 MFMA (8 features per lane)
+    int p23;                 // every hidden layer has the fused ReLU and accumulators below 2^23 whatever the input
+    const float* cfma;       // [layer][64] -2^23 * mult (p23 only)
     // debug taps (NULL = off): accumulator / activation of layer tap_layer, [B, n] row-major
     int32_t* tap_acc;
     int8_t* tap_act;

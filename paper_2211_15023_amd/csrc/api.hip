@@ -585,6 +585,8 @@ int build_plan(Builder& B) {
             std::vector<float> ml((size_t)nl * 64, 0.f);
             float s_in = act[0];
             int Kprev = a->obs_c;
+            m.k32 = a->obs_c <= 32 ? 1 : 0;
+            bool p23 = !getenv("ACCERL_NO_P23");
             for (int l = 0; l < nl; ++l) {
                 const TensorSpec& t = B.tensor(l < a->n_layers ? l : a->n_layers, 0);
                 const int N = (int)t.rows, K = (int)t.cols;
@@ -597,7 +599,9 @@ int build_plan(Builder& B) {
                         for (int e = 0; e < 16; ++e) {
                             // layer 0 reads features in natural order; later layers read the accumulator
                             // layout of the layer before: slot 4*t' + r of lane group g is unit 16t' + 4g + r
-                            const int k = (l == 0) ? 16 * g + e : 16 * (e >> 2) + 4 * g + (e & 3);
+                            // (observations of at most 32 features go through the K = 32 MFMA: 8 features per lane group)
+                            int k = (l == 0) ? 16 * g + e : 16 * (e >> 2) + 4 * g + (e & 3);
+                            if (l == 0 && m.k32) k = (e < 8) ? 8 * g + e : K;
                             if (k < K) dst[e] = (char)B.wq(t)[(int64_t)n * K + k];
                         }
                     }
@@ -605,6 +609,12 @@ int build_plan(Builder& B) {
                     bq[l * 64 + n] = Builder::biasq(B.bias(t)[n], s_in, B.sw(t)[n]);
                     ml[l * 64 + n] = l < a->n_layers ? Builder::mult(s_in, B.sw(t)[n], s_out)
                                                       : (float)((double)s_in * (double)B.sw(t)[n]);
+                    if (l < a->n_layers) {   // the largest accumulator any input (-127 .. 127 per feature) can produce
+                        int64_t wabs = 0;
+                        for (int k = 0; k < K; ++k) { const int v = B.wq(t)[(int64_t)n * K + k]; wabs += v < 0 ? -v : v; }
+                        const int64_t b = bq[l * 64 + n];
+                        if (!a->layers[l].relu || b + 127 * wabs >= (1 << 23) || b <= -(1 << 30)) p23 = false;
+                    }
                 }
                 if (l < a->n_layers) { m.lo[l] = a->layers[l].relu ? 0 : -127; s_in = s_out; }
                 (void)Kprev; Kprev = N;
@@ -612,6 +622,11 @@ int build_plan(Builder& B) {
             st.o_w = B.put(frag.data(), frag.size());
             st.o_bias = B.put(bq.data(), bq.size() * 4);
             st.o_mult = B.put(ml.data(), ml.size() * 4);
+            // three-instruction requantization (see requant_relu4_p23): c = -2^23 * m, exact
+            m.p23 = p23 ? 1 : 0;
+            std::vector<float> cf((size_t)a->n_layers * 64, 0.f);
+            for (size_t i = 0; i < cf.size(); ++i) cf[i] = ml[i] * -8388608.0f;
+            st.o_lut = B.put(cf.data(), cf.size() * 4);
             pol->steps.push_back(st);
             return ACCERL_OK;
         }
@@ -993,6 +1008,7 @@ int run(accerl_policy* p, const Call& c) {
                     m.wfrag = (const v4i*)(p->consts + s.o_w);
                     m.bias = (const int32_t*)(p->consts + s.o_bias);
                     m.mult = (const float*)(p->consts + s.o_mult);
+                    m.cfma = (const float*)(p->consts + s.o_lut);
                     m.tap_layer = -2; m.tap_acc = nullptr; m.tap_act = nullptr; m.tap_n = 0;
                     if (c.debug) {
                         m.tap_layer = c.layer; m.tap_n = (int)tap_elems;
