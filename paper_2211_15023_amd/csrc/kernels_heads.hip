@@ -28,6 +28,7 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
     const bool live = row < p.B;
     if (!live) row = p.B - 1;
 
+    const float u_row = p.uniforms ? p.uniforms[row] : 0.0f;      // requested first: the sampler at the end needs it
     // this lane's K chunks of its state: unconditional loads, the tail chunk rebuilt below
     v4i xb[KM];
     const char* xrow = (const char*)p.x + row * p.Kp_bytes;
@@ -83,8 +84,100 @@ __global__ __launch_bounds__(HD_WAVES * 64) void heads_kernel(const HeadsParams 
         }
     }
 
-    // heads -> staging area (outputs 16t + 4g + r of state j)
     const int A = p.A;
+    if constexpr (NT <= 2) {
+        // At most 31 actions: a state's logits and value are the 4 NT accumulators of each of its four lanes (lane
+        // group g holds outputs 16t + 4g .. 16t + 4g + 3), so the normaliser, the cumulative sums and the sampled action
+        // come from in-lane arithmetic plus row-pair / half-wave swaps: no staging area and no serial scan.  Sums are
+        // formed block-wise instead of in index order: they differ from an index-order evaluation by rounding (1e-7
+        // relative), far inside the 1e-5 band around a CDF boundary in which a sampled action may differ; the
+        // exponential is the hardware's 2^x (about 1e-7 relative per unit of |logit - max|).
+        auto pair16 = [](unsigned v) { return __builtin_amdgcn_permlane16_swap(v, v, false, false); };   // {even row, odd row} of the lane's row pair
+        auto pair32 = [](unsigned v) { return __builtin_amdgcn_permlane32_swap(v, v, false, false); };   // {lower half, upper half}
+        float o[NT][4];
+        bool is_logit[NT][4];
+        float m = -3.0e38f;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            v4f ml = {1.f, 1.f, 1.f, 1.f};
+            if constexpr (EL == EL_I8) ml = *(const v4f*)(p.mult + 16 * t + 4 * g);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int n = 16 * t + 4 * g + r;
+                if constexpr (EL == EL_I8) {
+                    o[t][r] = (float)acc_i[t][r] * ml[r];
+                    if (p.tap_acc && live && n <= A) p.tap_acc[row * (A + 1) + n] = acc_i[t][r];
+                } else {
+                    o[t][r] = acc_f[t][r];
+                }
+                is_logit[t][r] = n < A;
+                m = fmaxf(m, is_logit[t][r] ? o[t][r] : -3.0e38f);
+            }
+        }
+        {
+            const auto a = pair16(__float_as_uint(m));
+            m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+            const auto b = pair32(__float_as_uint(m));
+            m = fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+        }
+        float cum[NT][4], before[NT], Z = 0.0f;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            float run = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                run += is_logit[t][r] ? __builtin_amdgcn_exp2f((o[t][r] - m) * 1.44269504088896341f) : 0.0f;
+                cum[t][r] = run;
+            }
+            const auto t16 = pair16(__float_as_uint(run));
+            const float s_even = __uint_as_float(t16[0]), s_pair = s_even + __uint_as_float(t16[1]);
+            const auto t32 = pair32(__float_as_uint(s_pair));
+            const float s_low = __uint_as_float(t32[0]);
+            // exp terms in front of this lane's: all of the blocks before t, and block t's lane groups below g
+            before[t] = Z + ((g & 1) ? s_even : 0.0f) + ((g & 2) ? s_low : 0.0f);
+            Z += s_low + __uint_as_float(t32[1]);
+        }
+        if (p.logits && live) {
+            // rows of A floats: 16- or 8-byte stores where the row pitch allows (neighbouring states fill the lines)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                float* dst = p.logits + row * A + 16 * t + 4 * g;
+                if ((A & 3) == 0) {
+                    if (is_logit[t][3]) *(v4f*)dst = (v4f){o[t][0], o[t][1], o[t][2], o[t][3]};
+                } else if ((A & 1) == 0) {
+                    typedef float v2f __attribute__((ext_vector_type(2)));
+                    if (is_logit[t][1]) *(v2f*)dst = (v2f){o[t][0], o[t][1]};
+                    if (is_logit[t][3]) *(v2f*)(dst + 2) = (v2f){o[t][2], o[t][3]};
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (is_logit[t][r]) dst[r] = o[t][r];
+                }
+            }
+        }
+        if (p.action) {
+            const float thr = u_row * Z;
+            int cnt = 0;                                   // actions whose cumulative sum does not exceed the threshold
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) cnt += (is_logit[t][r] && !(before[t] + cum[t][r] > thr)) ? 1 : 0;
+            const auto c16 = pair16((unsigned)cnt);
+            cnt = (int)(c16[0] + c16[1]);
+            const auto c32 = pair32((unsigned)cnt);
+            cnt = (int)(c32[0] + c32[1]);
+            if (live) {
+                if (g == 0) p.action[row] = min(cnt, A - 1);
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (16 * t + 4 * g + r == A) p.value[row] = o[t][r];
+            }
+        }
+        return;
+    }
+    // heads -> staging area (outputs 16t + 4g + r of state j)
     float* stage = s_l + wave * 2 * 16 * HD_PITCH;
     float* stage_e = stage + 16 * HD_PITCH;
 #pragma unroll
