@@ -189,43 +189,83 @@ __global__ __launch_bounds__(MON_WAVES * 64) void is_ratio_kernel(const float* _
 }
 
 // ---- backward scan per environment: v_s - V(x_s) = delta_s + gamma_s c_s (v_{s+1} - V(x_{s+1}))
-__global__ __launch_bounds__(256) void vtrace_scan_kernel(const float* __restrict__ rewards, const float* __restrict__ discounts,
-                                                          const float* __restrict__ values, const float* __restrict__ bootstrap,
-                                                          int64_t T, int64_t B, float rho_bar, float c_bar,
-                                                          float* __restrict__ rho /* in: ratio, out: clipped */,
-                                                          float* __restrict__ vs, float* __restrict__ pg_adv) {
-    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (b >= B) return;
-    float v_next = bootstrap[b];      // V(x_{t+1})
-    float vs_next = v_next;           // v_{t+1}
-    float acc = 0.0f;                 // v_{t+1} - V(x_{t+1})
-    // steps are taken eight at a time, newest first: the loads of a group do not depend on the
-    // recurrence and are all in flight together
-    constexpr int CH = 8;
-    for (int64_t t1 = T; t1 > 0; t1 -= CH) {
-        float ra[CH], rw[CH], ga[CH], va[CH];
+// A scan with one lane per environment leaves the chip nearly empty (B / 64 wavefronts walking T dependent steps).  The
+// recurrence a_t = delta_t + k_t a_{t+1} (k_t = gamma_t c_t) is linear, so a run of steps [t0, t1) acts on the value
+// entering it as a_t0 = A + M a_t1 with A, M computed from that run alone.  A workgroup takes 64 environments; its
+// wavefronts split the last (up to) NSEG * L steps into runs of L steps held in registers: each forms its (A, M) with one
+// backward pass, the pairs meet in LDS, every wavefront folds the pairs of the runs behind it into the value entering
+// its run and walks its registers a second time to write v_s, the clipped weights and the advantages.  Longer unrolls
+// repeat this from the end of the trajectory towards its start, carrying a_t across.  delta_t needs V(x_{t+1}) only,
+// which is an input.  The order of the floating-point operations is fixed by (T, L), not by the launch.
+constexpr int VT_NSEG = 16;
+template <int L>
+__global__ __launch_bounds__(VT_NSEG * 64) void vtrace_scan_kernel(const float* __restrict__ rewards, const float* __restrict__ discounts,
+                                                                   const float* __restrict__ values, const float* __restrict__ bootstrap,
+                                                                   int64_t T, int64_t B, float rho_bar, float c_bar,
+                                                                   float* __restrict__ rho /* in: ratio, out: clipped */,
+                                                                   float* __restrict__ vs, float* __restrict__ pg_adv) {
+    __shared__ float sA[VT_NSEG][64], sM[VT_NSEG][64];
+    __shared__ float s_carry[64];
+    const int lane = threadIdx.x & 63, seg = threadIdx.x >> 6;
+    const int nseg = blockDim.x >> 6;
+    const int64_t b = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t bc = b < B ? b : B - 1;                  // lanes past the batch repeat the last environment, store nothing
+    if (seg == 0) s_carry[lane] = 0.0f;                    // a_T = v_T - V(x_T) = 0
+    for (int64_t hi = T; hi > 0; hi -= (int64_t)nseg * L) {
+        // this wavefront's run: steps [t0, t1) with t1 = hi - seg * L; runs past the start of the trajectory are empty
+        const int64_t t1 = hi - (int64_t)seg * L;
+        const int n = (int)(t1 <= 0 ? 0 : (t1 < L ? t1 : L));
+        const int64_t t0 = t1 - n;
+        float rh[L], kk[L], dl[L], vv[L], rw[L], gg[L];
+        float v_after = 0.0f;                              // V(x_t1)
+        if (n > 0) v_after = (t1 == T) ? bootstrap[bc] : values[t1 * B + bc];
 #pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            const int64_t t = t1 - 1 - k;
-            const int64_t i = (t >= 0 ? t : 0) * B + b;
-            ra[k] = rho[i]; rw[k] = rewards[i]; ga[k] = discounts[i]; va[k] = values[i];
+        for (int i = 0; i < L; ++i) {                      // i counts back from the end of the run
+            const int64_t t = t1 - 1 - i;
+            const int64_t idx = (t >= 0 ? t : 0) * B + bc;
+            rh[i] = rho[idx]; rw[i] = rewards[idx]; gg[i] = discounts[idx]; vv[i] = values[idx];
         }
+        float A = 0.0f, M = 1.0f;
+        {
+            float v_next = v_after;
 #pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            const int64_t t = t1 - 1 - k;
-            if (t < 0) break;
-            const int64_t i = t * B + b;
-            const float ratio = ra[k], r = rw[k], g = ga[k], v = va[k];
-            const float rh = fminf(rho_bar, ratio), c = fminf(c_bar, ratio);
-            const float delta = rh * (r + g * v_next - v);
-            acc = delta + g * c * acc;
-            const float vs_t = v + acc;
-            if (pg_adv) pg_adv[i] = rh * (r + g * vs_next - v);
-            vs[i] = vs_t;
-            rho[i] = rh;
-            v_next = v;
-            vs_next = vs_t;
+            for (int i = 0; i < L; ++i) {
+                const float ratio = rh[i];
+                const float r_c = fminf(rho_bar, ratio), c_c = fminf(c_bar, ratio);
+                rh[i] = r_c;
+                kk[i] = gg[i] * c_c;
+                dl[i] = r_c * (rw[i] + gg[i] * v_next - vv[i]);
+                if (i < n) { A = dl[i] + kk[i] * A; M = kk[i] * M; }
+                v_next = vv[i];
+            }
         }
+        sA[seg][lane] = A;
+        sM[seg][lane] = M;
+        __syncthreads();
+        // the value entering this run: the carry from beyond `hi`, pushed through the runs behind this one (lower seg)
+        float acc = s_carry[lane];
+        for (int k = 0; k < seg; ++k) acc = sA[k][lane] + sM[k][lane] * acc;
+        {
+            float vs_next = v_after + acc;                 // v_{t1}
+#pragma unroll
+            for (int i = 0; i < L; ++i) {
+                if (i < n) {
+                    const int64_t idx = (t1 - 1 - i) * B + b;
+                    acc = dl[i] + kk[i] * acc;
+                    const float vs_t = vv[i] + acc;
+                    if (b < B) {
+                        if (pg_adv) pg_adv[idx] = rh[i] * (rw[i] + gg[i] * vs_next - vv[i]);
+                        vs[idx] = vs_t;
+                        rho[idx] = rh[i];
+                    }
+                    vs_next = vs_t;
+                }
+            }
+        }
+        __syncthreads();                                    // every wavefront has read the pairs and the carry
+        if (seg == nseg - 1) s_carry[lane] = acc;           // the run that reaches furthest back hands a_t0 on
+        (void)t0;
+        __syncthreads();
     }
 }
 
@@ -358,8 +398,15 @@ extern "C" int accerl_vtrace(const float* logits_original, const float* logits_s
     is_ratio_kernel<<<dim3(blocks), dim3(MON_WAVES * 64), lds, s>>>(logits_original, logits_smaller, actions, R, A, out_rho);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("is_ratio_kernel", e);
-    vtrace_scan_kernel<<<dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s>>>(rewards, discounts, values, bootstrap, T, B, rho_bar, c_bar,
-                                                                              out_rho, out_vs, out_pg_adv);
+    // runs of 16 steps for long unrolls, of 4 for short ones; as many wavefronts per workgroup as there are runs (at most 16)
+    const dim3 vgrid((unsigned)((B + 63) / 64));
+    if (T > 32) {
+        const int nseg = (int)((T + 15) / 16 < VT_NSEG ? (T + 15) / 16 : VT_NSEG);
+        vtrace_scan_kernel<16><<<vgrid, dim3(nseg * 64), 0, s>>>(rewards, discounts, values, bootstrap, T, B, rho_bar, c_bar, out_rho, out_vs, out_pg_adv);
+    } else {
+        const int nseg = (int)((T + 3) / 4);
+        vtrace_scan_kernel<4><<<vgrid, dim3(nseg * 64), 0, s>>>(rewards, discounts, values, bootstrap, T, B, rho_bar, c_bar, out_rho, out_vs, out_pg_adv);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail("vtrace_scan_kernel", e);
     return ACCERL_OK;
 }

@@ -68,8 +68,11 @@ def test_kl_monitor_large_batch_stats(A):
     assert np.allclose(st.cpu().numpy(), st_o, rtol=2e-4, atol=1e-6)
 
 
+# the scan splits a trajectory into runs of 4 steps (T <= 32) or 16 steps handled by different wavefronts, and walks
+# unrolls of more than 256 steps in several rounds: 40 and 257 steps end in a cut run, 300 and 257 need a second round
 @pytest.mark.parametrize("T,B,nA,rb,cb", [(1, 1, 2, 1.0, 1.0), (16, 300, 18, 1.0, 1.0), (20, 257, 6, 1.5, 0.8),
-                                         (5, 4096, 18, 1.0, 1.0), (64, 33, 64, 2.0, 1.0)])
+                                         (5, 4096, 18, 1.0, 1.0), (64, 33, 64, 2.0, 1.0), (40, 65, 4, 1.0, 0.9),
+                                         (257, 64, 3, 1.0, 1.0), (300, 70, 5, 1.2, 1.0), (32, 64, 18, 1.0, 1.0), (33, 5, 18, 1.0, 1.0)])
 def test_vtrace_matches_oracle(A, T, B, nA, rb, cb):
     tr = wl.make_trajectory(T, B, nA, p_done=0.05)
     vs_o, adv_o, rho_o = L.vtrace(**tr, rho_bar=rb, c_bar=cb)
