@@ -51,12 +51,14 @@ struct StackParams {
     int64_t B;
 };
 
-constexpr int ST_THREADS = 256;
 constexpr int st_up16(int v) { return (v + 15) / 16 * 16; }
 
-template <bool U8, int CI, int HIN, int C, int G_>
+template <bool U8, int CI, int HIN, int C, int G_, int NW_>
 struct StShape {
     static constexpr int G = G_;
+    static constexpr int NW = NW_;                            // wavefronts per workgroup
+    static constexpr int ST_THREADS = NW * 64;
+    static constexpr int TU = NW >= 8 ? 1 : 2;                // block column tiles per wavefront and step
     static constexpr int P = 16 / C;                          // output pixels per MFMA column (2 for 8 channels)
     // input tile: one pixel of border on every side
     static constexpr int PITCH_IN = st_up16((HIN + 2) * CI);
@@ -94,7 +96,7 @@ struct StShape {
     static constexpr int O_RAW = O_TM + G * TILE_B;
     static constexpr int O_T1 = O_RAW + G * IMG;
     static constexpr int O_TABB = O_T1 + T1_BYTES;
-    static constexpr int O_CST = O_TABB + st_up16((TILES + 20) * 16 * 2);   // the block loops read two steps (up to 20 tiles) ahead
+    static constexpr int O_CST = O_TABB + st_up16((TILES + 3 * NW * TU) * 16 * 2);   // the block loops read their table two steps ahead
     static constexpr int LDS = O_CST + 5 * 2 * 16 * 4;
     static_assert(H % P == 0 && IMG == NPX * 16 && (U8 ? (HIN % 4 == 0 && CI == 4) : (HIN * CI) % 16 == 0), "shape");
     static_assert(G * TILE_IN + 64 < 65536 && G * TILE_B < 32768 && G * SLOTS < (1 << 20) && COLS < (1 << 20), "offsets");
@@ -114,9 +116,10 @@ __device__ __forceinline__ int max_with_left(int v) {
 }
 
 // P23: the first convolution of both blocks keeps its accumulators below 2^23 (see requant_relu4_p23)
-template <bool U8, int CI, int HIN, int C, int G, int MINB, bool P23>
-__global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackParams p) {
-    typedef StShape<U8, CI, HIN, C, G> S;
+template <bool U8, int CI, int HIN, int C, int G, int NW, int MINB, bool P23>
+__global__ __launch_bounds__(NW * 64, MINB) void stack_kernel(const StackParams p) {
+    typedef StShape<U8, CI, HIN, C, G, NW> S;
+    constexpr int ST_THREADS = S::ST_THREADS, TU = S::TU;
     typedef int v2i __attribute__((ext_vector_type(2)));
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* tin = smem;                                    // G bordered input tiles
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
                 ((v2i*)tab1)[sidx] = (v2i){(int)(a0 | (a1 << 16)), (int)(ox | (orr << 16))};
             }
         }
-        for (int c = tid; c < (S::TILES + 20) * 16; c += ST_THREADS) {
+        for (int c = tid; c < (S::TILES + 3 * NW * TU) * 16; c += ST_THREADS) {
             const int cc = min(c, S::COLS - 1);            // columns past the end repeat the last one (never stored)
             const int img = cc / S::NPX, w = cc - img * S::NPX, y = w / S::WP, xp = w - y * S::WP;
             tabB[c] = (uint16_t)(img * S::TILE_B + y * S::PITCH_B + xp * 16);
@@ -307,24 +310,35 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
                     }
                     finish(pooled, e[1] + (2 * rp + 1) * S::PITCH_B, e[2] + 2 * rp * S::H * C, e[3] != 0);
                 };
+                if constexpr (NW >= 8) {
+                    // four wavefronts per SIMD hide the read latency by themselves: one item at a time, fewer registers
+                    for (int it = wave; it < N_IT; it += NW) {
+                        issue(it, oA, eA, rpA);
+                        v4i c[5];
+#pragma unroll
+                        for (int k = 0; k < 5; ++k) c[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], oA[k], biC, 0, 0, 0);
+                        pool_store(c, eA, rpA);
+                    }
+                } else {
                 issue(wave, oA, eA, rpA);
-                for (int it = wave; it < N_IT; it += 8) {
+                for (int it = wave; it < N_IT; it += 2 * NW) {
                     v4i c[5];
 #pragma unroll
                     for (int k = 0; k < 5; ++k) c[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], oA[k], biC, 0, 0, 0);
-                    issue(it + 4, oB, eB, rpB);
+                    issue(it + NW, oB, eB, rpB);
                     pool_store(c, eA, rpA);
-                    if (it + 4 >= N_IT) break;
+                    if (it + NW >= N_IT) break;
 #pragma unroll
                     for (int k = 0; k < 5; ++k) c[k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[0], oB[k], biC, 0, 0, 0);
-                    issue(it + 8, oA, eA, rpA);
+                    issue(it + 2 * NW, oA, eA, rpA);
                     pool_store(c, eB, rpB);
+                }
                 }
             } else {
                 constexpr bool ODD = (HIN & 1) != 0;
                 const int n_slots = gc * S::SLOTS;
                 const int n_tiles = (n_slots - 1 + 14) / 15;
-                for (int t = wave; t < n_tiles; t += 4) {
+                for (int t = wave; t < n_tiles; t += NW) {
                     const int s = 15 * t + j;
                     const v2i e = ((const v2i*)tab1)[min(s, n_slots - 1)];
                     const uint32_t ex = (uint32_t)e[0], ey = (uint32_t)e[1];
@@ -362,39 +376,42 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
 
         const int total = gc * S::NPX;
         const int n_tiles = (total + 15) >> 4;
-        // Block convolutions: two column tiles per step; the window reads of the next step are issued before the current
-        // step's epilogue, and the table entries two steps ahead of their use.
-        auto load_ops = [&](const char* src, const int (&b)[2], v4i (&o)[2][S::KS_B]) {
+        // Block convolutions: TU column tiles per wavefront and step (tiles t, t + NW, ...); the window reads of the next
+        // step are issued before the current step's epilogue, and the table entries two steps ahead of their use.
+        constexpr int STEP = NW * TU;
+        auto load_ops = [&](const char* src, const int (&b)[TU], v4i (&o)[TU][S::KS_B]) {
 #pragma unroll
             for (int st = 0; st < S::KS_B; ++st)
 #pragma unroll
-                for (int u = 0; u < 2; ++u) o[u][st] = *(const v4i*)(src + b[u] + koffB[st]);
+                for (int u = 0; u < TU; ++u) o[u][st] = *(const v4i*)(src + b[u] + koffB[st]);
         };
         // ---- a block's first convolution: max(x, 0) -> inner tensor, requantized with the fused ReLU
         auto conv_a = [&](const v4i (&wA)[S::KS_B], int cv) {
             const v4i biA = *(const v4i*)(cst + cv * 32 + 4 * g) + (P23 ? P23_MAGIC : 0);
             const v4f mlA = *(const v4f*)(cst + cv * 32 + 16 + 4 * g);
             const v4f cA = mlA * -8388608.0f;
-            int bN[2] = {tabB[wave * 16 + j], tabB[(wave + 4) * 16 + j]};
-            int bNN[2] = {tabB[(wave + 8) * 16 + j], tabB[(wave + 12) * 16 + j]};
-            v4i ops[2][S::KS_B];
+            int bN[TU], bNN[TU];
+#pragma unroll
+            for (int u = 0; u < TU; ++u) { bN[u] = tabB[(wave + NW * u) * 16 + j]; bNN[u] = tabB[(wave + STEP + NW * u) * 16 + j]; }
+            v4i ops[TU][S::KS_B];
             load_ops(tX, bN, ops);
-            for (int t = wave; t < n_tiles; t += 8) {
-                const int base[2] = {bN[0], bN[1]};
-                v4i acc[2] = {biA, biA};
+            for (int t = wave; t < n_tiles; t += STEP) {
+                int base[TU];
+                v4i acc[TU];
+#pragma unroll
+                for (int u = 0; u < TU; ++u) { base[u] = bN[u]; acc[u] = biA; }
 #pragma unroll
                 for (int st = 0; st < S::KS_B; ++st)
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st], ops[u][st], acc[u], 0, 0, 0);
-                bN[0] = bNN[0]; bN[1] = bNN[1];
-                bNN[0] = tabB[(t + 16) * 16 + j];
-                bNN[1] = tabB[(t + 20) * 16 + j];
+                    for (int u = 0; u < TU; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wA[st], ops[u][st], acc[u], 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < TU; ++u) { bN[u] = bNN[u]; bNN[u] = tabB[(t + 2 * STEP + NW * u) * 16 + j]; }
                 load_ops(tX, bN, ops);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < TU; ++u) {
                     const uint32_t w = requant_relu4_p23<P23>(acc[u], mlA, cA);
                     // the column's own pixel(s) sit one row and one pixel inside its window
-                    if ((t + 4 * u) * 16 + j < total) *(uint32_t*)(tM + base[u] + S::PITCH_B + C + 4 * g) = w;
+                    if ((t + NW * u) * 16 + j < total) *(uint32_t*)(tM + base[u] + S::PITCH_B + C + 4 * g) = w;
                 }
             }
         };
@@ -404,30 +421,34 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
             const v4i biB = *(const v4i*)(cst + cv * 32 + 4 * g);
             const v4f mlB = *(const v4f*)(cst + cv * 32 + 16 + 4 * g);
             int8_t* outp = p.out + b0 * (int64_t)S::IMG;
-            int bN[2] = {tabB[wave * 16 + j], tabB[(wave + 4) * 16 + j]};
-            int bNN[2] = {tabB[(wave + 8) * 16 + j], tabB[(wave + 12) * 16 + j]};
-            v4i ops[2][S::KS_B];
-            uint32_t xn[2];
-            load_ops(tM, bN, ops);
+            int bN[TU], bNN[TU];
+            uint32_t xn[TU];
 #pragma unroll
-            for (int u = 0; u < 2; ++u) xn[u] = *(const uint32_t*)(xraw + (uint32_t)min((wave + 4 * u) * 16 + j, total - 1) * 16u + 4 * g);
-            for (int t = wave; t < n_tiles; t += 8) {
-                const int base[2] = {bN[0], bN[1]};
-                const uint32_t xr[2] = {xn[0], xn[1]};
-                v4i acc[2] = {biB, biB};
+            for (int u = 0; u < TU; ++u) {
+                bN[u] = tabB[(wave + NW * u) * 16 + j];
+                bNN[u] = tabB[(wave + STEP + NW * u) * 16 + j];
+                xn[u] = *(const uint32_t*)(xraw + (uint32_t)min((wave + NW * u) * 16 + j, total - 1) * 16u + 4 * g);
+            }
+            v4i ops[TU][S::KS_B];
+            load_ops(tM, bN, ops);
+            for (int t = wave; t < n_tiles; t += STEP) {
+                int base[TU];
+                uint32_t xr[TU];
+                v4i acc[TU];
+#pragma unroll
+                for (int u = 0; u < TU; ++u) { base[u] = bN[u]; xr[u] = xn[u]; acc[u] = biB; }
 #pragma unroll
                 for (int st = 0; st < S::KS_B; ++st)
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st], ops[u][st], acc[u], 0, 0, 0);
-                bN[0] = bNN[0]; bN[1] = bNN[1];
-                bNN[0] = tabB[(t + 16) * 16 + j];
-                bNN[1] = tabB[(t + 20) * 16 + j];
+                    for (int u = 0; u < TU; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wB[st], ops[u][st], acc[u], 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < TU; ++u) { bN[u] = bNN[u]; bNN[u] = tabB[(t + 2 * STEP + NW * u) * 16 + j]; }
                 load_ops(tM, bN, ops);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) xn[u] = *(const uint32_t*)(xraw + (uint32_t)min((t + 8 + 4 * u) * 16 + j, total - 1) * 16u + 4 * g);
+                for (int u = 0; u < TU; ++u) xn[u] = *(const uint32_t*)(xraw + (uint32_t)min((t + STEP + NW * u) * 16 + j, total - 1) * 16u + 4 * g);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int col = (t + 4 * u) * 16 + j;
+                for (int u = 0; u < TU; ++u) {
+                    const int col = (t + NW * u) * 16 + j;
                     int q[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -460,9 +481,9 @@ __global__ __launch_bounds__(ST_THREADS, MINB) void stack_kernel(const StackPara
 
 // the five convolutions of a stack as the planner laid them out: c = stack convolution (with its fused pool),
 // a1 / b1 and a2 / b2 = the two blocks
-template <bool U8, int CI, int HIN, int C, int G>
+template <bool U8, int CI, int HIN, int C, int G, int NW>
 bool st_shape_ok(const ConvParams& c, const ConvParams& a1, const ConvParams& b1, const ConvParams& a2, const ConvParams& b2) {
-    typedef StShape<U8, CI, HIN, C, G> S;
+    typedef StShape<U8, CI, HIN, C, G, NW> S;
     if (c.H != HIN || c.W != HIN || c.Cs_in != CI || c.Cin_real != CI || c.Ho != HIN || c.Wo != HIN / S::P || c.Cs_out != 16) return false;
     if (c.k != 3 || c.s != 1 || c.pad != 1 || c.sx != S::P || c.cpr != S::CPR_C || c.k_steps != S::KS_C) return false;
     if ((c.src_u8 != 0) != U8 || !c.pool || c.PH != S::H || c.PW != S::H || c.relu || c.relu_in || c.out_frag) return false;
@@ -474,16 +495,16 @@ bool st_shape_ok(const ConvParams& c, const ConvParams& a1, const ConvParams& b1
     return a1.relu_in && a1.relu && !b1.relu_in && !b1.relu && a2.relu_in && a2.relu && !b2.relu_in && !b2.relu;
 }
 
-template <bool U8, int CI, int HIN, int C, int G, int MINB, bool P23>
+template <bool U8, int CI, int HIN, int C, int G, int NW, int MINB, bool P23>
 hipError_t st_go(const StackParams& p, hipStream_t s) {
-    typedef StShape<U8, CI, HIN, C, G> S;
-    auto kfn = stack_kernel<U8, CI, HIN, C, G, MINB, P23>;
+    typedef StShape<U8, CI, HIN, C, G, NW> S;
+    auto kfn = stack_kernel<U8, CI, HIN, C, G, NW, MINB, P23>;
     static int occ = 0;
     if (!occ) {
         hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
         if (e != hipSuccess) return e;
         int o = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)kfn, ST_THREADS, S::LDS);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, (const void*)kfn, S::ST_THREADS, S::LDS);
         if (e != hipSuccess) return e;
         occ = o < 1 ? 1 : o;
     }
@@ -492,17 +513,21 @@ hipError_t st_go(const StackParams& p, hipStream_t s) {
     const int64_t cap = (int64_t)occ * conv_num_cus();
     const int64_t rounds = (batches + cap - 1) / cap;
     dim3 grid((unsigned)((batches + rounds - 1) / rounds));
-    kfn<<<grid, dim3(ST_THREADS), S::LDS, s>>>(p);
+    kfn<<<grid, dim3(S::ST_THREADS), S::LDS, s>>>(p);
     return hipGetLastError();
 }
 
 }  // namespace
 
-#define ACCERL_STACK_SHAPES(X) X(true, 4, 84, 8, 1, 2) X(false, 8, 42, 16, 1, 3) X(false, 16, 21, 16, 2, 3)
+// (uint8 source, stored input channels, input size, channels, images per batch, wavefronts per workgroup, wavefronts per
+// SIMD the register budget is set for).  Stack 1 is held to two workgroups per CU by its LDS: eight wavefronts per
+// workgroup at 128 registers give its SIMDs four wavefronts each (504 -> 453 us at 16384 states); stacks 2 and 3, bound by
+// LDS traffic rather than by issue, gain nothing from that and keep four-wavefront workgroups, three to a CU.
+#define ACCERL_STACK_SHAPES(X) X(true, 4, 84, 8, 1, 8, 4) X(false, 8, 42, 16, 1, 4, 3) X(false, 16, 21, 16, 2, 4, 3)
 
 bool stack_supported(const ConvParams& c, int NTC, const ConvParams& a1, const ConvParams& b1, const ConvParams& a2, const ConvParams& b2) {
     if (NTC != 1) return false;
-#define X(U8, CI, HIN, C, G, MINB) if (st_shape_ok<U8, CI, HIN, C, G>(c, a1, b1, a2, b2)) return true;
+#define X(U8, CI, HIN, C, G, NW, MINB) if (st_shape_ok<U8, CI, HIN, C, G, NW>(c, a1, b1, a2, b2)) return true;
     ACCERL_STACK_SHAPES(X)
 #undef X
     return false;
@@ -517,9 +542,9 @@ hipError_t launch_stack(const ConvParams& c, const ConvParams& a1, const ConvPar
     p.r1 = b1.r; p.r2 = b2.r; p.B = c.B;
     static const bool no_p23 = getenv("ACCERL_NO_P23") != nullptr;
     const bool p23 = a1.pos23 && a2.pos23 && !no_p23;
-#define X(U8, CI, HIN, C, G, MINB)                                                                  \
-    if (st_shape_ok<U8, CI, HIN, C, G>(c, a1, b1, a2, b2))                                          \
-        return p23 ? st_go<U8, CI, HIN, C, G, MINB, true>(p, s) : st_go<U8, CI, HIN, C, G, MINB, false>(p, s);
+#define X(U8, CI, HIN, C, G, NW, MINB)                                                              \
+    if (st_shape_ok<U8, CI, HIN, C, G, NW>(c, a1, b1, a2, b2))                                      \
+        return p23 ? st_go<U8, CI, HIN, C, G, NW, MINB, true>(p, s) : st_go<U8, CI, HIN, C, G, NW, MINB, false>(p, s);
     ACCERL_STACK_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;
