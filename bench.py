@@ -88,6 +88,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="only the headline workload")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the table of all five configurations")
     ap.add_argument("--paper-nets", action="store_true",
                     help="also time the paper's own networks (network table: Original with FC 2048, Net1-Net3)")
     ap.add_argument("--ceilings", action="store_true",
@@ -337,6 +338,49 @@ def main():
                                              frac_hbm_peak=round(kl_bytes / t_kl / PEAK["hbm"], 4))
             extra["vtrace" + tag] = dict(T=Tn, B=B, actions=nA, us=round(t_vt * 1e6, 2), gbps=round(vt_bytes / t_vt / 1e9, 1),
                                          frac_hbm_peak=round(vt_bytes / t_vt / PEAK["hbm"], 4))
+
+    if not args.no_extra and not args.no_per_config:
+        # every configuration at its largest configured batch: student and teacher time per forward and their ratio
+        # (the student / teacher speedup the paper reports for its compressed actors), with the share of the int8 MFMA
+        # peak (useful operations) and of the HBM peak (observations + outputs) that the student reaches
+        per = {}
+        frames = None
+        for cj, cfg_j in wl.CONFIGS.items():
+            ntj, nsj = cfg_j["teacher"], cfg_j["student"]
+            Bj = cfg_j["batches"][-1]
+            ptj = wl.init_params(ntj, wl.STREAM["weights_teacher"])
+            if cfg_j["student_from"] == "quantize":
+                psj = ptj
+            elif cfg_j["student_from"] == "independent":
+                psj = wl.init_params(nsj, wl.STREAM["weights_student"])
+            else:
+                psj, _ = oracle.prune_policy(ntj, ptj, nsj)
+            qpj = oracle.quantize_policy(nsj, psj, states(nsj, cfg_j["calib"], wl.STREAM["calibration"]))
+            stu_j = A.Policy(nsj, "int8", qpj.tensors, qpj.act_scales)
+            tea_j = A.Policy(ntj, cfg_j["teacher_precision"], teacher_tensors(ptj))
+            if nsj.obs_dtype == "u8":
+                if frames is None or frames.shape[0] < Bj:
+                    frames = torch.from_numpy(states(nsj, max(Bj, 16384), wl.STREAM["states"])).cuda()
+                xj = frames[:Bj].contiguous()
+            else:
+                xj = torch.from_numpy(states(nsj, Bj, wl.STREAM["states"])).cuda()
+            uj = torch.from_numpy(wl.make_uniforms(Bj)).cuda()
+            kwj = {}
+            if stu_j.recurrent:
+                hj, cj2 = wl.make_hc(Bj, 256)
+                kwj = dict(done=torch.from_numpy(wl.make_done(1, Bj)[0]).cuda(), h=torch.from_numpy(hj).cuda(), c=torch.from_numpy(cj2).cuda())
+            n_s = 400 if Bj * sum(layer_macs(nsj, None).values()) < 1e11 else 60
+            ts = time_forward(stu_j, xj, uj, stu_j.alloc_outputs(Bj), n_s, max(5, n_s // 10), **kwj)
+            tt = time_forward(tea_j, xj, uj, tea_j.alloc_outputs(Bj), max(5, n_s // 8), 3, **kwj)
+            mj = sum(layer_macs(nsj, None).values())
+            per[f"config{cj}_{cfg_j['name']}"] = dict(
+                B=Bj, student_us=round(ts * 1e6, 2), teacher_us=round(tt * 1e6, 2), teacher_precision=cfg_j["teacher_precision"],
+                student_states_per_s=round(Bj / ts, 1), student_over_teacher=round(tt / ts, 2),
+                frac_int8_peak=round(2 * mj * Bj / ts / PEAK["int8"], 4), frac_hbm_peak=round(io_bytes(nsj) * Bj / ts / PEAK["hbm"], 4))
+            stu_j.close()
+            tea_j.close()
+        del frames
+        extra["per_config"] = per
 
     if args.ceilings:
         def span(fn, n=60):
