@@ -377,6 +377,25 @@ def main():
                 B=Bj, student_us=round(ts * 1e6, 2), teacher_us=round(tt * 1e6, 2), teacher_precision=cfg_j["teacher_precision"],
                 student_states_per_s=round(Bj / ts, 1), student_over_teacher=round(tt / ts, 2),
                 frac_int8_peak=round(2 * mj * Bj / ts / PEAK["int8"], 4), frac_hbm_peak=round(io_bytes(nsj) * Bj / ts / PEAK["hbm"], 4))
+            if stu_j.recurrent and "unroll" in cfg_j:
+                # the configured unroll as an actor runs it: one call per environment step, the state carried in place
+                # (the observations of all steps are resident, as the workload states; done flags ~ Bernoulli(0.01))
+                Tn = cfg_j["unroll"]
+                dn = torch.from_numpy(wl.make_done(Tn, Bj)).cuda()
+                outs_j = stu_j.alloc_outputs(Bj)
+                def unroll():
+                    for t in range(Tn):
+                        stu_j.forward(xj, uj, outputs=outs_j, done=dn[t], h=kwj["h"], c=kwj["c"])
+                for _ in range(3):
+                    unroll()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(10):
+                    unroll()
+                torch.cuda.synchronize()
+                tu = (time.perf_counter() - t0) / 10
+                per[f"config{cj}_{cfg_j['name']}"].update(unroll_steps=Tn, unroll_ms=round(tu * 1e3, 3),
+                                                          unroll_state_steps_per_s=round(Tn * Bj / tu, 1))
             stu_j.close()
             tea_j.close()
         del frames
