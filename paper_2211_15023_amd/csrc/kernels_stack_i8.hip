@@ -58,7 +58,7 @@ struct StShape {
     static constexpr int G = G_;
     static constexpr int NW = NW_;                            // wavefronts per workgroup
     static constexpr int ST_THREADS = NW * 64;
-    static constexpr int TU = NW >= 8 ? 1 : 2;                // block column tiles per wavefront and step
+    static constexpr int TU = (NW >= 8 || C == 16) ? 1 : 2;   // block column tiles per wavefront and step (two only where registers allow)
     static constexpr int P = 16 / C;                          // output pixels per MFMA column (2 for 8 channels)
     // input tile: one pixel of border on every side
     static constexpr int PITCH_IN = st_up16((HIN + 2) * CI);
@@ -70,7 +70,11 @@ struct StShape {
     static constexpr int IMG_IN = U8 ? 4 * HIN * HIN : HIN * HIN * CI;
     static constexpr int PF = (G * UNITS_IN + ST_THREADS - 1) / ST_THREADS;
     static constexpr int RD_E = ((2 * CI) % 16 == 0) ? 16 : 8;  // alignment of the E windows (byte offset 2 px CI)
-    static constexpr int RD_O = (CI % 16 == 0) ? 16 : 8;        // O windows start one pixel further
+    // 16-channel layers: E (x = 2px) and O (x = 2px+1) windows together span the bordered pixels 2px .. 2px+3, which are
+    // whole aligned 16-byte chunks; the kernel reads CPRK chunks per kernel row once and multiplies them with two
+    // weight sets, the planner's (E) and the same shifted by one pixel (O): no second, misaligned read for O
+    static constexpr int CPRK = 4 * CI / 16;                    // chunks per kernel row as read (2 or 4)
+    static constexpr int KSK = (3 * CPRK + 3) / 4;              // MFMA steps over those chunks
     // pooled stream
     static constexpr int H = (HIN - 1) / 2 + 1;
     static constexpr int SLOTS = H * (H + 1);                  // per image: a dummy slot in front of every pooled row
@@ -101,6 +105,7 @@ struct StShape {
     static_assert(H % P == 0 && IMG == NPX * 16 && (U8 ? (HIN % 4 == 0 && CI == 4) : (HIN * CI) % 16 == 0), "shape");
     static_assert(G * TILE_IN + 64 < 65536 && G * TILE_B < 32768 && G * SLOTS < (1 << 20) && COLS < (1 << 20), "offsets");
     static_assert(P == 1 || (G == 1 && KS_C == 1 && H % 2 == 0 && HIN % 2 == 0), "8-channel layers: one image, one MFMA step, even sizes");
+    static_assert(P == 2 || (KSK == KS_C && (CI == 8 || CI == 16)), "16-channel layers: 8 or 16 stored input channels");
 };
 
 // max(v, v of the lane to its left in the same 16-lane row) for the lanes of rows `ROWS` (a 4-bit mask over the four
@@ -134,13 +139,34 @@ __global__ __launch_bounds__(NW * 64, MINB) void stack_kernel(const StackParams 
     const int j = lane & 15, g = lane >> 4;
 
     // ---- weights of all five convolutions and the chunk offsets of this lane
-    v4i wC[S::KS_C], wA1[S::KS_B], wB1[S::KS_B], wA2[S::KS_B], wB2[S::KS_B];
+    v4i wC[S::KS_C], wO[S::P == 1 ? S::KS_C : 1], wA1[S::KS_B], wB1[S::KS_B], wA2[S::KS_B], wB2[S::KS_B];
     int koffC[S::KS_C], koffB[S::KS_B];
+    if constexpr (S::P == 2) {
 #pragma unroll
-    for (int st = 0; st < S::KS_C; ++st) {
-        const int q = 4 * st + g, ky = q / S::CPR_C, cx = q - ky * S::CPR_C;
-        koffC[st] = (ky < 3) ? ky * S::PITCH_IN + cx * 16 : 0;
-        wC[st] = p.w[0][st * 64 + lane];
+        for (int st = 0; st < S::KS_C; ++st) {
+            const int q = 4 * st + g, ky = q / S::CPR_C, cx = q - ky * S::CPR_C;
+            koffC[st] = (ky < 3) ? ky * S::PITCH_IN + cx * 16 : 0;
+            wC[st] = p.w[0][st * 64 + lane];
+        }
+    } else {
+        // chunk (ky, cx) of the planner's fragments (CPR_C chunks per kernel row), zero outside the kernel
+        auto host_chunk = [&](int ky, int cx) -> v4i {
+            if (ky >= 3 || cx < 0 || cx >= S::CPR_C) return (v4i){0, 0, 0, 0};
+            const int qh = ky * S::CPR_C + cx;
+            return p.w[0][(qh >> 2) * 64 + 16 * (qh & 3) + (lane & 15)];
+        };
+#pragma unroll
+        for (int st = 0; st < S::KS_C; ++st) {
+            const int q = 4 * st + g, ky = q / S::CPRK, cx = q - ky * S::CPRK;
+            koffC[st] = (ky < 3) ? ky * S::PITCH_IN + cx * 16 : 0;
+            wC[st] = host_chunk(ky, cx);
+            if constexpr (CI == 16) {
+                wO[st] = host_chunk(ky, cx - 1);                 // a pixel is a whole chunk
+            } else {
+                const v4i prev = host_chunk(ky, cx - 1), own = host_chunk(ky, cx);   // a chunk is two pixels
+                wO[st] = (v4i){prev[2], prev[3], own[0], own[1]};
+            }
+        }
     }
 #pragma unroll
     for (int st = 0; st < S::KS_B; ++st) {
@@ -263,7 +289,6 @@ __global__ __launch_bounds__(NW * 64, MINB) void stack_kernel(const StackParams 
     for (; batch < n_batch; batch += gridDim.x) {
         commit(batch);
         __syncthreads();
-        if (batch + gridDim.x < n_batch) prefetch(batch + gridDim.x);
         const int64_t b0 = batch * G;
         const int gc = (int)((p.B - b0 < G) ? (p.B - b0) : G);
 
@@ -344,7 +369,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void stack_kernel(const StackParams 
                     const uint32_t ex = (uint32_t)e[0], ey = (uint32_t)e[1];
                     const int a0 = (int)(ex & (ODD ? 0xfffeu : 0xffffu)), a1 = (int)((ex >> 16) & (ODD ? 0xfffeu : 0xffffu));
                     const int d2 = (ODD && (ex & 1u)) ? 0 : S::PITCH_IN;            // no row below: repeat the middle one
-                    const int dO = (ODD && ((ex >> 16) & 1u)) ? 0 : CI;             // no column to the right: repeat E
+                    const bool no_right = ODD && ((ex >> 16) & 1u);                 // no column to the right: O repeats E
                     v4i acc[2][3];
 #pragma unroll
                     for (int eo = 0; eo < 2; ++eo)
@@ -357,15 +382,17 @@ __global__ __launch_bounds__(NW * 64, MINB) void stack_kernel(const StackParams 
                         const char* wr[3] = {w0, w1, w1 + d2};
 #pragma unroll
                         for (int k = 0; k < 3; ++k) {
-                            acc[0][k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[st], read_chunk<S::RD_E>(wr[k]), acc[0][k], 0, 0, 0);
-                            acc[1][k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[st], read_chunk<S::RD_O>(wr[k] + dO), acc[1][k], 0, 0, 0);
+                            const v4i b = *(const v4i*)wr[k];      // one aligned read serves the E and the O window
+                            acc[0][k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wC[st], b, acc[0][k], 0, 0, 0);
+                            acc[1][k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wO[st], b, acc[1][k], 0, 0, 0);
                         }
                     }
                     v4i pooled;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int ve = max(max(acc[0][0][r], acc[0][1][r]), acc[0][2][r]);
-                        const int vo = max(max(acc[1][0][r], acc[1][1][r]), acc[1][2][r]);
+                        int vo = max(max(acc[1][0][r], acc[1][1][r]), acc[1][2][r]);
+                        if (no_right) vo = ve;
                         pooled[r] = max(ve, max_with_left<0xF>(vo));
                     }
                     finish(pooled, (int)(ey & 0x7fffu) + 4 * g, (int)(ey >> 16) + 4 * g, s < n_slots && j >= 1 && !(ey & 0x8000u));
@@ -473,6 +500,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void stack_kernel(const StackParams 
         __syncthreads();
         conv_a(wA2, 3);
         __syncthreads();
+        // the next batch's bytes are requested here, not earlier: their registers are then free during the phases above
+        // (where the kernel needs the most), and the last phase is long enough for the loads to land
+        if (batch + gridDim.x < n_batch) prefetch(batch + gridDim.x);
         conv_b(wB2, 4, p.r2, std::true_type{});
         // no barrier here: the next commit writes the input tiles only, and the barrier behind it comes before the
         // next batch writes anything that the last phase reads
