@@ -91,3 +91,45 @@ def test_bf16_within_tolerance(A, name):
     check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 2e-2)
     check_sampler_self_consistency(action.cpu().numpy(), logits.cpu().numpy(), u)
     pol.close()
+
+
+def _mlps():
+    d = wl.dense
+    return {
+        # 40 features: the first layer on the K = 64 MFMA (16 features per lane); 6 actions: sampler in registers
+        "wide_obs": Net("wide_obs", "f32", (40,), 6, [d(40, 48, True), d(48, 64, True)]),
+        # 20 actions: two head tiles, logits staged in LDS and scanned by one lane per state
+        "many_actions": Net("many_actions", "f32", (24,), 20, [d(24, 64, True)]),
+        # 7 features (rows are not whole 16-byte groups: scalar observation loads), a hidden layer without ReLU
+        # (signed requantization, first-layer layout chosen at run time), 3 actions
+        "odd_obs_no_relu": Net("odd_obs_no_relu", "f32", (7,), 3, [d(7, 32, True), d(32, 16, False)]),
+        # three hidden layers, 64 features, the most actions the register sampler takes
+        "deep_15": Net("deep_15", "f32", (64,), 15, [d(64, 64, True), d(64, 64, True), d(64, 64, True)]),
+    }
+
+
+@pytest.mark.parametrize("name", ["wide_obs", "many_actions", "odd_obs_no_relu", "deep_15"])
+@pytest.mark.parametrize("B", [1, 333])
+def test_mlp_variants_bit_exact_with_taps(A, name, B):
+    """The fused MLP kernel's variants beyond the two benchmark networks, accumulators and activations bit-exact."""
+    net = _mlps()[name]
+    params = wl.init_params(net, wl.STREAM["weights_student"])
+    qp = oracle.quantize_policy(net, params, make_states(net, 256, wl.STREAM["calibration"]))
+    pol = A.Policy(net, "int8", qp.tensors, qp.act_scales)
+    x = make_states(net, B, wl.STREAM["states"])
+    u = wl.make_uniforms(B)
+    print(f"{name} int8 B={B}", flush=True)
+    otaps = {}
+    ref = oracle.forward_int8(net, qp, x, u, taps=otaps)
+    dx = _dev(x)
+    logits, value, action = pol.forward(dx, _dev(u))
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), ref["logits"])
+    assert np.array_equal(value.cpu().numpy(), ref["value"])
+    check_actions(action.cpu().numpy(), ref["action"], ref["logits"], u, 1e-5)
+    for (layer, tag), arr in otaps.items():
+        layer_i = len(net.layers) if layer == "heads" else layer
+        kind = A.TAP_ACC if tag == "acc" or layer == "heads" else A.TAP_ACT
+        got = pol.tap(dx, layer_i, kind, arr.shape, torch.int32 if arr.dtype == np.int32 else torch.int8).cpu().numpy()
+        assert np.array_equal(got, arr), (name, layer, tag, int((got != arr).sum()))
+    pol.close()
