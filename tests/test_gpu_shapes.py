@@ -39,13 +39,16 @@ def _nets():
         "bands": Net("bands", "u8", (2, 120, 16), 4, [
             conv(2, 16, 3, 1, 1, True), maxpool(3, 2, 1), conv(16, 20, 3, 1, 1, False), maxpool(3, 2, 1),
             relu(), flatten(), dense(20 * 30 * 4, 33, True)]),
+        # 40 actions: three head tiles, the heads kernel stages its logits in LDS and scans them with one lane per state
+        "many_actions": Net("many_actions", "u8", (4, 20, 20), 40, [
+            conv(4, 16, 4, 2, 0, True), flatten(), dense(16 * 9 * 9, 64, True)]),
         # the fused first-two-convolutions kernel with one channel tile in the first layer
         "fused16": Net("fused16", "u8", (4, 60, 60), 6, [
             conv(4, 16, 8, 4, 0, True), conv(16, 64, 4, 2, 0, True), flatten(), dense(64 * 6 * 6, 24, False)]),
     }
 
 
-@pytest.mark.parametrize("name", ["thin_pool_res", "pack4", "bands", "fused16"])
+@pytest.mark.parametrize("name", ["thin_pool_res", "pack4", "bands", "fused16", "many_actions"])
 @pytest.mark.parametrize("B", [5, 67])
 def test_int8_bit_exact_with_taps(A, name, B):
     net = _nets()[name]
@@ -74,7 +77,7 @@ def test_int8_bit_exact_with_taps(A, name, B):
     pol.close()
 
 
-@pytest.mark.parametrize("name", ["thin_pool_res", "pack4", "bands", "fused16"])
+@pytest.mark.parametrize("name", ["thin_pool_res", "pack4", "bands", "fused16", "many_actions"])
 def test_bf16_within_tolerance(A, name):
     net = _nets()[name]
     B = 19
