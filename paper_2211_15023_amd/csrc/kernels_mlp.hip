@@ -235,6 +235,36 @@ __global__ __launch_bounds__(MLP_WAVES * 64, NH <= 2 ? 3 : 2) void mlp_i8_kernel
                     if (p.tap_layer == NH && p.tap_acc && live && n <= A) p.tap_acc[row * (A + 1) + n] = acc[r];
                 }
             }
+            if (A <= 4) {
+                // all logits of a state sit in its first lane (group 0, outputs 0 .. 3): maximum, normaliser and scan are
+                // plain in-lane arithmetic there, no exchange between the lane groups (the other groups compute along)
+                float cum[4], run = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    run += (r < A) ? __builtin_amdgcn_exp2f((o[r] - m) * 1.44269504088896341f) : 0.0f;
+                    cum[r] = run;
+                }
+                if (p.logits && live && g == 0) {
+                    float* dst = p.logits + row * A;
+                    if (A == 4) *(v4f*)dst = (v4f){o[0], o[1], o[2], o[3]};
+                    else {
+#pragma unroll
+                        for (int r = 0; r < 3; ++r)
+                            if (r < A) dst[r] = o[r];
+                    }
+                }
+                if (p.action && live) {
+                    const float thr = u_cur * run;
+                    int cnt = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) cnt += (r < A && !(cum[r] > thr)) ? 1 : 0;
+                    if (g == 0) p.action[row] = min(cnt, A - 1);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (4 * g + r == A) p.value[row] = o[r];
+                }
+                continue;
+            }
             auto pair16 = [](unsigned v) { return __builtin_amdgcn_permlane16_swap(v, v, false, false); };   // {even row, odd row} of the lane's row pair
             auto pair32 = [](unsigned v) { return __builtin_amdgcn_permlane32_swap(v, v, false, false); };   // {lower half, upper half}
             {
