@@ -17,7 +17,9 @@
 //    value from outside its window.  Rows and columns outside the image are replaced by their nearest neighbour
 //    inside, which is part of the same window, so no -infinity is needed.
 //    16-channel layers: columns are "slots", the pooled pixels of the batch in raster order with the dummy in front
-//    of every row; E and O are separate MFMAs; one 8-byte table entry per slot gives the window addresses.
+//    of every row; one 8-byte table entry per slot gives the window addresses.  E and O are separate MFMAs on the
+//    same LDS reads: their windows together are the bordered pixels 2px .. 2px+3, whole aligned 16-byte chunks, which
+//    are multiplied with the planner's weight fragments (E) and with the same fragments shifted by one pixel (O).
 //    8-channel layers put E and O into the two halves of the 16 MFMA rows (the pixel packing of the layer-by-layer
 //    kernel: same weight fragments): E then sits in lanes 0-31 and O in lanes 32-63.  A tile is 15 pixels of one
 //    pooled row; two vertically adjacent pooled rows are processed together (they share a conv row: five MFMAs for
@@ -27,7 +29,7 @@
 //  * the pooled stream is written twice into LDS: max(x, 0) into a zero-bordered tile (the first block's conv A reads
 //    it) and x itself into a plain image (the skip connection).  The blocks run as in the single-block kernel, from
 //    LDS to LDS; the first block's output replaces the plain image in place, the second block's goes to memory.
-//  * the next batch's input bytes are requested before the current batch is computed.
+//  * the next batch's input bytes are requested at the start of the current batch's last phase and land while it runs.
 //
 // Arithmetic, fragments and constants are those of the layer-by-layer kernels (conv_kernel.h), so results are
 // bit-identical; the debug taps still run that path.  Network: the benchmark's IMPALA configuration (three such stacks).
@@ -78,8 +80,6 @@ struct StShape {
     // pooled stream
     static constexpr int H = (HIN - 1) / 2 + 1;
     static constexpr int SLOTS = H * (H + 1);                  // per image: a dummy slot in front of every pooled row
-    static constexpr int NU = (P == 2) ? 2 : 1;                // slot tiles per iteration
-    static constexpr int NE = (P == 2) ? 1 : 2;                // windows per slot: (E and O in one MFMA) or (E, O)
     // residual blocks
     static constexpr int WP = H / P;                           // columns per image row
     static constexpr int NPX = H * WP;                         // columns = 16-byte units per image
