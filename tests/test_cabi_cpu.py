@@ -168,12 +168,15 @@ def test_planner_decisions_on_the_benchmark_networks(A):
     # every residual block of the student is one launch: its first convolution carries the second
     assert [c["resblock"] for c in convs] == ["0", "1", "0", "1", "0", "0", "1", "0", "1", "0", "0", "1", "0", "1", "0"]
     assert [c["fuse_next"] for c in convs] == [c["resblock"] for c in convs]
+    # and every stack (conv + pool + two blocks) is one launch: the stack convolution heads it, the four block
+    # convolutions behind it are its members; 5 launches remain (three stacks, the dense layer, the heads)
+    assert [c["stack"] for c in convs] == ["1", "2", "2", "2", "2"] * 3
     # the stack convolutions have no ReLU before their max-pool, so the offset accumulators are not for them
     assert [c["pos23"] for c in convs][0] == "0" and convs[1]["pos23"] == "1"
     # the teacher's wider layers are not packed
     tsteps = [l for l in _plan(A, nt, "bf16", [dict(w=w, b=b) for _, w, b in pt]).splitlines() if l.startswith("step")]
     assert _fields([l for l in tsteps if " conv " in l][0])["out"] == "84x84x16"
-    assert all(_fields(l)["resblock"] == "0" for l in tsteps if " conv " in l)   # bf16 blocks run layer by layer
+    assert all(_fields(l)["resblock"] == "0" and _fields(l)["stack"] == "0" for l in tsteps if " conv " in l)   # bf16 blocks run layer by layer
 
 
 def test_workspace_slots_are_shared(A):
@@ -184,3 +187,6 @@ def test_workspace_slots_are_shared(A):
     shapes = wl.trace_shapes(ns)
     naive = sum(int(np.prod(s)) for s in shapes if len(s) == 3)    # one buffer per image-shaped layer output
     assert per_state < naive / 3
+    # with whole stacks fused only the stack outputs and the dense layer's output need workspace, and the third stack's
+    # and the dense layer's share the slot the first stack's output has left
+    assert per_state == 42 * 42 * 8 + 21 * 21 * 16
