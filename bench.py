@@ -377,6 +377,13 @@ def main():
                 B=Bj, student_us=round(ts * 1e6, 2), teacher_us=round(tt * 1e6, 2), teacher_precision=cfg_j["teacher_precision"],
                 student_states_per_s=round(Bj / ts, 1), student_over_teacher=round(tt / ts, 2),
                 frac_int8_peak=round(2 * mj * Bj / ts / PEAK["int8"], 4), frac_hbm_peak=round(io_bytes(nsj) * Bj / ts / PEAK["hbm"], 4))
+            # the student's latency at every configured batch of this configuration
+            by_b = {}
+            for bb in cfg_j["batches"]:
+                kwb = {k: v[:bb].contiguous() for k, v in kwj.items()}
+                tb = time_forward(stu_j, xj[:bb].contiguous(), uj[:bb].contiguous(), stu_j.alloc_outputs(bb), 300 if bb <= 1024 else n_s, 30, **kwb)
+                by_b[str(bb)] = round(tb * 1e6, 2)
+            per[f"config{cj}_{cfg_j['name']}"]["student_us_by_batch"] = by_b
             if stu_j.recurrent and "unroll" in cfg_j:
                 # the configured unroll as an actor runs it: one call per environment step, the state carried in place
                 # (the observations of all steps are resident, as the workload states; done flags ~ Bernoulli(0.01))
